@@ -1,0 +1,37 @@
+"""The four stages chained per frame, as one application stream (paper Section III-A:
+frame -> format conversion -> recurrent inference -> postprocess -> overlay on the
+original frame)."""
+from __future__ import annotations
+
+import numpy as np
+
+from .resize import preprocess
+from .convnet import Tiny4Net, ResNet18ConvLSTMNet
+from .postprocess import postprocess
+from .overlay import overlay
+
+
+class OracleApp:
+    def __init__(self, net: str, blob: np.ndarray, net_w: int, net_h: int, fp16_input: bool,
+                 palette: np.ndarray, mean: float = 0.5, std: float = 0.25,
+                 threshold: float = 0.5, alpha: float = 0.5, storage: str = "fp32"):
+        self.net = {"tiny4": Tiny4Net, "resnet18_convlstm": ResNet18ConvLSTMNet}[net](
+            blob, storage)
+        self.net_w, self.net_h, self.fp16_input = net_w, net_h, fp16_input
+        self.mean, self.std, self.threshold, self.alpha = mean, std, threshold, alpha
+        self.palette = np.asarray(palette, dtype=np.uint8)
+
+    def reset(self):
+        self.net.reset()
+
+    def process(self, frame: np.ndarray) -> dict:
+        resized, net_in = preprocess(frame, self.net_w, self.net_h, self.mean, self.std,
+                                     self.fp16_input)
+        logits = self.net.forward(net_in)
+        post = postprocess(logits, self.threshold)
+        out = overlay(frame, post["mask"], self.palette, self.alpha)
+        res = {"resized": resized, "net_input": net_in, "logits": logits, "overlay": out}
+        res.update(post)
+        if hasattr(self.net, "h") and self.net.h is not None:
+            res["h"], res["c"] = self.net.h, self.net.c
+        return res

@@ -1,0 +1,191 @@
+"""Pins for the stage-3 (postprocess), stage-4 (overlay) and metrics oracles: closed
+forms, degenerate cases, per-pixel brute force and library witnesses.  The paper gives
+the metric definitions (Section V-A) and the stage order (Section III-A) but no worked
+numeric example of any stage."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import (postprocess, logit_threshold, overlay, alpha_q8, determinism_metrics,
+                    trim_count, OracleApp)
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ postprocess
+def test_threshold_half_is_logit_zero_and_general_value():
+    assert logit_threshold(0.5) == 0.0
+    assert abs(float(logit_threshold(0.75)) - math.log(3.0)) < 1e-6
+    assert logit_threshold(0.25) == -logit_threshold(0.75)
+
+
+def test_constant_map_argmax_is_lowest_index():
+    out = postprocess(np.full((8, 5, 7), 1.5, np.float32), 0.5)
+    assert np.all(out["argmax_idx"] == 0)
+    assert np.all(out["present"] == 1) and np.all(out["mask"] == 1)
+    np.testing.assert_allclose(out["peak"], 1 / (1 + math.exp(-1.5)), rtol=1e-6)
+
+
+def test_signed_zero_tie_goes_to_lower_index():
+    l = np.full((1, 2, 3), -1.0, np.float32)
+    l[0, 0, 2] = -0.0
+    l[0, 1, 1] = 0.0
+    out = postprocess(l, 0.5)
+    assert out["argmax_idx"][0] == 2
+    assert out["present"][0] == 0 and out["mask"].sum() == 0     # 0 > 0 is false (strict)
+    assert out["peak"][0] == 0.5
+
+
+def test_single_spike_and_duplicate_spike():
+    l = np.random.default_rng(0).standard_normal((8, 15, 27)).astype(np.float32)
+    for k in range(8):
+        l[k, (3 * k) % 15, (5 * k + 1) % 27] = 50.0
+    l[5, 14, 26] = 50.0                       # later duplicate of channel 5's maximum
+    out = postprocess(l, 0.5)
+    want = [((3 * k) % 15) * 27 + (5 * k + 1) % 27 for k in range(8)]
+    assert list(out["argmax_idx"]) == want
+    assert np.array_equal(out["argmax_idx"], l.reshape(8, -1).argmax(axis=1))   # numpy: first max
+
+
+def test_all_negative_map_is_empty():
+    l = -np.abs(np.random.default_rng(1).standard_normal((8, 4, 4))).astype(np.float32) - 0.1
+    out = postprocess(l, 0.5)
+    assert out["mask"].sum() == 0 and out["present"].sum() == 0
+    assert np.all(out["peak"] < 0.5)
+
+
+def test_sigmoid_identities_and_mask_consistency():
+    l = np.linspace(-12, 12, 8 * 6 * 6, dtype=np.float32).reshape(8, 6, 6)
+    out = postprocess(l, 0.5)
+    heat = out["heat"].astype(np.float64)
+    assert out["heat"].dtype == np.float32
+    np.testing.assert_allclose(heat + postprocess(-l, 0.5)["heat"], 1.0, atol=1e-7)
+    assert np.all(np.diff(heat.ravel()) >= 0)
+    assert postprocess(np.zeros((1, 1, 1), np.float32), 0.5)["heat"][0, 0, 0] == 0.5
+    clear = np.abs(l) > 1e-3
+    assert np.array_equal(out["mask"][clear], (heat[clear] > 0.5).astype(np.uint8))
+    out3 = postprocess(l, 0.75)
+    clear3 = np.abs(l - math.log(3.0)) > 1e-3
+    assert np.array_equal(out3["mask"][clear3], (heat[clear3] > 0.75).astype(np.uint8))
+
+
+# ------------------------------------------------------------------ overlay
+PAL = si.DEFAULT_PALETTE
+
+
+def _frame(h, w, seed):
+    return np.random.default_rng(seed).integers(0, 256, (h, w, 3), dtype=np.uint8)
+
+
+def _mask(k, h, w, seed, p=0.3):
+    return (np.random.default_rng(seed).random((k, h, w)) < p).astype(np.uint8)
+
+
+def test_alpha_quantisation():
+    assert alpha_q8(0.0) == 0 and alpha_q8(1.0) == 256 and alpha_q8(0.5) == 128
+    assert alpha_q8(-1.0) == 0 and alpha_q8(3.0) == 256
+    assert alpha_q8(0.25) == 64
+
+
+def test_alpha_zero_and_empty_mask_are_identity():
+    f, m = _frame(24, 32, 2), _mask(8, 3, 4, 3)
+    assert np.array_equal(overlay(f, m, PAL, 0.0), f)
+    assert np.array_equal(overlay(f, np.zeros_like(m), PAL, 0.5), f)
+
+
+def test_alpha_one_paints_palette_of_lowest_set_channel():
+    f, m = _frame(24, 32, 4), _mask(8, 3, 4, 5, p=0.4)
+    out = overlay(f, m, PAL, 1.0)
+    for Y in range(24):
+        for X in range(32):
+            cell = m[:, Y * 3 // 24, X * 4 // 32]
+            if cell.any():
+                assert tuple(out[Y, X]) == tuple(PAL[int(np.flatnonzero(cell)[0])])
+            else:
+                assert tuple(out[Y, X]) == tuple(f[Y, X])
+
+
+def test_brute_force_blend_ragged_cells():
+    hf, wf, hm, wm = 19, 23, 4, 5          # cells of unequal pixel size
+    f, m = _frame(hf, wf, 6), _mask(8, hm, wm, 7)
+    out = overlay(f, m, PAL, 0.5)
+    for Y in range(hf):
+        for X in range(wf):
+            cell = m[:, (Y * hm) // hf, (X * wm) // wf]
+            if not cell.any():
+                assert tuple(out[Y, X]) == tuple(f[Y, X])
+                continue
+            k = int(np.flatnonzero(cell)[0])
+            for c in range(3):
+                assert out[Y, X, c] == (128 * int(PAL[k, c]) + 128 * int(f[Y, X, c]) + 128) >> 8
+
+
+def test_changed_pixel_count_equals_cell_areas():
+    hf, wf, hm, wm = 40, 50, 3, 7
+    f = np.zeros((hf, wf, 3), np.uint8)          # black, so every blended pixel changes
+    m = _mask(8, hm, wm, 8)
+    m[:, :, :] &= 1
+    out = overlay(f, m, PAL, 0.5)
+    xs = [sum(1 for X in range(wf) if X * wm // wf == j) for j in range(wm)]
+    ys = [sum(1 for Y in range(hf) if Y * hm // hf == i) for i in range(hm)]
+    assert sum(xs) == wf and sum(ys) == hf
+    want = sum(ys[i] * xs[j] for i in range(hm) for j in range(wm) if m[:, i, j].any())
+    assert int((out != f).any(axis=2).sum()) == want
+
+
+def test_frame_equal_to_colour_is_fixed_point_for_any_alpha():
+    m = np.zeros((8, 2, 2), np.uint8)
+    m[6] = 1
+    f = np.tile(PAL[6][None, None, :], (10, 10, 1))
+    for a in (0.1, 0.37, 0.5, 0.9, 1.0):
+        assert np.array_equal(overlay(f, m, PAL, a), f)
+
+
+# ------------------------------------------------------------------ metrics
+def test_metrics_golden_1_to_101():
+    want = {}
+    with open(os.path.join(GOLDEN, "latency_1_to_101.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                want[k] = float(v)
+    m = determinism_metrics(np.arange(1, 102)[::-1], trim=False)   # order must not matter
+    assert m["n"] == 101 and m["p50"] == want["p50"] and m["max"] == want["max"]
+    assert m["mean"] == want["mean"] and m["tail"] == want["tail"]
+    assert m["flatness"] == want["flatness"]
+    assert abs(m["std"] - want["std"]) < 1e-12
+
+
+def test_metrics_against_numpy_estimators():
+    x = np.random.default_rng(9).gamma(2.0, 3.0, 977)
+    m = determinism_metrics(x, trim=False)
+    assert abs(m["flatness"] - (np.percentile(x, 90) - np.percentile(x, 10))) < 1e-9
+    assert abs(m["tail"] - (x.max() - np.percentile(x, 95))) < 1e-9
+    assert abs(m["p99"] - np.percentile(x, 99)) < 1e-9
+    assert abs(m["std"] - np.std(x)) < 1e-9 and abs(m["mean"] - np.mean(x)) < 1e-9
+
+
+def test_trimming_rule():
+    assert trim_count(1000) == 10 and trim_count(60) == 10 and trim_count(8) == 1
+    x = np.concatenate([[1000.0] * 10, np.arange(40.0), [2000.0] * 10])
+    m = determinism_metrics(x)
+    assert m["n"] == 40 and m["max"] == 39.0
+    assert determinism_metrics([5.0, 1.0, 2.0, 3.0, 4.0, 1.5, 2.5, 9.0])["n"] == 6
+
+
+# ------------------------------------------------------------------ pipeline
+def test_pipeline_stage_order_and_shapes():
+    frames = si.uniform_frames(2, 240, 320, 0)
+    app = OracleApp("tiny4", si.he_normal_blob(si.TINY4_LAYERS, 0), 128, 128, False, PAL)
+    r = app.process(frames[0])
+    assert r["net_input"].shape == (3, 128, 128) and r["logits"].shape == (8, 32, 32)
+    assert r["overlay"].shape == frames[0].shape and r["overlay"].dtype == np.uint8
+    # the overlay is drawn on the ORIGINAL frame: unmasked cells keep the input pixels
+    cell_y = (np.arange(240) * 32) // 240
+    cell_x = (np.arange(320) * 32) // 320
+    untouched = ~r["mask"].any(axis=0)[cell_y][:, cell_x]
+    assert np.array_equal(r["overlay"][untouched], frames[0][untouched])
+    assert (r["overlay"][~untouched] != frames[0][~untouched]).any()
