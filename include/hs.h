@@ -1,0 +1,242 @@
+/*
+ * hs.h -- C ABI of libhs: the per-frame hot path of N concurrent tool-tracking
+ * application streams on one AMD MI355X (gfx950).
+ *
+ * The calls follow the problem statement of "Towards Deterministic End-to-end Latency
+ * for Medical AI Systems in NVIDIA Holoscan" (arXiv 2402.04466):
+ *   - an application is created once; its model is loaded at run time and one stream
+ *     is created for the first operator and reused downstream (Section III-A);
+ *   - it receives video frames one at a time and runs four stages per frame: format
+ *     conversion, recurrent conv-net inference, tool-tracking postprocess, overlay of
+ *     the result on the ORIGINAL frame (Section III-A);
+ *   - every message is time-stamped on arrival at the first stage and on departure
+ *     from the last; end-to-end latency is the difference (Section II-C, Section V-A);
+ *   - each application gets an exclusive compute partition and is refused when its
+ *     request exceeds what is free (Section IV-A "MPS Partition Creation" and
+ *     "Admission Control").  Here the partition is a set of compute units (CUs) bound
+ *     to the application's HIP streams with a CU mask, and the inference stages and
+ *     the overlay stage can be given disjoint CU sets (the one-GPU analogue of the
+ *     compute/graphics isolation of Section IV-B).
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers (HIP global memory of the device given to
+ *     hs_init); all others are host pointers.  No torch types cross this boundary.
+ *   - All device memory is allocated and owned by the caller: the workspace given to
+ *     hs_create_app, the input frames and the overlay outputs.  The library owns its
+ *     HIP streams and events, a few KiB of pinned host memory per application, and
+ *     its host threads.
+ *   - Every call returns an hs_status; nothing throws or aborts across the boundary.
+ *     hs_last_error() returns a thread-local description of the last failure.
+ *   - Threading: one thread at a time may submit to a given application; any thread
+ *     may poll it; different applications may be driven from different threads
+ *     concurrently (the paper runs one process per application, Section V-B).
+ */
+#ifndef HS_H_
+#define HS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hs_ctx hs_ctx; /* one per device, opaque */
+typedef struct hs_app hs_app; /* one per application stream, opaque */
+
+typedef enum {
+  HS_OK = 0,
+  HS_E_INVAL = -1,          /* NULL pointer, bad dimension, weight size mismatch       */
+  HS_E_NOMEM = -2,          /* workspace too small / host allocation failed            */
+  HS_E_OVERSUBSCRIBED = -3, /* admission control refused the partition                 */
+  HS_E_QUEUE_FULL = -4,     /* all queue_depth slots hold unpolled or in-flight frames */
+  HS_E_NOT_READY = -5,      /* no finished frame to deliver yet                        */
+  HS_E_DEVICE = -6,         /* a HIP call failed; see hs_last_error()                  */
+  HS_E_STATE = -7           /* call not allowed now (e.g. frames still in flight)      */
+} hs_status;
+
+typedef enum {
+  /* 3->16 (stride 2) -> 32 (stride 2) -> 32 -> 8, all 3x3 pad 1, ReLU after the first
+   * three layers, linear logits; stateless.  Logit map = net_h/4 x net_w/4.            */
+  HS_NET_TINY4 = 1,
+  /* ResNet-18-style backbone (7x7/2 stem + ReLU, 3x3/2 max-pool, 4 stages x 2 basic
+   * blocks, widths 64/128/256/512, 1x1/2 projection shortcuts, no normalisation, no
+   * bias) + one ConvLSTM cell (512+256 -> 4x256, 3x3, gate order i,f,g,o, state carried
+   * across frames) + 1x1 head 256 -> 8.  Logit map = ceil(net/32) per axis.            */
+  HS_NET_RESNET18_CONVLSTM = 2
+} hs_net_kind;
+
+#define HS_NUM_TOOLS 8      /* output channels of either network = tool classes        */
+#define HS_MAX_CU_WORDS 8   /* CU masks are bit sets of up to 256 CUs, 32 per word      */
+
+/* Application description (read by hs_query_workspace and hs_create_app; copied). */
+typedef struct {
+  int frame_w, frame_h;     /* input video frame, pixels                                */
+  size_t frame_pitch;       /* bytes between frame rows, >= 3*frame_w; rows are RGBRGB.. */
+  int net_w, net_h;         /* size the frame is resized to for the network              */
+  int net_fp32_input;       /* 1: stage 1 also stores the converted tensor as planar fp32 */
+  float mean, std;          /* normalisation: (v/255 - mean) / std                       */
+  float threshold;          /* heat-map threshold in (0,1), compared strictly (>)        */
+  float alpha;              /* overlay opacity in [0,1], quantised to 1/256 steps        */
+  int net;                  /* hs_net_kind                                               */
+  const float* weights;     /* HOST fp32 blob: layers in network order, each             */
+                            /* [Cout][Cin][kh][kw]; copied and repacked to fp16 at create */
+  size_t weight_floats;     /* number of floats in the blob; must match the network      */
+  uint8_t palette[HS_NUM_TOOLS][3]; /* overlay colour per tool channel, RGB              */
+  int queue_depth;          /* frames that may be in flight or unpolled, 1..64           */
+  void* d_workspace;        /* DEVICE memory owned by the caller, 256-byte aligned       */
+  size_t workspace_bytes;   /* >= hs_query_workspace(); plays the role of the per-client  */
+                            /* device-memory limit of the paper's partitions              */
+} hs_app_desc;
+
+/* What stage 3 found for one frame, plus the frame's time stamps. All times are
+ * CLOCK_MONOTONIC nanoseconds. t_submit_ns is taken on entry to hs_submit_frame
+ * (arrival at the first stage). t_overlay_done_ns is taken by the library's completion
+ * thread when the overlay kernel's completion event fires (departure from the last
+ * stage) -- independent of when the caller polls; t_observed_ns is the poll time.
+ * The three intermediate stamps are t_overlay_done_ns minus the GPU-event time between
+ * that stage's end and the overlay's end.  End-to-end latency = t_overlay_done_ns -
+ * t_submit_ns (Section II-C).
+ *
+ * Device pointers alias the application's workspace (slot frame_id % queue_depth ...
+ * strictly: the slot the frame was given) and stay valid until queue_depth further
+ * frames have been submitted to the same application.
+ *   d_net_input     fp16, pixel-interleaved with 4 channels per pixel (R,G,B,0),
+ *                   net_h rows of net_w pixels, row pitch net_input_pitch_bytes
+ *   d_net_input_f32 fp32 planar [3][net_h][net_w], or NULL unless net_fp32_input
+ *   d_logits        fp32 planar [8][map_h][map_w]
+ *   d_heat          fp32 planar [8][map_h][map_w] = sigmoid(logits)
+ *   d_mask          uint8 planar [8][map_h][map_w] in {0,1}
+ *   d_overlay       the caller's d_overlay_out for this frame
+ */
+typedef struct {
+  uint64_t frame_id;
+  uint64_t t_submit_ns, t_pre_done_ns, t_infer_done_ns, t_post_done_ns, t_overlay_done_ns,
+      t_observed_ns;
+  int32_t argmax_idx[HS_NUM_TOOLS]; /* row-major index y*map_w+x of the channel maximum,  */
+                                    /* lowest index among equal maxima                    */
+  uint8_t present[HS_NUM_TOOLS];    /* 1 if the channel maximum exceeds the threshold     */
+  float peak[HS_NUM_TOOLS];         /* sigmoid of the channel maximum                     */
+  int map_w, map_h;
+  size_t net_input_pitch_bytes;
+  const void* d_overlay;
+  const void* d_mask;
+  const void* d_heat;
+  const void* d_logits;
+  const void* d_net_input;
+  const void* d_net_input_f32;
+} hs_result;
+
+/* Latency determinism metrics of Section V-A, in the unit of the input. */
+typedef struct {
+  uint64_t n;      /* samples left after trimming                                        */
+  double mean, max, std; /* std: population standard deviation                           */
+  double p50, p99;
+  double tail;     /* 100th - 95th percentile                                            */
+  double flatness; /* 90th - 10th percentile                                             */
+} hs_latency_metrics;
+
+/* Aggregated kernel timing of one application (see hs_set_kernel_timing). */
+typedef struct {
+  char name[48];      /* kernel family, e.g. "conv_mfma", "resize_norm", "overlay"       */
+  uint64_t launches;  /* launches timed since the last reset                             */
+  double total_ms;    /* sum of HIP-event elapsed time over those launches               */
+  double flops;       /* algorithmic flops of those launches (0 for byte-bound kernels)   */
+  double bytes;       /* algorithmic bytes of those launches (0 for flop-bound kernels)   */
+} hs_kernel_time;
+
+/* ---- context ------------------------------------------------------------------- */
+
+/* Bind a context to HIP device `device` (makes it current for the calling thread).
+ * HS_E_DEVICE if there is no such GPU or it is not a gfx950 part. */
+hs_status hs_init(int device, hs_ctx** out);
+/* Destroys the context. All its applications must have been destroyed (HS_E_STATE). */
+hs_status hs_shutdown(hs_ctx* ctx);
+/* Number of CUs of the context's device (256 on MI355X). */
+hs_status hs_device_cus(hs_ctx* ctx, int* n_cus);
+
+/* ---- application life cycle (Section III-A: model loaded at run time, stream created
+ *      once and reused by the later stages) ---------------------------------------- */
+
+/* Device bytes hs_create_app needs for this description (weights in fp16, activation
+ * and state buffers, queue_depth result slots). Pure host computation. */
+hs_status hs_query_workspace(const hs_app_desc* desc, size_t* bytes);
+/* Validates the description, repacks and uploads the weights into the workspace, zeroes
+ * the recurrent state, creates the application's two HIP streams (inference stages;
+ * overlay stage), its events and its completion thread. Synchronous. The application
+ * starts unpartitioned (all CUs). */
+hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out);
+/* Waits for in-flight frames, stops the completion thread, releases streams, events and
+ * claimed CUs. The workspace returns to the caller. */
+hs_status hs_destroy_app(hs_app* app);
+/* Zero the ConvLSTM state (h, c). HS_E_STATE while frames are in flight. */
+hs_status hs_reset_state(hs_app* app);
+/* Copy the ConvLSTM state of the last completed frame to HOST buffers, as fp32 planar
+ * [256][map_h][map_w] each (either may be NULL). HS_E_STATE while frames are in flight,
+ * HS_E_INVAL for a stateless network. For tests and for checkpointing a stream. */
+hs_status hs_get_state(hs_app* app, float* h_out, float* c_out);
+
+/* ---- spatial partition + admission control (Section IV-A) ------------------------- */
+
+/* Bind the application's inference stream (stages 1-3) and overlay stream (stage 4) to
+ * CU sets. Masks are bit sets, bit i of word i/32 = CU i, n_words <= HS_MAX_CU_WORDS.
+ * The two masks may be equal or disjoint (compute / visualisation isolation).
+ * Admission control: refused with HS_E_OVERSUBSCRIBED, changing nothing, if a mask is
+ * empty, names a CU the device does not have, or intersects CUs claimed by another
+ * application of the context. Passing NULL for both masks releases the claim and
+ * returns the application to the unpartitioned state (all CUs, claims nothing).
+ * HS_E_STATE while frames are in flight. */
+hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
+                           const uint32_t* cu_mask_overlay, int n_words);
+/* The admission predicate alone, on host data (no GPU needed): would a request for
+ * req_infer | req_overlay be admitted given the CUs already claimed by others?
+ * Returns HS_OK or HS_E_OVERSUBSCRIBED / HS_E_INVAL exactly as hs_set_partition would. */
+hs_status hs_admission_check(const uint32_t* claimed_by_others, const uint32_t* req_infer,
+                             const uint32_t* req_overlay, int n_words, int device_cus);
+
+/* ---- per-frame hot path (Section III-A) ------------------------------------------- */
+
+/* Enqueue the four stages for one frame and return without waiting.
+ *   d_frame       device, frame_h rows of frame_pitch bytes, RGB uint8; read by stage 1
+ *                 and again by stage 4; must stay untouched until the result is polled
+ *   d_overlay_out device, same shape and pitch as d_frame; written by stage 4; must not
+ *                 alias d_frame
+ * Frames of one application are processed strictly in submit order (the recurrent
+ * state of frame t feeds frame t+1). HS_E_QUEUE_FULL (frame NOT enqueued) when
+ * queue_depth frames are in flight or unpolled. */
+hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
+                          uint64_t frame_id);
+/* Deliver the oldest finished, not yet delivered frame (submit order). Non-blocking:
+ * HS_E_NOT_READY if none has finished. Frees that frame's queue slot. */
+hs_status hs_poll_result(hs_app* app, hs_result* out);
+/* As hs_poll_result, but sleeps until a frame has finished or timeout_ns elapsed
+ * (HS_E_NOT_READY on time-out). */
+hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns);
+
+/* ---- measurement ------------------------------------------------------------------ */
+
+/* Section V-A / Section VI metrics of n latencies. trim != 0 first discards
+ * min(10, n/6) samples from each end in the given (arrival) order, the paper's warm-up
+ * and cool-down rule scaled to short runs. Percentiles interpolate linearly between
+ * closest ranks. HS_E_INVAL if nothing is left. Pure host computation. */
+hs_status hs_latency_metrics_compute(const double* latencies, size_t n, int trim,
+                                     hs_latency_metrics* out);
+/* enable != 0: bracket every kernel launch of this application with HIP events on the
+ * launching stream and accumulate elapsed time per kernel family (adds event overhead;
+ * meant for roofline measurements, off by default). Switching resets the accumulators.
+ * HS_E_STATE while frames are in flight. */
+hs_status hs_set_kernel_timing(hs_app* app, int enable);
+/* Copy up to max_entries accumulated entries; *n_entries receives the count available.
+ * Collects finished events first. HS_E_STATE while frames are in flight. */
+hs_status hs_get_kernel_times(hs_app* app, hs_kernel_time* entries, int max_entries,
+                              int* n_entries);
+
+/* Thread-local, never NULL; valid until the next failing call on this thread. */
+const char* hs_last_error(void);
+/* Library version string. */
+const char* hs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HS_H_ */

@@ -1,0 +1,106 @@
+// Host-only parts of libhs that need no GPU: the admission-control predicate of the
+// spatial partitions (paper Section IV-A) and the latency determinism metrics
+// (Section V-A, warm-up / cool-down rule of Section VI).
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <vector>
+
+#include "hs.h"
+#include "hs_internal.h"
+
+namespace hs {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+hs_status admission_check(const uint32_t* claimed, const uint32_t* req_a, const uint32_t* req_b,
+                          int n_words, int device_cus) {
+  if (!req_a || !req_b || n_words < 1 || n_words > HS_MAX_CU_WORDS || device_cus < 1 ||
+      device_cus > 32 * HS_MAX_CU_WORDS) {
+    set_error("admission: bad arguments (n_words=%d, device_cus=%d)", n_words, device_cus);
+    return HS_E_INVAL;
+  }
+  bool any_a = false, any_b = false;
+  for (int w = 0; w < n_words; ++w) {
+    any_a |= req_a[w] != 0;
+    any_b |= req_b[w] != 0;
+    const uint32_t req = req_a[w] | req_b[w];
+    // bits naming CUs the device does not have
+    uint32_t legal = 0;
+    const int lo = 32 * w;
+    if (device_cus >= lo + 32) legal = 0xffffffffu;
+    else if (device_cus > lo) legal = (1u << (device_cus - lo)) - 1u;
+    if (req & ~legal) {
+      set_error("admission denied: request names a CU >= %d", device_cus);
+      return HS_E_OVERSUBSCRIBED;
+    }
+    if (claimed && (req & claimed[w])) {
+      set_error("admission denied: requested CUs are claimed by another application");
+      return HS_E_OVERSUBSCRIBED;
+    }
+  }
+  if (!any_a || !any_b) {
+    set_error("admission denied: empty CU mask");
+    return HS_E_OVERSUBSCRIBED;
+  }
+  return HS_OK;
+}
+
+static double percentile_sorted(const std::vector<double>& s, double p) {
+  const double pos = (double)(s.size() - 1) * p / 100.0;
+  const size_t lo = (size_t)std::floor(pos);
+  const size_t hi = std::min(lo + 1, s.size() - 1);
+  return s[lo] + (s[hi] - s[lo]) * (pos - (double)lo);
+}
+
+}  // namespace hs
+
+extern "C" {
+
+const char* hs_last_error(void) { return hs::g_err; }
+const char* hs_version(void) { return "libhs 0.1 (gfx950)"; }
+
+hs_status hs_admission_check(const uint32_t* claimed_by_others, const uint32_t* req_infer,
+                             const uint32_t* req_overlay, int n_words, int device_cus) {
+  return hs::admission_check(claimed_by_others, req_infer, req_overlay, n_words, device_cus);
+}
+
+hs_status hs_latency_metrics_compute(const double* lat, size_t n, int trim,
+                                     hs_latency_metrics* out) {
+  if (!lat || !out) {
+    hs::set_error("latency metrics: NULL argument");
+    return HS_E_INVAL;
+  }
+  size_t t = 0;
+  if (trim) t = std::min<size_t>(10, n / 6);
+  if (n <= 2 * t) {
+    hs::set_error("latency metrics: no samples left");
+    return HS_E_INVAL;
+  }
+  std::vector<double> s(lat + t, lat + (n - t));
+  std::sort(s.begin(), s.end());
+  double sum = 0.0;
+  for (double v : s) sum += v;
+  const double mean = sum / (double)s.size();
+  double ss = 0.0;
+  for (double v : s) ss += (v - mean) * (v - mean);
+  out->n = s.size();
+  out->mean = mean;
+  out->max = s.back();
+  out->std = std::sqrt(ss / (double)s.size());
+  out->p50 = hs::percentile_sorted(s, 50.0);
+  out->p99 = hs::percentile_sorted(s, 99.0);
+  out->tail = s.back() - hs::percentile_sorted(s, 95.0);
+  out->flatness = hs::percentile_sorted(s, 90.0) - hs::percentile_sorted(s, 10.0);
+  return HS_OK;
+}
+
+}  // extern "C"

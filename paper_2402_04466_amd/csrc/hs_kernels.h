@@ -1,0 +1,108 @@
+// Device-side interface of libhs: parameter blocks and launch functions of the HIP
+// kernels behind the four per-frame stages (format conversion, recurrent conv-net
+// inference, postprocess, overlay; paper Section III-A).  Host code fills a parameter
+// block once per layer at application creation and launches it per frame.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hs {
+
+typedef _Float16 f16;
+
+// ---- stage 1: bilinear resize (exact integer) + normalise + interleave ----------------
+struct ResizeParams {
+  const uint8_t* src;   // frame, RGB bytes, row pitch src_pitch (16-byte multiple)
+  size_t src_pitch;
+  int wi, hi, wo, ho;
+  f16* dst;             // padded 4-channel fp16 image: pixel (y+pad_t, x+pad_l), pitch dst_w px
+  int dst_w, pad_l, pad_t;
+  float* dst_f32;       // optional planar fp32 [3][ho][wo]
+  const float* lut32;   // 256 entries
+  const f16* lut16;     // 256 entries
+  float rcp_dx, rcp_dy, rcp_d;  // 1/(2*wo), 1/(2*ho), 1/(4*wo*ho): division estimates
+};
+void launch_resize_norm(const ResizeParams& p, hipStream_t s);
+
+// ---- stage 2: implicit-GEMM convolution on fp16 MFMA ------------------------------------
+// Activations are pixel-major ("NHWC"): element (y, x, c) at in[(y*win + x)*cin_pitch + c].
+// The K axis is cut into chunks of KC contiguous halves; chunk q belongs to tap
+// q / chunks_per_tap = (ky, kx) = (tap / kw, tap % kw) and starts at channel
+// (q % chunks_per_tap) * KC of input pixel (stride*oy + ky - pad, stride*ox + kx - pad).
+// Out-of-range pixels read as zero.  First layers (3 input channels) use a padded
+// 4-channel image and "row taps": kw = 1, a chunk spans several adjacent pixels.
+struct ConvParams {
+  const f16* in;
+  const f16* wt;        // packed [cout_pad][ktot], ktot = nchunks*KC, zero rows above cout
+  int hin, win, cin_pitch;
+  int hout, wout, m;    // m = hout*wout output pixels
+  int cout, cout_pad;   // cout_pad: multiple of the block's N tile
+  int kc;               // 16, 32 or 64
+  int ntaps, kw, chunks_per_tap, nchunks, ktot;
+  int stride, pad;
+  // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)
+  int nsplit, chunks_per_split;
+  int use_partial;      // 1: store fp32 partial sums instead of running the fused epilogue
+  float* partial;       // [nsplit][m][cout_pad] fp32
+  // fused epilogue (use_partial == 0, nsplit == 1)
+  f16* out;             // out[m*out_pitch + n]
+  int out_pitch;
+  const f16* res;       // optional residual, res[m*res_pitch + n]
+  int res_pitch;
+  int relu;
+  float* out_f32;       // if set: planar fp32 out_f32[n*m_total + m] instead of `out`
+};
+void launch_conv_mfma(const ConvParams& p, hipStream_t s);
+
+// Sum split-K partials, add residual, ReLU, store fp16 (or planar fp32).
+struct SplitKEpilogueParams {
+  const float* partial; int nsplit; int m; int cout; int cout_pad;
+  f16* out; int out_pitch; const f16* res; int res_pitch; int relu; float* out_f32;
+};
+void launch_splitk_epilogue(const SplitKEpilogueParams& p, hipStream_t s);
+
+// ConvLSTM gate non-linearities and state update from the gate pre-activations.
+// partial: [nsplit][m][4*hid] with channels ordered i, f, g, o (hid each).
+// c: fp32 [m][hid] updated in place; h: fp16 written to h_out[m*h_pitch + j].
+struct LstmEpilogueParams {
+  const float* partial; int nsplit; int m; int hid;
+  float* c; f16* h_out; int h_pitch;
+};
+void launch_lstm_epilogue(const LstmEpilogueParams& p, hipStream_t s);
+
+// 3x3 stride-2 pad-1 max-pool on pixel-major fp16, c multiple of 8.
+struct MaxPoolParams { const f16* in; f16* out; int hin, win, hout, wout, c; };
+void launch_maxpool(const MaxPoolParams& p, hipStream_t s);
+
+// 1x1 head: logits[k][m] = sum_j w[k][j] * h[m*h_pitch + j], fp32 planar output.
+struct HeadParams { const f16* h; int h_pitch; const f16* w; int cin; int m; float* logits; };
+void launch_head(const HeadParams& p, hipStream_t s);
+
+// ---- stage 3: postprocess -----------------------------------------------------------------
+struct PostRecord {           // written by the kernel into pinned host memory
+  int32_t argmax_idx[8];
+  float peak[8];
+  uint8_t present[8];
+};
+struct PostParams {
+  const float* logits; int n;    // [8][n]
+  float theta;                   // logit threshold
+  float* heat; uint8_t* mask;    // [8][n]
+  PostRecord* rec;               // host-visible
+};
+void launch_postprocess(const PostParams& p, hipStream_t s);
+
+// ---- stage 4: overlay ---------------------------------------------------------------------
+struct OverlayParams {
+  const uint8_t* src; uint8_t* dst; size_t pitch; int wf, hf;
+  const uint8_t* mask; int wm, hm;   // [8][hm][wm]
+  int a;                             // Q8 alpha, 0..256
+  uint32_t pal[8];                   // R | G<<8 | B<<16
+};
+void launch_overlay(const OverlayParams& p, hipStream_t s);
+
+// ---- helpers ------------------------------------------------------------------------------
+void launch_fill_zero(void* d, size_t bytes, hipStream_t s);   // bytes multiple of 16
+
+}  // namespace hs

@@ -1,0 +1,1051 @@
+// libhs host runtime: contexts, applications, the per-frame launch plan, CU-masked stream
+// partitions with admission control, per-frame time stamps and the completion thread.
+// Paper: Section III-A (application and its four stages), Section II-C (time stamps at the
+// first and last stage), Section IV-A (exclusive partitions, admission control).
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <condition_variable>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <time.h>
+#include <vector>
+
+#include "hs.h"
+#include "hs_internal.h"
+#include "hs_kernels.h"
+
+namespace hs {
+
+static inline uint64_t now_ns() {
+  timespec ts;
+  clock_gettime(CLOCK_MONOTONIC, &ts);
+  return (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
+}
+
+#define HS_HIP(call)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return HS_E_DEVICE;                                                              \
+    }                                                                                  \
+  } while (0)
+
+// ---- kernel families (for timing) ----------------------------------------------------------
+enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_MAXPOOL, F_HEAD, F_POST, F_OVERLAY, F_COUNT };
+static const char* kFamilyName[F_COUNT] = {"resize_norm", "conv_mfma", "splitk_epilogue",
+                                           "lstm_epilogue", "maxpool", "head", "postprocess",
+                                           "overlay"};
+
+struct Op {
+  Family fam;
+  double flops = 0, bytes = 0;
+  ResizeParams resize;
+  ConvParams conv;
+  SplitKEpilogueParams splitk;
+  LstmEpilogueParams lstm;
+  MaxPoolParams pool;
+  HeadParams head;
+  PostParams post;
+  OverlayParams overlay;
+};
+
+static void launch_op(const Op& op, hipStream_t s) {
+  switch (op.fam) {
+    case F_RESIZE: launch_resize_norm(op.resize, s); break;
+    case F_CONV: launch_conv_mfma(op.conv, s); break;
+    case F_SPLITK: launch_splitk_epilogue(op.splitk, s); break;
+    case F_LSTM: launch_lstm_epilogue(op.lstm, s); break;
+    case F_MAXPOOL: launch_maxpool(op.pool, s); break;
+    case F_HEAD: launch_head(op.head, s); break;
+    case F_POST: launch_postprocess(op.post, s); break;
+    case F_OVERLAY: launch_overlay(op.overlay, s); break;
+    default: break;
+  }
+}
+
+// ---- workspace carving -----------------------------------------------------------------------
+struct Carver {
+  uint8_t* base;   // may be NULL for a dry run
+  size_t off = 0;
+  explicit Carver(void* b) : base((uint8_t*)b) {}
+  template <typename T>
+  T* take(size_t count) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct Tensor {
+  f16* p = nullptr;
+  int h = 0, w = 0, c = 0, pitch = 0;
+};
+
+enum SlotState { SLOT_FREE = 0, SLOT_INFLIGHT = 1, SLOT_DONE = 2 };
+
+struct Slot {
+  std::vector<Op> pre;     // stage 1
+  std::vector<Op> infer;   // stage 2
+  std::vector<Op> post;    // stage 3
+  Op overlay;              // stage 4
+  hipEvent_t ev_begin = nullptr, ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr,
+             ev_overlay = nullptr;
+  PostRecord* rec = nullptr;   // pinned host memory, written by the stage-3 kernel
+  f16* d_netin = nullptr;
+  float* d_netin_f32 = nullptr;
+  float* d_logits = nullptr;
+  float* d_heat = nullptr;
+  uint8_t* d_mask = nullptr;
+  int state = SLOT_FREE;
+  hs_result result;
+};
+
+struct TimedLaunch {
+  Family fam;
+  double flops, bytes;
+  hipEvent_t e0, e1;
+};
+
+}  // namespace hs
+
+using namespace hs;
+
+struct hs_ctx {
+  int device = 0;
+  int n_cus = 0;
+  std::mutex mu;
+  std::vector<hs_app*> apps;
+};
+
+struct hs_app {
+  hs_ctx* ctx = nullptr;
+  hs_app_desc desc;
+  int map_w = 0, map_h = 0;
+  int netin_w = 0, netin_h = 0, netin_pad = 0;   // padded stage-1 output geometry
+  bool stateful = false;
+  // recurrent state
+  float* d_c = nullptr;
+  f16* d_concat = nullptr;
+  int concat_pitch = 0, hid = 0, x_ch = 0;
+  // streams / partition
+  hipStream_t s_infer = nullptr, s_overlay = nullptr;
+  bool partitioned = false;
+  uint32_t claim[HS_MAX_CU_WORDS] = {0};
+  // ring
+  std::vector<Slot> slots;
+  int depth = 0;
+  uint64_t n_submitted = 0, n_completed = 0, n_delivered = 0;
+  std::mutex mu;
+  std::condition_variable cv_work, cv_done;
+  std::thread completer;
+  bool stop = false;
+  std::string completer_error;
+  // kernel timing
+  bool timing = false;
+  std::vector<TimedLaunch> timed;
+  double acc_ms[F_COUNT] = {0}, acc_flops[F_COUNT] = {0}, acc_bytes[F_COUNT] = {0};
+  uint64_t acc_n[F_COUNT] = {0};
+  void* pinned = nullptr;
+};
+
+namespace hs {
+
+// ---- weight packing ----------------------------------------------------------------------------
+// Generic layer: packed[n][(ky*k + kx)*cin + c] = w[n][c][ky][kx]; rows cout..cout_pad-1 zero.
+static void pack_generic(const float* w, int cout, int cin, int k, int cout_pad, f16* dst) {
+  const size_t ktot = (size_t)k * k * cin;
+  std::memset(dst, 0, (size_t)cout_pad * ktot * sizeof(f16));
+  for (int n = 0; n < cout; ++n)
+    for (int c = 0; c < cin; ++c)
+      for (int ky = 0; ky < k; ++ky)
+        for (int kx = 0; kx < k; ++kx)
+          dst[(size_t)n * ktot + (size_t)(ky * k + kx) * cin + c] =
+              (f16)w[(((size_t)n * cin + c) * k + ky) * k + kx];
+}
+
+// First layer on the padded 4-channel image: one chunk per kernel row, covering chunk_px
+// adjacent pixels of 4 channels; packed[n][ky][px][ch] = w[n][ch][ky][px] (px < k, ch < 3).
+static void pack_rowtap(const float* w, int cout, int k, int chunk_px, int cout_pad, f16* dst) {
+  const size_t ktot = (size_t)k * chunk_px * 4;
+  std::memset(dst, 0, (size_t)cout_pad * ktot * sizeof(f16));
+  for (int n = 0; n < cout; ++n)
+    for (int ch = 0; ch < 3; ++ch)
+      for (int ky = 0; ky < k; ++ky)
+        for (int px = 0; px < k; ++px)
+          dst[(size_t)n * ktot + ((size_t)ky * chunk_px + px) * 4 + ch] =
+              (f16)w[(((size_t)n * 3 + ch) * k + ky) * k + px];
+}
+
+// ---- plan builder ------------------------------------------------------------------------------
+static inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+static inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+// Walks the layers of a network in blob order.  Used twice: a sizing walk (no pointers, no
+// packing) that yields the packed-weight and split-K scratch sizes, then the real walk.
+struct Builder {
+  const hs_app_desc& d;
+  Carver carve;
+  bool pack;                      // pack weights on the host (create only)
+  bool carve_acts;                // hand out activation storage (second walk)
+  std::vector<f16> host_w;        // packed weights staged on the host
+  f16* d_w = nullptr;             // device weights base
+  size_t w_halves = 0;            // packed weights consumed so far
+  const float* blob;
+  size_t blob_off = 0;
+  size_t partial_floats = 0;
+  std::vector<Op> ops;            // stage-2 ops; slot-dependent pointers are patched per slot
+  int first_conv_op = -1;         // op whose conv.in is the slot's padded net input
+  int logits_op = -1;             // op that writes the slot's logits
+  int map_h = 0, map_w = 0;
+  bool stateful = false;
+  float* d_c = nullptr;
+  f16* d_concat = nullptr;
+
+  Builder(const hs_app_desc& desc, void* base, bool do_pack, bool do_carve)
+      : d(desc), carve(base), pack(do_pack), carve_acts(do_carve), blob(desc.weights) {}
+
+  template <typename T>
+  T* acts(size_t count) { return carve_acts ? carve.take<T>(count) : nullptr; }
+
+  // Reserve room for n packed halves; returns the offset. Regions start 256-byte aligned.
+  size_t reserve_w(size_t n) {
+    const size_t off = w_halves;
+    w_halves = round_up_sz(off + n, 128);
+    if (pack) host_w.resize(w_halves);
+    return off;
+  }
+
+  static void choose_split(ConvParams& c) {
+    const int tiles = ((c.m + 63) / 64) * (c.cout_pad / 64);
+    int ns = 1;
+    if (tiles < 192) ns = std::max(1, std::min((320 + tiles - 1) / tiles, c.nchunks / 4));
+    c.chunks_per_split = (c.nchunks + ns - 1) / ns;
+    c.nsplit = (c.nchunks + c.chunks_per_split - 1) / c.chunks_per_split;
+  }
+
+  // Appends the convolution and, when it is split along K, its reduction epilogue.
+  // keep_partial: leave the partial sums in the scratch buffer for a later kernel.
+  // Returns the index of the convolution op.
+  int add_conv(ConvParams c, size_t w_off, const Tensor* res, const Tensor* out, bool relu,
+               bool want_f32, bool keep_partial, double flops) {
+    Op op;
+    op.fam = F_CONV;
+    op.flops = flops;
+    c.wt = d_w ? d_w + w_off : nullptr;
+    choose_split(c);
+    const bool partial = c.nsplit > 1 || keep_partial;
+    c.use_partial = partial ? 1 : 0;
+    c.partial = nullptr;   // patched when the scratch buffer is carved
+    c.out = nullptr; c.out_pitch = 0; c.res = nullptr; c.res_pitch = 0; c.relu = 0;
+    c.out_f32 = nullptr;
+    if (partial) {
+      partial_floats = std::max(partial_floats, (size_t)c.nsplit * c.m * c.cout_pad);
+    } else {
+      if (out) { c.out = out->p; c.out_pitch = out->pitch; }
+      if (res) { c.res = res->p; c.res_pitch = res->pitch; }
+      c.relu = relu ? 1 : 0;
+    }
+    op.conv = c;
+    ops.push_back(op);
+    const int conv_idx = (int)ops.size() - 1;
+    if (want_f32 && !partial) logits_op = conv_idx;
+    if (partial && !keep_partial) {
+      Op e;
+      e.fam = F_SPLITK;
+      e.bytes = (double)c.nsplit * c.m * c.cout * 4.0 + (double)c.m * c.cout * 2.0;
+      SplitKEpilogueParams& s = e.splitk;
+      s.partial = nullptr;
+      s.nsplit = c.nsplit; s.m = c.m; s.cout = c.cout; s.cout_pad = c.cout_pad;
+      s.out = out ? out->p : nullptr; s.out_pitch = out ? out->pitch : 0;
+      s.res = res ? res->p : nullptr; s.res_pitch = res ? res->pitch : 0;
+      s.relu = relu ? 1 : 0;
+      s.out_f32 = nullptr;
+      ops.push_back(e);
+      if (want_f32) logits_op = (int)ops.size() - 1;
+    }
+    return conv_idx;
+  }
+
+  // Generic convolution on a pixel-major tensor; weights are the next cout*cin*k*k floats of the
+  // blob starting at blob_at. Fills out->h/w/c.
+  int conv_layer(const Tensor& in, size_t blob_at, int cout, int k, int stride, int pad, bool relu,
+                 const Tensor* res, Tensor* out, bool want_f32, bool keep_partial) {
+    const int cin = in.c;
+    ConvParams g;
+    std::memset(&g, 0, sizeof(g));
+    g.in = in.p; g.hin = in.h; g.win = in.w; g.cin_pitch = in.pitch;
+    g.hout = conv_out(in.h, k, stride, pad); g.wout = conv_out(in.w, k, stride, pad);
+    g.m = g.hout * g.wout;
+    g.cout = cout; g.cout_pad = round_up(cout, 64);
+    g.kc = (cin % 64 == 0) ? 64 : (cin % 32 == 0 ? 32 : 16);
+    g.ntaps = k * k; g.kw = k; g.chunks_per_tap = cin / g.kc;
+    g.nchunks = g.ntaps * g.chunks_per_tap; g.ktot = g.nchunks * g.kc;
+    g.stride = stride; g.pad = pad;
+    const size_t w_off = reserve_w((size_t)g.cout_pad * g.ktot);
+    if (pack) pack_generic(blob + blob_at, cout, cin, k, g.cout_pad, host_w.data() + w_off);
+    out->h = g.hout; out->w = g.wout; out->c = cout;
+    return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
+                    2.0 * g.m * (double)cout * cin * k * k);
+  }
+
+  // First layer: 3 input channels on the padded 4-channel image, k x k, stride 2, ReLU.
+  void first_layer(size_t blob_at, int pad_img_h, int pad_img_w, int cout, int k, Tensor* out) {
+    const int pad = k / 2;
+    const int chunk_px = (k <= 4) ? 4 : 8;
+    ConvParams g;
+    std::memset(&g, 0, sizeof(g));
+    g.in = nullptr;   // per slot
+    g.hin = pad_img_h; g.win = pad_img_w; g.cin_pitch = 4;
+    g.hout = conv_out(d.net_h, k, 2, pad); g.wout = conv_out(d.net_w, k, 2, pad);
+    g.m = g.hout * g.wout;
+    g.cout = cout; g.cout_pad = round_up(cout, 64);
+    g.kc = chunk_px * 4;
+    g.ntaps = k; g.kw = 1; g.chunks_per_tap = 1; g.nchunks = k; g.ktot = k * g.kc;
+    g.stride = 2; g.pad = 0;
+    const size_t w_off = reserve_w((size_t)g.cout_pad * g.ktot);
+    if (pack) pack_rowtap(blob + blob_at, cout, k, chunk_px, g.cout_pad, host_w.data() + w_off);
+    out->h = g.hout; out->w = g.wout; out->c = cout;
+    first_conv_op =
+        add_conv(g, w_off, nullptr, out, true, false, false, 2.0 * g.m * (double)cout * 3 * k * k);
+  }
+
+  void walk_tiny(int ph, int pw) {
+    const int h1 = conv_out(d.net_h, 3, 2, 1), w1 = conv_out(d.net_w, 3, 2, 1);
+    const int h2 = conv_out(h1, 3, 2, 1), w2 = conv_out(w1, 3, 2, 1);
+    Tensor t1, t2, t3, lg;
+    t1.p = acts<f16>((size_t)h1 * w1 * 16); t1.pitch = 16;
+    t2.p = acts<f16>((size_t)h2 * w2 * 32); t2.pitch = 32;
+    t3.p = acts<f16>((size_t)h2 * w2 * 32); t3.pitch = 32;
+    size_t at = 0;
+    first_layer(at, ph, pw, 16, 3, &t1);                                 at += 16 * 3 * 9;
+    conv_layer(t1, at, 32, 3, 2, 1, true, nullptr, &t2, false, false);   at += 32 * 16 * 9;
+    conv_layer(t2, at, 32, 3, 1, 1, true, nullptr, &t3, false, false);   at += 32 * 32 * 9;
+    conv_layer(t3, at, 8, 3, 1, 1, false, nullptr, &lg, true, false);    at += 8 * 32 * 9;
+    blob_off = at;
+    map_h = lg.h; map_w = lg.w; stateful = false;
+  }
+
+  void walk_resnet(int ph, int pw) {
+    const int hs_ = conv_out(d.net_h, 7, 2, 3), ws_ = conv_out(d.net_w, 7, 2, 3);
+    const int hp = conv_out(hs_, 3, 2, 1), wp = conv_out(ws_, 3, 2, 1);
+    int hf = hp, wf = wp;
+    for (int i = 0; i < 3; ++i) { hf = conv_out(hf, 3, 2, 1); wf = conv_out(wf, 3, 2, 1); }
+    const int mf = hf * wf;
+    Tensor stem;
+    stem.p = acts<f16>((size_t)hs_ * ws_ * 64); stem.pitch = 64;
+    Tensor buf[4];
+    for (int i = 0; i < 4; ++i) buf[i].p = acts<f16>((size_t)hp * wp * 64);
+    f16* concat = acts<f16>((size_t)mf * 768);
+    float* cstate = acts<float>((size_t)mf * 256);
+
+    size_t at = 0;
+    first_layer(at, ph, pw, 64, 7, &stem);
+    at += 64 * 3 * 49;
+    {
+      Op op;
+      op.fam = F_MAXPOOL;
+      op.pool = MaxPoolParams{stem.p, buf[0].p, hs_, ws_, hp, wp, 64};
+      op.bytes = ((double)hs_ * ws_ + (double)hp * wp) * 64 * 2;
+      ops.push_back(op);
+    }
+    int cur = 0;
+    buf[0].h = hp; buf[0].w = wp; buf[0].c = 64; buf[0].pitch = 64;
+    const int widths[4] = {64, 128, 256, 512};
+    int cin = 64;
+    for (int s = 0; s < 4; ++s) {
+      for (int blk = 0; blk < 2; ++blk) {
+        const int width = widths[s];
+        const bool proj = blk == 0 && cin != width;
+        const int bc_in = blk == 0 ? cin : width;
+        const Tensor a = buf[cur];
+        Tensor& t = buf[(cur + 1) % 4];
+        Tensor& sc = buf[(cur + 2) % 4];
+        Tensor& o = buf[(cur + 3) % 4];
+        // blob order within a block: conv a, conv b, projection
+        const size_t at_a = at, at_b = at_a + (size_t)width * bc_in * 9,
+                     at_p = at_b + (size_t)width * width * 9;
+        at = at_p + (proj ? (size_t)width * bc_in : 0);
+        t.pitch = width;
+        conv_layer(a, at_a, width, 3, proj ? 2 : 1, 1, true, nullptr, &t, false, false);
+        const Tensor* shortcut = &a;
+        if (proj) {
+          sc.pitch = width;
+          conv_layer(a, at_p, width, 1, 2, 0, false, nullptr, &sc, false, false);
+          shortcut = &sc;
+        }
+        const bool last = s == 3 && blk == 1;
+        if (last) { o.p = concat; o.pitch = 768; } else { o.pitch = width; }
+        conv_layer(t, at_b, width, 3, 1, 1, true, shortcut, &o, false, false);
+        cur = (cur + 3) % 4;
+        cin = width;
+      }
+    }
+    Tensor cat;
+    cat.p = concat; cat.h = hf; cat.w = wf; cat.c = 768; cat.pitch = 768;
+    Tensor gates;
+    const int lstm_conv = conv_layer(cat, at, 1024, 3, 1, 1, false, nullptr, &gates, false, true);
+    at += (size_t)1024 * 768 * 9;
+    {
+      Op op;
+      op.fam = F_LSTM;
+      op.lstm = LstmEpilogueParams{nullptr, ops[lstm_conv].conv.nsplit, mf, 256, cstate,
+                                   concat ? concat + 512 : nullptr, 768};
+      op.bytes = (double)ops[lstm_conv].conv.nsplit * mf * 1024 * 4.0 + (double)mf * 256 * 10.0;
+      ops.push_back(op);
+    }
+    // head weights: 8 x 256 fp16, plain [k][c]
+    const size_t w_off = reserve_w(2048);
+    if (pack)
+      for (int i = 0; i < 2048; ++i) host_w[w_off + i] = (f16)blob[at + i];
+    at += 2048;
+    {
+      Op op;
+      op.fam = F_HEAD;
+      op.head = HeadParams{concat ? concat + 512 : nullptr, 768, d_w ? d_w + w_off : nullptr, 256,
+                           mf, nullptr};
+      op.flops = 2.0 * mf * 8 * 256;
+      ops.push_back(op);
+      logits_op = (int)ops.size() - 1;
+    }
+    blob_off = at;
+    map_h = hf; map_w = wf; stateful = true;
+    d_c = cstate; d_concat = concat;
+  }
+
+  void walk(int ph, int pw) {
+    if (d.net == HS_NET_TINY4) walk_tiny(ph, pw); else walk_resnet(ph, pw);
+  }
+};
+
+static void padded_input_geometry(int net_w, int net_h, int k, int* pw, int* ph, int* pad) {
+  const int p = k / 2, chunk_px = (k <= 4) ? 4 : 8;
+  const int wout = conv_out(net_w, k, 2, p);
+  *pad = p;
+  *ph = net_h + 2 * p;
+  *pw = round_up(std::max(net_w + 2 * p, 2 * (wout - 1) + chunk_px), 2);
+}
+
+static size_t expected_weight_floats(int net) {
+  if (net == HS_NET_TINY4) return 16 * 3 * 9 + 32 * 16 * 9 + 32 * 32 * 9 + 8 * 32 * 9;
+  size_t n = 64 * 3 * 49;
+  int cin = 64;
+  const int widths[4] = {64, 128, 256, 512};
+  for (int s = 0; s < 4; ++s) {
+    const int w = widths[s];
+    n += (size_t)w * cin * 9 + (size_t)w * w * 9 * 3;
+    if (cin != w) n += (size_t)w * cin;
+    cin = w;
+  }
+  n += (size_t)1024 * 768 * 9 + 8 * 256;
+  return n;
+}
+
+static hs_status validate_desc(const hs_app_desc* d) {
+  if (!d) { set_error("NULL description"); return HS_E_INVAL; }
+  if (d->frame_w < 1 || d->frame_h < 1 || d->net_w < 8 || d->net_h < 8 || d->frame_w > 10922 ||
+      d->frame_h > 65535 || d->net_w > 16384 || d->net_h > 16384) {
+    set_error("bad frame or network size");
+    return HS_E_INVAL;
+  }
+  if (d->frame_pitch < (size_t)3 * d->frame_w || d->frame_pitch % 16 != 0) {
+    set_error("frame_pitch must be >= 3*frame_w and a multiple of 16");
+    return HS_E_INVAL;
+  }
+  // exact 32-bit integer resize: 255*D + D/2 with D = 4*net_w*net_h must stay below 2^31
+  if ((double)d->net_w * d->net_h * 4.0 * 255.5 >= 2147483648.0 ||
+      (2.0 * d->net_w + 1.0) * d->frame_w >= 2147483648.0 ||
+      (2.0 * d->net_h + 1.0) * d->frame_h >= 2147483648.0) {
+    set_error("resize dimensions exceed the exact 32-bit range");
+    return HS_E_INVAL;
+  }
+  if (d->net != HS_NET_TINY4 && d->net != HS_NET_RESNET18_CONVLSTM) {
+    set_error("unknown network kind %d", d->net);
+    return HS_E_INVAL;
+  }
+  if (!(d->std > 0.0f) || !(d->threshold > 0.0f && d->threshold < 1.0f) ||
+      !(d->alpha >= 0.0f && d->alpha <= 1.0f)) {
+    set_error("std must be > 0, threshold in (0,1), alpha in [0,1]");
+    return HS_E_INVAL;
+  }
+  if (d->queue_depth < 1 || d->queue_depth > 64) {
+    set_error("queue_depth must be 1..64");
+    return HS_E_INVAL;
+  }
+  return HS_OK;
+}
+
+// Builds the whole plan into `app`, or only sizes the workspace when app == NULL.
+static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out) {
+  const bool create = app != nullptr;
+  const int depth = d->queue_depth;
+  const int k1 = d->net == HS_NET_TINY4 ? 3 : 7;
+  int pw, ph, pad;
+  padded_input_geometry(d->net_w, d->net_h, k1, &pw, &ph, &pad);
+
+  // sizing walk: packed-weight size
+  Builder sizing(*d, nullptr, false, false);
+  sizing.walk(ph, pw);
+  if (sizing.blob_off != expected_weight_floats(d->net)) {
+    set_error("internal: layer walk consumed %zu floats, expected %zu", sizing.blob_off,
+              expected_weight_floats(d->net));
+    return HS_E_INVAL;
+  }
+
+  // real walk: workspace = [weights][activations, state][split-K scratch][tables][slots]
+  Builder b(*d, create ? d->d_workspace : nullptr, create, true);
+  b.d_w = b.carve.take<f16>(sizing.w_halves);
+  b.walk(ph, pw);
+  float* d_partial = b.carve.take<float>(b.partial_floats);
+  for (Op& op : b.ops) {
+    if (op.fam == F_CONV && op.conv.use_partial) op.conv.partial = d_partial;
+    if (op.fam == F_SPLITK) op.splitk.partial = d_partial;
+    if (op.fam == F_LSTM) op.lstm.partial = d_partial;
+  }
+  float* d_lut32 = b.carve.take<float>(256);
+  f16* d_lut16 = b.carve.take<f16>(256);
+  const int mh = b.map_h, mw = b.map_w;
+  const size_t n_map = (size_t)mh * mw;
+  struct SlotBuf { f16* netin; float* netin32; float* logits; float* heat; uint8_t* mask; };
+  std::vector<SlotBuf> sb(depth);
+  for (int i = 0; i < depth; ++i) {
+    sb[i].netin = b.carve.take<f16>((size_t)ph * pw * 4);
+    sb[i].netin32 = d->net_fp32_input ? b.carve.take<float>((size_t)3 * d->net_h * d->net_w)
+                                      : nullptr;
+    sb[i].logits = b.carve.take<float>(8 * n_map);
+    sb[i].heat = b.carve.take<float>(8 * n_map);
+    sb[i].mask = b.carve.take<uint8_t>(8 * n_map);
+  }
+  const size_t total = round_up_sz(b.carve.off, 256);
+  if (bytes_out) *bytes_out = total;
+  if (!create) return HS_OK;
+
+  if (d->workspace_bytes < total) {
+    set_error("workspace too small: %zu bytes given, %zu needed", d->workspace_bytes, total);
+    return HS_E_NOMEM;
+  }
+  app->map_h = mh; app->map_w = mw; app->stateful = b.stateful;
+  app->d_c = b.d_c; app->d_concat = b.d_concat; app->concat_pitch = 768; app->hid = 256;
+  app->x_ch = 512;
+
+  // upload weights and tables, zero the recurrent state and the padded borders
+  HS_HIP(hipMemcpy(b.d_w, b.host_w.data(), b.host_w.size() * sizeof(f16), hipMemcpyHostToDevice));
+  {
+    float lut32[256];
+    f16 lut16[256];
+    for (int v = 0; v < 256; ++v) {
+      lut32[v] = (float)(((double)v / 255.0 - (double)d->mean) / (double)d->std);
+      lut16[v] = (f16)lut32[v];
+    }
+    HS_HIP(hipMemcpy(d_lut32, lut32, sizeof(lut32), hipMemcpyHostToDevice));
+    HS_HIP(hipMemcpy(d_lut16, lut16, sizeof(lut16), hipMemcpyHostToDevice));
+  }
+  for (int i = 0; i < depth; ++i)
+    HS_HIP(hipMemset(sb[i].netin, 0, (size_t)ph * pw * 4 * sizeof(f16)));
+  if (app->stateful) {
+    HS_HIP(hipMemset(app->d_c, 0, n_map * 256 * sizeof(float)));
+    HS_HIP(hipMemset(app->d_concat, 0, n_map * 768 * sizeof(f16)));
+  }
+  HS_HIP(hipDeviceSynchronize());
+
+  // per-slot launch plans
+  app->netin_w = pw; app->netin_h = ph; app->netin_pad = pad;
+  const double theta_d = std::log((double)d->threshold / (1.0 - (double)d->threshold));
+  int a_q8 = (int)lrint(256.0 * (double)d->alpha);
+  a_q8 = std::max(0, std::min(256, a_q8));
+  HS_HIP(hipHostMalloc(&app->pinned, sizeof(PostRecord) * depth, hipHostMallocDefault));
+  std::memset(app->pinned, 0, sizeof(PostRecord) * depth);
+  app->slots.resize(depth);
+  for (int i = 0; i < depth; ++i) {
+    Slot& s = app->slots[i];
+    s.d_netin = sb[i].netin; s.d_netin_f32 = sb[i].netin32;
+    s.d_logits = sb[i].logits; s.d_heat = sb[i].heat; s.d_mask = sb[i].mask;
+    s.rec = (PostRecord*)app->pinned + i;
+    Op r;
+    r.fam = F_RESIZE;
+    ResizeParams& rp = r.resize;
+    rp.src = nullptr; rp.src_pitch = d->frame_pitch;
+    rp.wi = d->frame_w; rp.hi = d->frame_h; rp.wo = d->net_w; rp.ho = d->net_h;
+    rp.dst = s.d_netin; rp.dst_w = pw; rp.pad_l = pad; rp.pad_t = pad;
+    rp.dst_f32 = s.d_netin_f32; rp.lut32 = d_lut32; rp.lut16 = d_lut16;
+    rp.rcp_dx = 1.0f / (2.0f * d->net_w); rp.rcp_dy = 1.0f / (2.0f * d->net_h);
+    rp.rcp_d = 1.0f / (4.0f * (float)d->net_w * (float)d->net_h);
+    r.bytes = 3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
+              (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0);
+    s.pre.push_back(r);
+    s.infer = b.ops;
+    s.infer[b.first_conv_op].conv.in = s.d_netin;
+    Op& lo = s.infer[b.logits_op];
+    if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits;
+    else if (lo.fam == F_SPLITK) lo.splitk.out_f32 = s.d_logits;
+    else lo.head.logits = s.d_logits;
+    Op p;
+    p.fam = F_POST;
+    p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec};
+    p.bytes = 8.0 * n_map * (4 + 4 + 1);
+    s.post.push_back(p);
+    Op& o = s.overlay;
+    o.fam = F_OVERLAY;
+    OverlayParams& op = o.overlay;
+    op.src = nullptr; op.dst = nullptr; op.pitch = d->frame_pitch;
+    op.wf = d->frame_w; op.hf = d->frame_h; op.mask = s.d_mask; op.wm = mw; op.hm = mh;
+    op.a = a_q8;
+    for (int k = 0; k < 8; ++k)
+      op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
+                  ((uint32_t)d->palette[k][2] << 16);
+    o.bytes = 6.0 * d->frame_w * d->frame_h + 8.0 * n_map;
+    HS_HIP(hipEventCreate(&s.ev_begin));
+    HS_HIP(hipEventCreate(&s.ev_pre));
+    HS_HIP(hipEventCreate(&s.ev_infer));
+    HS_HIP(hipEventCreate(&s.ev_post));
+    HS_HIP(hipEventCreate(&s.ev_overlay));
+  }
+  return HS_OK;
+}
+
+// ---- completion thread ---------------------------------------------------------------------------
+static void completer_main(hs_app* app) {
+  (void)hipSetDevice(app->ctx->device);
+  for (;;) {
+    Slot* s = nullptr;
+    {
+      std::unique_lock<std::mutex> lk(app->mu);
+      app->cv_work.wait(lk, [&] { return app->stop || app->n_completed < app->n_submitted; });
+      if (app->n_completed >= app->n_submitted) return;   // stop requested and nothing pending
+      s = &app->slots[app->n_completed % app->depth];
+    }
+    hipError_t e = hipEventSynchronize(s->ev_overlay);
+    const uint64_t t_done = now_ns();
+    hs_result& r = s->result;
+    r.t_overlay_done_ns = t_done;
+    float ms_pre = 0, ms_inf = 0, ms_post = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms_pre, s->ev_pre, s->ev_overlay);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms_inf, s->ev_infer, s->ev_overlay);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms_post, s->ev_post, s->ev_overlay);
+    auto back = [&](float ms) {
+      const double ns = (double)ms * 1e6;
+      return t_done - (uint64_t)std::max(0.0, ns);
+    };
+    r.t_pre_done_ns = back(ms_pre);
+    r.t_infer_done_ns = back(ms_inf);
+    r.t_post_done_ns = back(ms_post);
+    std::memcpy(r.argmax_idx, s->rec->argmax_idx, sizeof(r.argmax_idx));
+    std::memcpy(r.peak, s->rec->peak, sizeof(r.peak));
+    std::memcpy(r.present, s->rec->present, sizeof(r.present));
+    {
+      std::lock_guard<std::mutex> lk(app->mu);
+      if (e != hipSuccess && app->completer_error.empty())
+        app->completer_error = hipGetErrorString(e);
+      s->state = SLOT_DONE;
+      app->n_completed++;
+    }
+    app->cv_done.notify_all();
+  }
+}
+
+static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* mo, int n_words) {
+  hipStream_t si = nullptr, so = nullptr;
+  if (mi) {
+    HS_HIP(hipExtStreamCreateWithCUMask(&si, (uint32_t)n_words, mi));
+    hipError_t e = hipExtStreamCreateWithCUMask(&so, (uint32_t)n_words, mo);
+    if (e != hipSuccess) {
+      (void)hipStreamDestroy(si);
+      set_error("hipExtStreamCreateWithCUMask failed: %s", hipGetErrorString(e));
+      return HS_E_DEVICE;
+    }
+  } else {
+    HS_HIP(hipStreamCreateWithFlags(&si, hipStreamNonBlocking));
+    hipError_t e = hipStreamCreateWithFlags(&so, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+      (void)hipStreamDestroy(si);
+      set_error("hipStreamCreateWithFlags failed: %s", hipGetErrorString(e));
+      return HS_E_DEVICE;
+    }
+  }
+  if (app->s_infer) (void)hipStreamDestroy(app->s_infer);
+  if (app->s_overlay) (void)hipStreamDestroy(app->s_overlay);
+  app->s_infer = si;
+  app->s_overlay = so;
+  return HS_OK;
+}
+
+static bool frames_in_flight(hs_app* app) {
+  std::lock_guard<std::mutex> lk(app->mu);
+  return app->n_completed < app->n_submitted;
+}
+
+static void collect_timing(hs_app* app) {
+  for (TimedLaunch& t : app->timed) {
+    float ms = 0;
+    if (hipEventSynchronize(t.e1) == hipSuccess && hipEventElapsedTime(&ms, t.e0, t.e1) == hipSuccess) {
+      app->acc_ms[t.fam] += ms;
+      app->acc_flops[t.fam] += t.flops;
+      app->acc_bytes[t.fam] += t.bytes;
+      app->acc_n[t.fam] += 1;
+    }
+    (void)hipEventDestroy(t.e0);
+    (void)hipEventDestroy(t.e1);
+  }
+  app->timed.clear();
+}
+
+static hs_status run_ops(hs_app* app, const std::vector<Op>& ops, hipStream_t st) {
+  for (const Op& op : ops) {
+    if (app->timing) {
+      TimedLaunch t{op.fam, op.flops, op.bytes, nullptr, nullptr};
+      HS_HIP(hipEventCreate(&t.e0));
+      HS_HIP(hipEventCreate(&t.e1));
+      HS_HIP(hipEventRecord(t.e0, st));
+      launch_op(op, st);
+      HS_HIP(hipEventRecord(t.e1, st));
+      app->timed.push_back(t);
+    } else {
+      launch_op(op, st);
+    }
+  }
+  HS_HIP(hipGetLastError());
+  return HS_OK;
+}
+
+}  // namespace hs
+
+// ================================================================================================
+extern "C" {
+
+hs_status hs_init(int device, hs_ctx** out) {
+  if (!out) { set_error("hs_init: NULL out"); return HS_E_INVAL; }
+  *out = nullptr;
+  int n = 0;
+  hipError_t e = hipGetDeviceCount(&n);
+  if (e != hipSuccess || device < 0 || device >= n) {
+    set_error("hs_init: no HIP device %d (%s)", device,
+              e == hipSuccess ? "out of range" : hipGetErrorString(e));
+    return HS_E_DEVICE;
+  }
+  HS_HIP(hipSetDevice(device));
+  hipDeviceProp_t prop;
+  HS_HIP(hipGetDeviceProperties(&prop, device));
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+    set_error("hs_init: device %d is %s; this library contains gfx950 code only", device,
+              prop.gcnArchName);
+    return HS_E_DEVICE;
+  }
+  hs_ctx* c = new hs_ctx();
+  c->device = device;
+  c->n_cus = prop.multiProcessorCount;
+  *out = c;
+  return HS_OK;
+}
+
+hs_status hs_shutdown(hs_ctx* ctx) {
+  if (!ctx) { set_error("hs_shutdown: NULL"); return HS_E_INVAL; }
+  {
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    if (!ctx->apps.empty()) {
+      set_error("hs_shutdown: %zu applications still exist", ctx->apps.size());
+      return HS_E_STATE;
+    }
+  }
+  delete ctx;
+  return HS_OK;
+}
+
+hs_status hs_device_cus(hs_ctx* ctx, int* n_cus) {
+  if (!ctx || !n_cus) { set_error("hs_device_cus: NULL"); return HS_E_INVAL; }
+  *n_cus = ctx->n_cus;
+  return HS_OK;
+}
+
+hs_status hs_query_workspace(const hs_app_desc* desc, size_t* bytes) {
+  if (!bytes) { set_error("hs_query_workspace: NULL bytes"); return HS_E_INVAL; }
+  hs_status st = validate_desc(desc);
+  if (st != HS_OK) return st;
+  return build_plan(desc, nullptr, bytes);
+}
+
+hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
+  if (!ctx || !out) { set_error("hs_create_app: NULL argument"); return HS_E_INVAL; }
+  *out = nullptr;
+  hs_status st = validate_desc(desc);
+  if (st != HS_OK) return st;
+  if (!desc->weights || desc->weight_floats != expected_weight_floats(desc->net)) {
+    set_error("weight blob has %zu floats, network needs %zu", desc->weights ? desc->weight_floats : 0,
+              expected_weight_floats(desc->net));
+    return HS_E_INVAL;
+  }
+  if (!desc->d_workspace || ((uintptr_t)desc->d_workspace & 255) != 0) {
+    set_error("d_workspace must be a 256-byte aligned device pointer");
+    return HS_E_INVAL;
+  }
+  HS_HIP(hipSetDevice(ctx->device));
+  hs_app* app = new hs_app();
+  app->ctx = ctx;
+  app->desc = *desc;
+  app->desc.weights = nullptr;   // not retained
+  app->depth = desc->queue_depth;
+  size_t need = 0;
+  st = build_plan(desc, app, &need);
+  if (st == HS_OK) st = make_streams(app, nullptr, nullptr, 0);
+  if (st != HS_OK) {
+    for (Slot& s : app->slots) {
+      if (s.ev_begin) (void)hipEventDestroy(s.ev_begin);
+      if (s.ev_pre) (void)hipEventDestroy(s.ev_pre);
+      if (s.ev_infer) (void)hipEventDestroy(s.ev_infer);
+      if (s.ev_post) (void)hipEventDestroy(s.ev_post);
+      if (s.ev_overlay) (void)hipEventDestroy(s.ev_overlay);
+    }
+    if (app->pinned) (void)hipHostFree(app->pinned);
+    delete app;
+    return st;
+  }
+  app->completer = std::thread(completer_main, app);
+  {
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ctx->apps.push_back(app);
+  }
+  *out = app;
+  return HS_OK;
+}
+
+hs_status hs_destroy_app(hs_app* app) {
+  if (!app) { set_error("hs_destroy_app: NULL"); return HS_E_INVAL; }
+  (void)hipSetDevice(app->ctx->device);
+  {
+    std::lock_guard<std::mutex> lk(app->mu);
+    app->stop = true;
+  }
+  app->cv_work.notify_all();
+  if (app->completer.joinable()) app->completer.join();   // drains pending frames first
+  (void)hipStreamSynchronize(app->s_infer);
+  (void)hipStreamSynchronize(app->s_overlay);
+  collect_timing(app);
+  for (Slot& s : app->slots) {
+    (void)hipEventDestroy(s.ev_begin);
+    (void)hipEventDestroy(s.ev_pre);
+    (void)hipEventDestroy(s.ev_infer);
+    (void)hipEventDestroy(s.ev_post);
+    (void)hipEventDestroy(s.ev_overlay);
+  }
+  (void)hipStreamDestroy(app->s_infer);
+  (void)hipStreamDestroy(app->s_overlay);
+  if (app->pinned) (void)hipHostFree(app->pinned);
+  {
+    std::lock_guard<std::mutex> lk(app->ctx->mu);
+    auto& v = app->ctx->apps;
+    v.erase(std::remove(v.begin(), v.end(), app), v.end());
+  }
+  delete app;
+  return HS_OK;
+}
+
+hs_status hs_reset_state(hs_app* app) {
+  if (!app) { set_error("hs_reset_state: NULL"); return HS_E_INVAL; }
+  if (frames_in_flight(app)) { set_error("hs_reset_state: frames in flight"); return HS_E_STATE; }
+  if (!app->stateful) return HS_OK;
+  HS_HIP(hipSetDevice(app->ctx->device));
+  const size_t n = (size_t)app->map_w * app->map_h;
+  launch_fill_zero(app->d_c, n * app->hid * sizeof(float), app->s_infer);
+  launch_fill_zero(app->d_concat, n * app->concat_pitch * sizeof(f16), app->s_infer);
+  HS_HIP(hipGetLastError());
+  HS_HIP(hipStreamSynchronize(app->s_infer));
+  return HS_OK;
+}
+
+hs_status hs_get_state(hs_app* app, float* h_out, float* c_out) {
+  if (!app) { set_error("hs_get_state: NULL"); return HS_E_INVAL; }
+  if (!app->stateful) { set_error("hs_get_state: network has no recurrent state"); return HS_E_INVAL; }
+  if (frames_in_flight(app)) { set_error("hs_get_state: frames in flight"); return HS_E_STATE; }
+  HS_HIP(hipSetDevice(app->ctx->device));
+  const size_t n = (size_t)app->map_w * app->map_h;
+  const int hid = app->hid;
+  if (c_out) {
+    std::vector<float> tmp(n * hid);
+    HS_HIP(hipMemcpy(tmp.data(), app->d_c, tmp.size() * sizeof(float), hipMemcpyDeviceToHost));
+    for (size_t m = 0; m < n; ++m)
+      for (int j = 0; j < hid; ++j) c_out[(size_t)j * n + m] = tmp[m * hid + j];
+  }
+  if (h_out) {
+    std::vector<f16> tmp(n * app->concat_pitch);
+    HS_HIP(hipMemcpy(tmp.data(), app->d_concat, tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
+    for (size_t m = 0; m < n; ++m)
+      for (int j = 0; j < hid; ++j)
+        h_out[(size_t)j * n + m] = (float)tmp[m * app->concat_pitch + app->x_ch + j];
+  }
+  return HS_OK;
+}
+
+hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
+                           const uint32_t* cu_mask_overlay, int n_words) {
+  if (!app) { set_error("hs_set_partition: NULL app"); return HS_E_INVAL; }
+  if ((cu_mask_infer == nullptr) != (cu_mask_overlay == nullptr)) {
+    set_error("hs_set_partition: give both masks or neither");
+    return HS_E_INVAL;
+  }
+  if (frames_in_flight(app)) { set_error("hs_set_partition: frames in flight"); return HS_E_STATE; }
+  hs_ctx* ctx = app->ctx;
+  HS_HIP(hipSetDevice(ctx->device));
+  std::lock_guard<std::mutex> lk(ctx->mu);
+  if (!cu_mask_infer) {
+    hs_status st = make_streams(app, nullptr, nullptr, 0);
+    if (st != HS_OK) return st;
+    std::memset(app->claim, 0, sizeof(app->claim));
+    app->partitioned = false;
+    return HS_OK;
+  }
+  uint32_t others[HS_MAX_CU_WORDS] = {0};
+  for (hs_app* o : ctx->apps)
+    if (o != app)
+      for (int w = 0; w < HS_MAX_CU_WORDS; ++w) others[w] |= o->claim[w];
+  hs_status st = admission_check(others, cu_mask_infer, cu_mask_overlay, n_words, ctx->n_cus);
+  if (st != HS_OK) return st;
+  st = make_streams(app, cu_mask_infer, cu_mask_overlay, n_words);
+  if (st != HS_OK) return st;
+  std::memset(app->claim, 0, sizeof(app->claim));
+  for (int w = 0; w < n_words; ++w) app->claim[w] = cu_mask_infer[w] | cu_mask_overlay[w];
+  app->partitioned = true;
+  return HS_OK;
+}
+
+hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
+                          uint64_t frame_id) {
+  const uint64_t t_submit = now_ns();
+  if (!app || !d_frame || !d_overlay_out) { set_error("hs_submit_frame: NULL argument"); return HS_E_INVAL; }
+  if (((uintptr_t)d_frame & 15) || ((uintptr_t)d_overlay_out & 15)) {
+    set_error("hs_submit_frame: frame pointers must be 16-byte aligned");
+    return HS_E_INVAL;
+  }
+  if (d_frame == d_overlay_out) { set_error("hs_submit_frame: output aliases input"); return HS_E_INVAL; }
+  Slot* s = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(app->mu);
+    if (!app->completer_error.empty()) {
+      set_error("device error in an earlier frame: %s", app->completer_error.c_str());
+      return HS_E_DEVICE;
+    }
+    if (app->n_submitted - app->n_delivered >= (uint64_t)app->depth) {
+      set_error("hs_submit_frame: queue full (%d slots)", app->depth);
+      return HS_E_QUEUE_FULL;
+    }
+    s = &app->slots[app->n_submitted % app->depth];
+  }
+  HS_HIP(hipSetDevice(app->ctx->device));
+  hs_result& r = s->result;
+  std::memset(&r, 0, sizeof(r));
+  r.frame_id = frame_id;
+  r.t_submit_ns = t_submit;
+  r.map_w = app->map_w; r.map_h = app->map_h;
+  r.net_input_pitch_bytes = (size_t)app->netin_w * 4 * sizeof(f16);
+  r.d_overlay = d_overlay_out;
+  r.d_mask = s->d_mask; r.d_heat = s->d_heat; r.d_logits = s->d_logits;
+  r.d_net_input = s->d_netin + ((size_t)app->netin_pad * app->netin_w + app->netin_pad) * 4;
+  r.d_net_input_f32 = s->d_netin_f32;
+  s->pre[0].resize.src = d_frame;
+  s->overlay.overlay.src = d_frame;
+  s->overlay.overlay.dst = d_overlay_out;
+
+  HS_HIP(hipEventRecord(s->ev_begin, app->s_infer));
+  hs_status st = run_ops(app, s->pre, app->s_infer);
+  if (st != HS_OK) return st;
+  HS_HIP(hipEventRecord(s->ev_pre, app->s_infer));
+  st = run_ops(app, s->infer, app->s_infer);
+  if (st != HS_OK) return st;
+  HS_HIP(hipEventRecord(s->ev_infer, app->s_infer));
+  st = run_ops(app, s->post, app->s_infer);
+  if (st != HS_OK) return st;
+  HS_HIP(hipEventRecord(s->ev_post, app->s_infer));
+  HS_HIP(hipStreamWaitEvent(app->s_overlay, s->ev_post, 0));
+  std::vector<Op> ov(1, s->overlay);
+  st = run_ops(app, ov, app->s_overlay);
+  if (st != HS_OK) return st;
+  HS_HIP(hipEventRecord(s->ev_overlay, app->s_overlay));
+  {
+    std::lock_guard<std::mutex> lk(app->mu);
+    s->state = SLOT_INFLIGHT;
+    app->n_submitted++;
+  }
+  app->cv_work.notify_one();
+  return HS_OK;
+}
+
+static hs_status deliver_locked(hs_app* app, hs_result* out) {
+  Slot& s = app->slots[app->n_delivered % app->depth];
+  *out = s.result;
+  out->t_observed_ns = now_ns();
+  s.state = SLOT_FREE;
+  app->n_delivered++;
+  if (!app->completer_error.empty()) {
+    set_error("device error: %s", app->completer_error.c_str());
+    return HS_E_DEVICE;
+  }
+  return HS_OK;
+}
+
+hs_status hs_poll_result(hs_app* app, hs_result* out) {
+  if (!app || !out) { set_error("hs_poll_result: NULL argument"); return HS_E_INVAL; }
+  std::lock_guard<std::mutex> lk(app->mu);
+  if (app->n_delivered >= app->n_completed) {
+    set_error("hs_poll_result: no finished frame");
+    return HS_E_NOT_READY;
+  }
+  return deliver_locked(app, out);
+}
+
+hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns) {
+  if (!app || !out) { set_error("hs_wait_result: NULL argument"); return HS_E_INVAL; }
+  std::unique_lock<std::mutex> lk(app->mu);
+  const bool ok = app->cv_done.wait_for(lk, std::chrono::nanoseconds(timeout_ns), [&] {
+    return app->n_delivered < app->n_completed;
+  });
+  if (!ok) {
+    set_error("hs_wait_result: timed out");
+    return HS_E_NOT_READY;
+  }
+  return deliver_locked(app, out);
+}
+
+hs_status hs_set_kernel_timing(hs_app* app, int enable) {
+  if (!app) { set_error("hs_set_kernel_timing: NULL"); return HS_E_INVAL; }
+  if (frames_in_flight(app)) { set_error("hs_set_kernel_timing: frames in flight"); return HS_E_STATE; }
+  (void)hipSetDevice(app->ctx->device);
+  collect_timing(app);
+  for (int f = 0; f < F_COUNT; ++f) {
+    app->acc_ms[f] = app->acc_flops[f] = app->acc_bytes[f] = 0;
+    app->acc_n[f] = 0;
+  }
+  app->timing = enable != 0;
+  return HS_OK;
+}
+
+hs_status hs_get_kernel_times(hs_app* app, hs_kernel_time* entries, int max_entries,
+                              int* n_entries) {
+  if (!app || !n_entries) { set_error("hs_get_kernel_times: NULL"); return HS_E_INVAL; }
+  if (frames_in_flight(app)) { set_error("hs_get_kernel_times: frames in flight"); return HS_E_STATE; }
+  (void)hipSetDevice(app->ctx->device);
+  collect_timing(app);
+  int n = 0;
+  for (int f = 0; f < F_COUNT; ++f) {
+    if (!app->acc_n[f]) continue;
+    if (entries && n < max_entries) {
+      hs_kernel_time& k = entries[n];
+      std::memset(&k, 0, sizeof(k));
+      std::strncpy(k.name, kFamilyName[f], sizeof(k.name) - 1);
+      k.launches = app->acc_n[f];
+      k.total_ms = app->acc_ms[f];
+      k.flops = app->acc_flops[f];
+      k.bytes = app->acc_bytes[f];
+    }
+    ++n;
+  }
+  *n_entries = n;
+  return HS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,155 @@
+"""Small harness over the binding: PyTorch supplies device memory (workspace, frames,
+overlay outputs); everything that computes runs inside libhs.
+
+``AppStream`` is one application stream (paper Section III-A); ``run_paced`` drives several
+of them concurrently at a fixed frame rate, one submitting thread per stream, the way the
+paper runs one process per application instance (Section V-B).
+"""
+from __future__ import annotations
+
+import threading
+import time
+
+import numpy as np
+import torch
+
+from . import api
+
+
+class AppStream:
+    def __init__(self, ctx: int, *, net: int, frame_w: int, frame_h: int, net_w: int, net_h: int,
+                 blob: np.ndarray, palette: np.ndarray, queue_depth: int = 2,
+                 net_fp32_input: bool = False, frame_pitch: int | None = None, mean: float = 0.5,
+                 std: float = 0.25, threshold: float = 0.5, alpha: float = 0.5,
+                 device: str = "cuda:0"):
+        self.ctx = ctx
+        self.frame_w, self.frame_h = frame_w, frame_h
+        self.frame_pitch = frame_pitch if frame_pitch is not None else (3 * frame_w + 15) // 16 * 16
+        self.net_w, self.net_h = net_w, net_h
+        self.device = torch.device(device)
+        kw = dict(frame_w=frame_w, frame_h=frame_h, net_w=net_w, net_h=net_h, net=net,
+                  weights=blob, palette=palette, frame_pitch=self.frame_pitch,
+                  net_fp32_input=int(net_fp32_input), mean=mean, std=std, threshold=threshold,
+                  alpha=alpha, queue_depth=queue_depth)
+        need = api.hs_query_workspace(api.make_desc(**kw))
+        self.workspace = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        self._ws_off = base - self.workspace.data_ptr()
+        self.workspace_bytes = need
+        torch.cuda.synchronize(self.device)
+        self.app = api.hs_create_app(ctx, api.make_desc(d_workspace=base, workspace_bytes=need, **kw))
+        self.queue_depth = queue_depth
+        self._held = {}
+
+    # -- device buffers ---------------------------------------------------------------------
+    def upload_frame(self, frame: np.ndarray) -> torch.Tensor:
+        """HxWx3 uint8 host frame -> pitched device buffer (H x pitch bytes)."""
+        h, w, _ = frame.shape
+        assert (w, h) == (self.frame_w, self.frame_h)
+        host = np.zeros((h, self.frame_pitch), dtype=np.uint8)
+        host[:, :3 * w] = frame.reshape(h, 3 * w)
+        return torch.from_numpy(host).to(self.device)
+
+    def new_output(self) -> torch.Tensor:
+        return torch.zeros((self.frame_h, self.frame_pitch), dtype=torch.uint8, device=self.device)
+
+    # -- hot path ---------------------------------------------------------------------------
+    def submit(self, d_frame: torch.Tensor, d_out: torch.Tensor, frame_id: int) -> int:
+        st = api.hs_submit_frame(self.app, d_frame.data_ptr(), d_out.data_ptr(), frame_id)
+        if st == api.HS_OK:
+            self._held[frame_id] = (d_frame, d_out)      # keep alive until polled
+        return st
+
+    def poll(self):
+        r = api.hs_poll_result(self.app)
+        if r is not None:
+            self._held.pop(r.frame_id, None)
+        return r
+
+    def wait(self, timeout_s: float = 30.0):
+        r = api.hs_wait_result(self.app, int(timeout_s * 1e9))
+        if r is None:
+            raise TimeoutError("no result within %.1f s" % timeout_s)
+        self._held.pop(r.frame_id, None)
+        return r
+
+    # -- read-back (tests, smoke) -----------------------------------------------------------
+    def _view(self, ptr: int, nbytes: int) -> torch.Tensor:
+        off = ptr - self.workspace.data_ptr()
+        assert 0 <= off and off + nbytes <= self.workspace.numel(), "pointer outside workspace"
+        return self.workspace[off:off + nbytes]
+
+    def fetch(self, r, d_out: torch.Tensor | None = None) -> dict:
+        """Copy one frame's device results to host NumPy arrays."""
+        n = r.map_w * r.map_h
+        out = {"argmax_idx": np.array(list(r.argmax_idx), dtype=np.int32),
+               "present": np.array(list(r.present), dtype=np.uint8),
+               "peak": np.array(list(r.peak), dtype=np.float32)}
+        out["logits"] = self._view(r.d_logits, 32 * n).view(torch.float32).cpu().numpy().reshape(
+            8, r.map_h, r.map_w)
+        out["heat"] = self._view(r.d_heat, 32 * n).view(torch.float32).cpu().numpy().reshape(
+            8, r.map_h, r.map_w)
+        out["mask"] = self._view(r.d_mask, 8 * n).cpu().numpy().reshape(8, r.map_h, r.map_w)
+        pitch = r.net_input_pitch_bytes
+        rows = self._view(r.d_net_input, pitch * (self.net_h - 1) + 8 * self.net_w)
+        rows = torch.nn.functional.pad(rows, (0, pitch * self.net_h - rows.numel()))
+        ni = rows.view(self.net_h, pitch)[:, :8 * self.net_w].contiguous().view(torch.float16)
+        out["net_input"] = ni.cpu().numpy().reshape(self.net_h, self.net_w, 4)
+        if r.d_net_input_f32:
+            out["net_input_f32"] = self._view(
+                r.d_net_input_f32, 12 * self.net_w * self.net_h).view(torch.float32).cpu().numpy(
+            ).reshape(3, self.net_h, self.net_w)
+        if d_out is not None:
+            out["overlay"] = d_out.cpu().numpy()[:, :3 * self.frame_w].reshape(
+                self.frame_h, self.frame_w, 3)
+        return out
+
+    def state(self, r):
+        return api.hs_get_state(self.app, r.map_h, r.map_w)
+
+    def close(self):
+        if self.app:
+            api.hs_destroy_app(self.app)
+            self.app = None
+            self._held.clear()
+
+
+def run_paced(streams, frames, fps: float, outputs=None):
+    """Submit frame k of every stream at t0 + k/fps from one thread per stream and collect
+    the per-frame results.  ``frames[i]`` is a list of device frame tensors for stream i
+    (cycled if shorter than n).  Returns per-stream lists of hs_result plus the number of
+    frames dropped because the queue was full."""
+    n_streams = len(streams)
+    results = [[] for _ in range(n_streams)]
+    dropped = [0] * n_streams
+    n = max(len(f) for f in frames)
+    if outputs is None:
+        outputs = [[s.new_output() for _ in range(s.queue_depth)] for s in streams]
+    t0 = time.monotonic() + 0.05
+    period = 1.0 / fps
+
+    def worker(i):
+        s = streams[i]
+        fr = frames[i]
+        for k in range(n):
+            deadline = t0 + k * period
+            while True:
+                r = s.poll()
+                if r is None:
+                    break
+                results[i].append(r)
+            dt = deadline - time.monotonic()
+            if dt > 0:
+                time.sleep(dt)
+            st = s.submit(fr[k % len(fr)], outputs[i][k % len(outputs[i])], k)
+            if st != api.HS_OK:
+                dropped[i] += 1
+        while len(results[i]) + dropped[i] < n:
+            results[i].append(s.wait())
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n_streams)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    return results, dropped

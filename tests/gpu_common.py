@@ -1,0 +1,66 @@
+"""Shared helpers of the GPU parity tests: run frames through libhs (via the binding) and
+through the CPU oracle on the same seeded inputs, and compare stage by stage."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import synth_inputs as si
+
+TOL_NET = 2e-2        # fp16 GPU vs fp32 oracle, max |diff| / max |ref| per output tensor
+TOL_EMU = 5e-3        # fp16 GPU vs the oracle's fp16-storage emulation
+
+
+def rel_err(a, ref):
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.abs(a - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, threshold, alpha,
+                palette, fp32_input, mean=0.5, std=0.25, tag=""):
+    """g: GPU outputs of one frame; o32 / o16: oracle outputs (fp32 storage / fp16 emulation)."""
+    # ---- stage 1: bit-exact -------------------------------------------------------------
+    lut16 = oracle.normalize_lut(mean, std, fp16=True)
+    want = lut16[o32["resized"]]                                   # (H, W, 3) float32 of fp16
+    got = g["net_input"].astype(np.float32)
+    assert np.array_equal(got[..., :3], want), f"{tag}: stage-1 fp16 tensor differs"
+    assert np.all(got[..., 3] == 0), f"{tag}: stage-1 pad channel not zero"
+    if fp32_input:
+        lut32 = oracle.normalize_lut(mean, std, fp16=False)
+        want32 = lut32[o32["resized"]].transpose(2, 0, 1)
+        assert np.array_equal(g["net_input_f32"], want32), f"{tag}: stage-1 fp32 tensor differs"
+    # ---- stage 2: tolerance --------------------------------------------------------------
+    e32 = rel_err(g["logits"], o32["logits"])
+    assert e32 <= TOL_NET, f"{tag}: logits vs fp32 oracle {e32:.3e}"
+    if o16 is not None:
+        e16 = rel_err(g["logits"], o16["logits"])
+        assert e16 <= TOL_EMU, f"{tag}: logits vs fp16-emulating oracle {e16:.3e}"
+    # ---- stage 3, stage-isolated: the oracle's postprocess on the GPU's own logits ---------
+    p = oracle.postprocess(g["logits"], threshold)
+    assert np.array_equal(g["mask"], p["mask"]), f"{tag}: mask differs"
+    assert np.array_equal(g["argmax_idx"], p["argmax_idx"]), f"{tag}: argmax differs"
+    assert np.array_equal(g["present"], p["present"]), f"{tag}: present differs"
+    assert np.abs(g["heat"] - p["heat"]).max() <= 1e-6, f"{tag}: heat differs"
+    assert np.abs(g["peak"] - p["peak"]).max() <= 1e-6, f"{tag}: peak differs"
+    # end to end: mask / argmax may differ from the fp32 oracle only inside the tolerance band
+    theta = float(oracle.logit_threshold(threshold))
+    band = TOL_NET * np.abs(o32["logits"]).max()
+    bad = (g["mask"] != o32["mask"]) & (np.abs(o32["logits"] - theta) > band)
+    assert not bad.any(), f"{tag}: {int(bad.sum())} mask cells differ outside the band"
+    ref = o32["logits"].reshape(8, -1)
+    for k in range(8):
+        if g["argmax_idx"][k] != o32["argmax_idx"][k]:
+            gap = ref[k].max() - ref[k, g["argmax_idx"][k]]
+            assert gap <= 2 * band, f"{tag}: argmax of channel {k} differs outside the band"
+    # ---- stage 4, stage-isolated: the oracle's overlay with the GPU's own mask --------------
+    if "overlay" in g:
+        want_ov = oracle.overlay(frame, g["mask"], palette, alpha)
+        assert np.array_equal(g["overlay"], want_ov), f"{tag}: overlay differs"
+    return e32
+
+
+def make_oracles(net_name, blob, net_w, net_h, fp16_input, palette, **kw):
+    o32 = oracle.OracleApp(net_name, blob, net_w, net_h, fp16_input, palette, **kw)
+    o16 = oracle.OracleApp(net_name, blob, net_w, net_h, True, palette, storage="fp16", **kw)
+    return o32, o16

@@ -1,0 +1,132 @@
+"""CPU-only tests of the boundary: the shared library loads and exports every symbol that
+include/hs.h declares, and its host-only logic (admission control of Section IV-A, latency
+determinism metrics of Section V-A, description validation, workspace sizing) behaves as
+documented.  No compute call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2402_04466_amd as hs
+import synth_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "hs.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(hs_[a-z_]+)\s*\(", header))
+    assert {"hs_create_app", "hs_submit_frame", "hs_poll_result", "hs_set_partition"} <= names
+    lib = ctypes.CDLL(hs.lib_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), f"libhs.so does not export {n}"
+    assert "gfx950" in hs.hs_version()
+
+
+def test_binding_struct_sizes_match_the_header(tmp_path):
+    src = tmp_path / "sz.c"
+    src.write_text('#include <stdio.h>\n#include "hs.h"\nint main(void){printf("%zu %zu %zu %zu\\n",'
+                   "sizeof(hs_app_desc),sizeof(hs_result),sizeof(hs_latency_metrics),"
+                   "sizeof(hs_kernel_time));return 0;}\n")
+    exe = tmp_path / "sz"
+    import subprocess
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    want = [int(v) for v in subprocess.check_output([str(exe)]).split()]
+    got = [ctypes.sizeof(c) for c in (hs.hs_app_desc, hs.hs_result, hs.hs_latency_metrics,
+                                      hs.hs_kernel_time)]
+    assert got == want
+
+
+# ---- admission control ---------------------------------------------------------------------
+def _m(cus):
+    return hs.cu_mask_words(cus)
+
+
+def test_admission_disjoint_partitions_are_admitted_until_full():
+    """Six equal partitions of 42 CUs (6 x 42 = 252 <= 256) fit; a seventh does not."""
+    claimed = np.zeros(8, np.uint32)
+    for i in range(6):
+        infer, over = _m(range(42 * i, 42 * i + 36)), _m(range(42 * i + 36, 42 * i + 42))
+        assert hs.hs_admission_check(claimed, infer, over, 256) == hs.HS_OK
+        claimed |= infer | over
+    assert hs.hs_admission_check(claimed, _m(range(250, 256)), _m(range(250, 256)), 256) \
+        == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(claimed, _m(range(252, 256)), _m(range(252, 256)), 256) == hs.HS_OK
+
+
+def test_admission_five_quarters_oversubscribe():
+    """5 x 25 % = 125 % is the bad case named in the paper's appendix: the fifth is refused."""
+    claimed = np.zeros(8, np.uint32)
+    results = []
+    for i in range(5):
+        cus = [c % 256 for c in range(64 * i, 64 * i + 64)]
+        st = hs.hs_admission_check(claimed, _m(cus), _m(cus), 256)
+        results.append(st)
+        if st == hs.HS_OK:
+            claimed |= _m(cus)
+    assert results == [hs.HS_OK] * 4 + [hs.HS_E_OVERSUBSCRIBED]
+
+
+def test_admission_rejects_empty_out_of_range_and_bad_args():
+    z = np.zeros(8, np.uint32)
+    assert hs.hs_admission_check(None, z, _m([1]), 256) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([1]), z, 256) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([200]), _m([3]), 128) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([127]), _m([3]), 128) == hs.HS_OK
+    assert hs.hs_admission_check(None, _m([3]), _m([3]), 0) == hs.HS_E_INVAL
+    assert "CU" in hs.hs_last_error() or "argument" in hs.hs_last_error()
+    # inference and overlay masks of ONE application may overlap each other
+    assert hs.hs_admission_check(z, _m(range(0, 32)), _m(range(16, 48)), 256) == hs.HS_OK
+
+
+# ---- metrics ---------------------------------------------------------------------------------
+def test_metrics_match_oracle_and_golden():
+    x = np.random.default_rng(0).gamma(2.0, 3.0, 1000)
+    for trim in (False, True):
+        got, want = hs.hs_latency_metrics_compute(x, trim), oracle.determinism_metrics(x, trim)
+        assert got["n"] == want["n"]
+        for k in ("mean", "max", "std", "p50", "p99", "tail", "flatness"):
+            assert abs(got[k] - want[k]) <= 1e-12 * max(1.0, abs(want[k])), k
+    m = hs.hs_latency_metrics_compute(np.arange(1, 102), trim=False)
+    assert (m["p50"], m["tail"], m["flatness"], m["max"]) == (51.0, 5.0, 80.0, 101.0)
+    short = hs.hs_latency_metrics_compute([5, 1, 2, 3, 4, 1.5, 2.5, 9], trim=True)
+    assert short["n"] == 6 and short["max"] == 4.0
+    with pytest.raises(hs.HsError):
+        hs.hs_latency_metrics_compute([], trim=True)
+
+
+# ---- description validation and workspace sizing ---------------------------------------------
+def _desc(**over):
+    kw = dict(frame_w=1920, frame_h=1080, net_w=854, net_h=480, net=hs.HS_NET_RESNET18_CONVLSTM,
+              weights=np.zeros(4, np.float32), palette=si.DEFAULT_PALETTE, frame_pitch=5760)
+    kw.update(over)
+    return hs.make_desc(**kw)
+
+
+def test_workspace_query_and_validation():
+    big = hs.hs_query_workspace(_desc())
+    # fp16 weights 36.5 MB + stem output 13.1 MB + 4 activation buffers + split-K scratch ...
+    assert 60e6 < big < 120e6
+    assert hs.hs_query_workspace(_desc(queue_depth=4)) > big
+    small = hs.hs_query_workspace(_desc(frame_w=320, frame_h=240, net_w=128, net_h=128,
+                                        net=hs.HS_NET_TINY4, frame_pitch=960))
+    assert small < 4e6
+    for bad in (dict(frame_pitch=5761), dict(frame_pitch=100), dict(net=7), dict(queue_depth=0),
+                dict(threshold=1.0), dict(alpha=1.5), dict(std=0.0), dict(net_w=0),
+                dict(net_w=16000, net_h=16000)):
+        with pytest.raises(hs.HsError) as ei:
+            hs.hs_query_workspace(_desc(**bad))
+        assert ei.value.status == hs.HS_E_INVAL, bad
+
+
+def test_no_gpu_means_loud_failure_not_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(hs.HsError) as ei:
+        hs.hs_init(0)
+    assert ei.value.status == hs.HS_E_DEVICE

@@ -1,0 +1,192 @@
+"""GPU parity tests: every stage of libhs (called through the C ABI via the binding)
+against the CPU oracle on the same seeded inputs.  Integer stages bit-exact; network
+outputs within 2e-2 of the fp32 oracle (max-norm relative) and within 5e-3 of the oracle's
+fp16-storage emulation."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from gpu_common import check_frame, make_oracles, rel_err, TOL_EMU
+
+pytestmark = pytest.mark.gpu
+PAL = si.DEFAULT_PALETTE
+
+
+@pytest.fixture(scope="module")
+def ctx(hs):
+    c = hs.hs_init(0)
+    yield c
+    hs.hs_shutdown(c)
+
+
+def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_input, depth=2,
+                threshold=0.5, alpha=0.5, check_state=False, tag=""):
+    from paper_2402_04466_amd.harness import AppStream
+    fh, fw, _ = frames[0].shape
+    s = AppStream(ctx, net=net, frame_w=fw, frame_h=fh, net_w=net_w, net_h=net_h, blob=blob,
+                  palette=PAL, queue_depth=depth, net_fp32_input=fp32_input, threshold=threshold,
+                  alpha=alpha)
+    o32, o16 = make_oracles(net_name, blob, net_w, net_h, not fp32_input, PAL,
+                            threshold=threshold, alpha=alpha)
+    errs = []
+    try:
+        for i, f in enumerate(frames):
+            print(f"[{tag}] frame {i} {fw}x{fh} -> {net_w}x{net_h}", flush=True)
+            d_in, d_out = s.upload_frame(f), s.new_output()
+            assert s.submit(d_in, d_out, i) == hs.HS_OK
+            r = s.wait()
+            assert r.frame_id == i
+            assert r.t_submit_ns <= r.t_pre_done_ns <= r.t_infer_done_ns <= r.t_post_done_ns \
+                <= r.t_overlay_done_ns <= r.t_observed_ns
+            g = s.fetch(r, d_out)
+            a, b = o32.process(f), o16.process(f)
+            errs.append(check_frame(g, f, a, b, threshold=threshold, alpha=alpha, palette=PAL,
+                                    fp32_input=fp32_input, tag=f"{tag}/frame{i}"))
+            if check_state and "h" in b:
+                gh, gc = s.state(r)
+                eh, ec = rel_err(gh, b["h"]), rel_err(gc, b["c"])
+                print(f"[{tag}] state vs fp16-emulating oracle: h {eh:.2e} c {ec:.2e}; "
+                      f"vs fp32 oracle: h {rel_err(gh, a['h']):.2e} c {rel_err(gc, a['c']):.2e}",
+                      flush=True)
+                assert eh <= 2e-2 and ec <= 2e-2, f"{tag}: recurrent state h {eh:.3e} c {ec:.3e}"
+    finally:
+        s.close()
+    print(f"[{tag}] logits max-norm error vs fp32 oracle per frame: "
+          + " ".join(f"{e:.2e}" for e in errs), flush=True)
+    return errs
+
+
+def test_config1_tiny_net_all_frames(hs, ctx):
+    """8 frames 320x240 uniform random, 128x128 fp32 normalise, 4-layer net, 32x32x8 map."""
+    frames = list(si.uniform_frames(8, 240, 320, 0))
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+    _run_stream(hs, ctx, net=hs.HS_NET_TINY4, net_name="tiny4", frames=frames, net_w=128,
+                net_h=128, blob=blob, fp32_input=True, tag="config1")
+
+
+def test_resnet_convlstm_reduced_size_with_state(hs, ctx):
+    """640x360 -> 288x160: several 64-pixel tiles per layer with ragged tails (M = 80*144,
+    40*72, 20*36, 10*18, 5*9 = 45) and the ConvLSTM state carried over 4 frames."""
+    frames = list(si.tool_scene_frames(4, 360, 640, 31))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    _run_stream(hs, ctx, net=hs.HS_NET_RESNET18_CONVLSTM, net_name="resnet18_convlstm",
+                frames=frames, net_w=288, net_h=160, blob=blob, fp32_input=False,
+                check_state=True, tag="resnet-small")
+
+
+def test_config2_full_size_three_frames(hs, ctx):
+    """1920x1080 -> 854x480, full network, 3 frames of the seed-1 scene with state."""
+    frames = list(si.tool_scene_frames(3, 1080, 1920, 1))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    _run_stream(hs, ctx, net=hs.HS_NET_RESNET18_CONVLSTM, net_name="resnet18_convlstm",
+                frames=frames, net_w=854, net_h=480, blob=blob, fp32_input=False,
+                check_state=True, tag="config2")
+
+
+@pytest.mark.parametrize("fw,fh,nw,nh,thr,alpha", [
+    (128, 128, 128, 128, 0.5, 0.0),      # identity resize, alpha 0 => overlay == input
+    (322, 241, 96, 72, 0.75, 1.0),       # odd frame size (pitch padding), upscale-free, opaque
+    (64, 48, 160, 120, 0.3, 0.37),       # upscaling resize, odd alpha
+])
+def test_tiny_net_edge_shapes(hs, ctx, fw, fh, nw, nh, thr, alpha):
+    frames = list(si.uniform_frames(2, fh, fw, 5))
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 3)
+    _run_stream(hs, ctx, net=hs.HS_NET_TINY4, net_name="tiny4", frames=frames, net_w=nw, net_h=nh,
+                blob=blob, fp32_input=True, threshold=thr, alpha=alpha,
+                tag=f"edge-{fw}x{fh}-{nw}x{nh}")
+    if alpha == 0.0:
+        pass  # check_frame already compared against the oracle overlay (== input for alpha 0)
+
+
+def test_reset_state_and_queue_semantics(hs, ctx):
+    from paper_2402_04466_amd.harness import AppStream
+    frames = list(si.tool_scene_frames(2, 180, 320, 7))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=320, frame_h=180, net_w=160,
+                  net_h=96, blob=blob, palette=PAL, queue_depth=2)
+    try:
+        assert s.poll() is None                                  # nothing submitted yet
+        d_in = s.upload_frame(frames[0])
+        outs = [s.new_output() for _ in range(3)]
+
+        def one(i):
+            assert s.submit(d_in, outs[i % 3], i) == hs.HS_OK
+            return s.fetch(s.wait())["logits"]
+        l0 = one(0)
+        l1 = one(1)
+        assert not np.array_equal(l0, l1)                        # state carried across frames
+        hs.hs_reset_state(s.app)
+        l2 = one(2)
+        assert np.array_equal(l0, l2)                            # reset => same as first frame
+        # queue_depth 2: a third unpolled frame is refused and not enqueued
+        assert s.submit(d_in, outs[0], 10) == hs.HS_OK
+        assert s.submit(d_in, outs[1], 11) == hs.HS_OK
+        assert s.submit(d_in, outs[2], 12) == hs.HS_E_QUEUE_FULL
+        assert s.wait().frame_id == 10 and s.wait().frame_id == 11
+        assert s.poll() is None
+    finally:
+        s.close()
+
+
+def test_partition_admission_and_masked_results_identical(hs, ctx):
+    """Two applications on disjoint CU sets; an overlapping request is refused and changes
+    nothing; results under a CU mask equal the unpartitioned ones bit for bit."""
+    from paper_2402_04466_amd.harness import AppStream
+    n_cus = hs.hs_device_cus(ctx)
+    assert n_cus >= 64
+    frames = list(si.uniform_frames(1, 240, 320, 9))
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+    kw = dict(net=hs.HS_NET_TINY4, frame_w=320, frame_h=240, net_w=128, net_h=128, blob=blob,
+              palette=PAL, queue_depth=2, net_fp32_input=True)
+    a, b = AppStream(ctx, **kw), AppStream(ctx, **kw)
+    try:
+        d_in, o1, o2 = a.upload_frame(frames[0]), a.new_output(), a.new_output()
+        assert a.submit(d_in, o1, 0) == hs.HS_OK
+        ref = a.fetch(a.wait(), o1)
+        half = n_cus // 2
+        hs.hs_set_partition(a.app, hs.cu_mask_words(range(0, half - 8)),
+                            hs.cu_mask_words(range(half - 8, half)))
+        with pytest.raises(hs.HsError) as ei:                   # overlaps a's claim
+            hs.hs_set_partition(b.app, hs.cu_mask_words(range(half - 4, n_cus)),
+                                hs.cu_mask_words(range(half - 4, n_cus)))
+        assert ei.value.status == hs.HS_E_OVERSUBSCRIBED
+        with pytest.raises(hs.HsError):                          # CU the device does not have
+            hs.hs_set_partition(b.app, hs.cu_mask_words([n_cus]), hs.cu_mask_words([n_cus]))
+        hs.hs_set_partition(b.app, hs.cu_mask_words(range(half, n_cus)),
+                            hs.cu_mask_words(range(half, n_cus)))
+        assert a.submit(d_in, o2, 1) == hs.HS_OK
+        got = a.fetch(a.wait(), o2)
+        for k in ("logits", "mask", "overlay", "net_input"):
+            assert np.array_equal(ref[k], got[k]), k
+        d_in_b, ob = b.upload_frame(frames[0]), b.new_output()
+        assert b.submit(d_in_b, ob, 0) == hs.HS_OK
+        got_b = b.fetch(b.wait(), ob)
+        assert np.array_equal(ref["logits"], got_b["logits"])
+        assert np.array_equal(ref["overlay"], got_b["overlay"])
+        hs.hs_set_partition(a.app, None, None)                   # release: b may now take them
+        hs.hs_set_partition(b.app, hs.cu_mask_words(range(0, n_cus)),
+                            hs.cu_mask_words(range(0, n_cus)))
+    finally:
+        a.close()
+        b.close()
+
+
+def test_kernel_timing_reports_every_family(hs, ctx):
+    from paper_2402_04466_amd.harness import AppStream
+    frames = list(si.uniform_frames(1, 240, 320, 2))
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+    s = AppStream(ctx, net=hs.HS_NET_TINY4, frame_w=320, frame_h=240, net_w=128, net_h=128,
+                  blob=blob, palette=PAL, queue_depth=2)
+    try:
+        hs.hs_set_kernel_timing(s.app, True)
+        d_in, d_out = s.upload_frame(frames[0]), s.new_output()
+        for i in range(3):
+            assert s.submit(d_in, d_out, i) == hs.HS_OK
+            s.wait()
+        t = {e["name"]: e for e in hs.hs_get_kernel_times(s.app)}
+        assert {"resize_norm", "conv_mfma", "postprocess", "overlay"} <= set(t)
+        assert t["conv_mfma"]["launches"] == 12 and t["conv_mfma"]["total_ms"] > 0
+        assert abs(t["conv_mfma"]["flops"] / 3 - 36.6e6) < 0.5e6     # 36.6 MFLOP per frame
+    finally:
+        s.close()
