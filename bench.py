@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-frame tool-tracking hot path on one MI355X.
+
+A step is one frame through all four stages (format conversion + resize, ResNet-18-style
+backbone + ConvLSTM + head on fp16 MFMA, postprocess, overlay) of one application stream.
+Default workload: one stream of 1920x1080 frames resized to 854x480 (the configuration
+the headline metric is quoted on).  Frames are synthetic and already resident in HBM when
+the timed region starts.
+
+Prints ONE JSON line: aggregate frames/s over the timed steps, the per-frame end-to-end
+latency determinism metrics of a paced (fixed frame-rate) run, the roofline of the
+dominant kernel measured with HIP events on its own stream, and the CPU oracle timed on
+the host cores of this machine.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import threading
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP16_TFLOPS = 2500.0   # MI355X dense fp16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--streams", type=int, default=1, help="concurrent application streams")
+    ap.add_argument("--fps", type=float, default=60.0, help="pacing of the latency run")
+    ap.add_argument("--partition", choices=["none", "equal"], default="none",
+                    help="equal: disjoint CU-masked partitions, inference/overlay split")
+    ap.add_argument("--paced-frames", type=int, default=60)
+    ap.add_argument("--distinct-frames", type=int, default=8)
+    ap.add_argument("--queue-depth", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-frames", type=int, default=6)
+    return ap.parse_args()
+
+
+def equal_partitions(n_cus: int, n_streams: int, overlay_cus: int = 6, spare: int = 4):
+    """n_streams disjoint CU sets of equal size; inside each, the last overlay_cus CUs
+    serve the overlay stream and the rest the inference stream; `spare` CUs stay unclaimed
+    (the paper's appendix recommends leaving headroom)."""
+    per = (n_cus - spare) // n_streams
+    parts = []
+    for i in range(n_streams):
+        cus = list(range(i * per, (i + 1) * per))
+        parts.append((cus[:-overlay_cus], cus[-overlay_cus:]))
+    return parts
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (streams would "
+              "shard one application per GPU with no communication); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2402_04466_amd as hs
+    from paper_2402_04466_amd.harness import AppStream, run_paced
+    import synth_inputs as si
+
+    FW, FH, NW, NH = 1920, 1080, 854, 480
+    ctx = hs.hs_init(0)
+    n_cus = hs.hs_device_cus(ctx)
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    streams, frames = [], []
+    for i in range(args.streams):
+        s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW,
+                      net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
+                      queue_depth=args.queue_depth)
+        streams.append(s)
+        seed = 1 if args.streams == 1 else 2 + i
+        frames.append([s.upload_frame(f)
+                       for f in si.tool_scene_frames(args.distinct_frames, FH, FW, seed)])
+    if args.partition == "equal":
+        for s, (ci, co) in zip(streams, equal_partitions(n_cus, args.streams)):
+            hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+    outs = [[s.new_output() for _ in range(args.queue_depth)] for s in streams]
+    torch.cuda.synchronize()
+
+    def run_back_to_back(n_frames: int):
+        """Every stream submits n_frames as fast as its queue allows; returns elapsed s."""
+        def worker(i):
+            s, fr, ou = streams[i], frames[i], outs[i]
+            done = 0
+            for k in range(n_frames):
+                while s.submit(fr[k % len(fr)], ou[k % len(ou)], k) != hs.HS_OK:
+                    s.wait()
+                    done += 1
+            while done < n_frames:
+                s.wait()
+                done += 1
+        th = [threading.Thread(target=worker, args=(i,)) for i in range(len(streams))]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in th:
+            t.start()
+        for t in th:
+            t.join()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    # ---- throughput: W warm-up steps, then exactly K timed steps per stream ---------------
+    run_back_to_back(args.warmup)
+    elapsed = run_back_to_back(args.steps)
+    total_frames = args.steps * args.streams
+    fps = total_frames / elapsed
+
+    # ---- latency determinism at a fixed frame rate (paper Section V-A metrics) -------------
+    for s in streams:
+        hs.hs_reset_state(s.app)
+    paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
+             for f in frames]
+    results, dropped = run_paced(streams, paced, args.fps, outs)
+    lat_ms = []
+    for rs in results:
+        per = [(r.t_overlay_done_ns - r.t_submit_ns) / 1e6 for r in rs]
+        t = min(10, len(per) // 6)
+        lat_ms.extend(per[t:len(per) - t])       # trim each stream's warm-up / cool-down
+    m = hs.hs_latency_metrics_compute(lat_ms, trim=False)
+    stage_ms = {}
+    for name, a, b in (("pre", "t_submit_ns", "t_pre_done_ns"),
+                       ("infer", "t_pre_done_ns", "t_infer_done_ns"),
+                       ("post", "t_infer_done_ns", "t_post_done_ns"),
+                       ("overlay", "t_post_done_ns", "t_overlay_done_ns")):
+        v = [(getattr(r, b) - getattr(r, a)) / 1e6 for rs in results for r in rs]
+        stage_ms[name] = round(float(np.median(v)), 4)
+
+    # ---- roofline of the dominant kernel: HIP events around every launch -------------------
+    s0 = streams[0]
+    hs.hs_set_kernel_timing(s0.app, True)
+    n_prof = 20
+    for k in range(n_prof):
+        assert s0.submit(frames[0][k % len(frames[0])], outs[0][k % len(outs[0])], k) == hs.HS_OK
+        s0.wait()
+    kt = hs.hs_get_kernel_times(s0.app)
+    hs.hs_set_kernel_timing(s0.app, False)
+    dom = max(kt, key=lambda e: e["total_ms"])
+    if dom["flops"] > 0:
+        ach = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_FP16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_FP16_TFLOPS, 4), "traffic": None}
+    else:
+        ach = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    roof["kernel"] = dom["name"]
+    roof["avg_launch_us"] = round(dom["total_ms"] * 1e3 / dom["launches"], 2)
+    roof["launches_per_frame"] = dom["launches"] // n_prof
+    kernels = {}
+    for e in kt:
+        d = {"us_per_frame": round(e["total_ms"] * 1e3 / n_prof, 2),
+             "launches_per_frame": e["launches"] // n_prof}
+        if e["flops"] > 0:
+            d["TFLOP/s"] = round(e["flops"] / (e["total_ms"] * 1e-3) / 1e12, 2)
+        if e["bytes"] > 0:
+            d["GB/s"] = round(e["bytes"] / (e["total_ms"] * 1e-3) / 1e9, 1)
+        kernels[e["name"]] = d
+
+    for s in streams:
+        s.close()
+    hs.hs_shutdown(ctx)
+
+    # ---- the CPU oracle on the host cores, bounded sample --------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        app = oracle.OracleApp("resnet18_convlstm", blob, NW, NH, True, si.DEFAULT_PALETTE)
+        fr = list(si.tool_scene_frames(args.cpu_frames, FH, FW, 1))
+        app.process(fr[0])                       # first call pays one-time page-in costs
+        t0 = time.perf_counter()
+        for f in fr[1:]:
+            app.process(f)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round((len(fr) - 1) / dt, 4), "unit": "frames/s", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"{len(fr) - 1} frames of the same 1080p workload, one stream, all "
+                         "four stages, NumPy float64 (BLAS threads = cores)"}
+
+    line = {
+        "metric": "aggregate frames/s + p50/max per-frame latency at N concurrent streams, 1 GPU",
+        "value": round(fps, 2), "unit": "frames/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(1e3 * elapsed / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.streams} stream(s) x 1920x1080 RGB uint8 -> 854x480 fp16, "
+                               "ResNet-18-style + ConvLSTM(256) + 8-ch head, sigmoid/threshold/"
+                               "argmax, alpha-blend overlay on the 1080p frame",
+                   "streams": args.streams, "partition": args.partition,
+                   "queue_depth": args.queue_depth, "device_cus": n_cus},
+        "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
+                       "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
+                       "max": round(m["max"], 4), "mean": round(m["mean"], 4),
+                       "std": round(m["std"], 4), "tail": round(m["tail"], 4),
+                       "flatness": round(m["flatness"], 4), "dropped": int(sum(dropped)),
+                       "stage_median_ms": stage_ms},
+        "roofline": roof,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -175,6 +175,10 @@ hs_status hs_reset_state(hs_app* app);
  * [256][map_h][map_w] each (either may be NULL). HS_E_STATE while frames are in flight,
  * HS_E_INVAL for a stateless network. For tests and for checkpointing a stream. */
 hs_status hs_get_state(hs_app* app, float* h_out, float* c_out);
+/* Copy the backbone's output for the last completed frame (the ConvLSTM cell's input x_t)
+ * to a HOST buffer as fp32 planar [512][map_h][map_w]. Same status rules as hs_get_state.
+ * Lets a test check the recurrent cell in isolation. */
+hs_status hs_get_features(hs_app* app, float* x_out);
 
 /* ---- spatial partition + admission control (Section IV-A) ------------------------- */
 

@@ -18,7 +18,7 @@ __all__ = [
     "HS_NUM_TOOLS", "HS_MAX_CU_WORDS", "HsError", "hs_app_desc", "hs_result",
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
-    "hs_get_state", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
+    "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
     "hs_poll_result", "hs_wait_result", "hs_latency_metrics_compute", "hs_set_kernel_timing",
     "hs_get_kernel_times", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
@@ -101,6 +101,7 @@ def load() -> C.CDLL:
         "hs_destroy_app": (C.c_int, [C.c_void_p]),
         "hs_reset_state": (C.c_int, [C.c_void_p]),
         "hs_get_state": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+        "hs_get_features": (C.c_int, [C.c_void_p, C.c_void_p]),
         "hs_set_partition": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
         "hs_admission_check": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
         "hs_submit_frame": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
@@ -209,6 +210,13 @@ def hs_get_state(app: int, map_h: int, map_w: int, hid: int = 256):
     c = np.empty((hid, map_h, map_w), dtype=np.float32)
     _check(load().hs_get_state(app, h.ctypes.data, c.ctypes.data))
     return h, c
+
+
+def hs_get_features(app: int, map_h: int, map_w: int, ch: int = 512) -> np.ndarray:
+    """Returns the ConvLSTM cell's input of the last frame, float32 (ch, map_h, map_w)."""
+    x = np.empty((ch, map_h, map_w), dtype=np.float32)
+    _check(load().hs_get_features(app, x.ctypes.data))
+    return x
 
 
 def hs_set_partition(app: int, cu_mask_infer, cu_mask_overlay) -> None:

@@ -882,6 +882,20 @@ hs_status hs_get_state(hs_app* app, float* h_out, float* c_out) {
   return HS_OK;
 }
 
+hs_status hs_get_features(hs_app* app, float* x_out) {
+  if (!app || !x_out) { set_error("hs_get_features: NULL"); return HS_E_INVAL; }
+  if (!app->stateful) { set_error("hs_get_features: network has no recurrent cell"); return HS_E_INVAL; }
+  if (frames_in_flight(app)) { set_error("hs_get_features: frames in flight"); return HS_E_STATE; }
+  HS_HIP(hipSetDevice(app->ctx->device));
+  const size_t n = (size_t)app->map_w * app->map_h;
+  std::vector<f16> tmp(n * app->concat_pitch);
+  HS_HIP(hipMemcpy(tmp.data(), app->d_concat, tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
+  for (size_t m = 0; m < n; ++m)
+    for (int j = 0; j < app->x_ch; ++j)
+      x_out[(size_t)j * n + m] = (float)tmp[m * app->concat_pitch + j];
+  return HS_OK;
+}
+
 hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
                            const uint32_t* cu_mask_overlay, int n_words) {
   if (!app) { set_error("hs_set_partition: NULL app"); return HS_E_INVAL; }

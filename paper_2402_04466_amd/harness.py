@@ -107,6 +107,9 @@ class AppStream:
     def state(self, r):
         return api.hs_get_state(self.app, r.map_h, r.map_w)
 
+    def features(self, r):
+        return api.hs_get_features(self.app, r.map_h, r.map_w)
+
     def close(self):
         if self.app:
             api.hs_destroy_app(self.app)

@@ -8,7 +8,16 @@ import oracle
 import synth_inputs as si
 
 TOL_NET = 2e-2        # fp16 GPU vs fp32 oracle, max |diff| / max |ref| per output tensor
-TOL_EMU = 5e-3        # fp16 GPU vs the oracle's fp16-storage emulation
+TOL_CELL = 2e-3       # one ConvLSTM step / head on identical fp16 inputs: fp32-accumulate vs fp64
+TOL_STATE_RMS = 2e-2  # end-to-end recurrent state: rms(diff) / rms(ref)
+TOL_STATE_MAX = 0.15  # end-to-end recurrent state: max |diff| / max |ref| (gates near zero
+                      # amplify the fp16 storage noise of the 20 layers before them)
+
+
+def rms_rel(a, ref):
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.sqrt(((a - ref) ** 2).mean()) / max(np.sqrt((ref ** 2).mean()), 1e-30))
 
 
 def rel_err(a, ref):
@@ -35,7 +44,7 @@ def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, thre
     assert e32 <= TOL_NET, f"{tag}: logits vs fp32 oracle {e32:.3e}"
     if o16 is not None:
         e16 = rel_err(g["logits"], o16["logits"])
-        assert e16 <= TOL_EMU, f"{tag}: logits vs fp16-emulating oracle {e16:.3e}"
+        assert e16 <= TOL_NET, f"{tag}: logits vs fp16-emulating oracle {e16:.3e}"
     # ---- stage 3, stage-isolated: the oracle's postprocess on the GPU's own logits ---------
     p = oracle.postprocess(g["logits"], threshold)
     assert np.array_equal(g["mask"], p["mask"]), f"{tag}: mask differs"

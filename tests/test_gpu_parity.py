@@ -7,7 +7,9 @@ import pytest
 import torch
 
 import synth_inputs as si
-from gpu_common import check_frame, make_oracles, rel_err, TOL_EMU
+import oracle
+from gpu_common import (check_frame, make_oracles, rel_err, rms_rel, TOL_CELL, TOL_STATE_RMS,
+                        TOL_STATE_MAX)
 
 pytestmark = pytest.mark.gpu
 PAL = si.DEFAULT_PALETTE
@@ -30,6 +32,11 @@ def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_inpu
     o32, o16 = make_oracles(net_name, blob, net_w, net_h, not fp32_input, PAL,
                             threshold=threshold, alpha=alpha)
     errs = []
+    w16 = None
+    if check_state:
+        ws = oracle.split_blob(blob, oracle.ResNet18ConvLSTMNet.shapes())
+        w16 = [w.astype(np.float16).astype(np.float32) for w in ws[-2:]]   # lstm, head
+        h_prev = c_prev = None
     try:
         for i, f in enumerate(frames):
             print(f"[{tag}] frame {i} {fw}x{fh} -> {net_w}x{net_h}", flush=True)
@@ -43,13 +50,27 @@ def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_inpu
             a, b = o32.process(f), o16.process(f)
             errs.append(check_frame(g, f, a, b, threshold=threshold, alpha=alpha, palette=PAL,
                                     fp32_input=fp32_input, tag=f"{tag}/frame{i}"))
-            if check_state and "h" in b:
+            if check_state:
                 gh, gc = s.state(r)
-                eh, ec = rel_err(gh, b["h"]), rel_err(gc, b["c"])
-                print(f"[{tag}] state vs fp16-emulating oracle: h {eh:.2e} c {ec:.2e}; "
-                      f"vs fp32 oracle: h {rel_err(gh, a['h']):.2e} c {rel_err(gc, a['c']):.2e}",
+                gx = s.features(r)
+                if h_prev is None:
+                    h_prev, c_prev = np.zeros_like(gh), np.zeros_like(gc)
+                # the recurrent cell and the head in isolation: the oracle's step on the GPU's
+                # own fp16 inputs (features, previous state) and fp16-rounded weights
+                oh, oc = oracle.convlstm_step(gx, h_prev, c_prev, w16[0])
+                ol = oracle.conv2d(gh, w16[1], 1, 0)
+                ech, ecc, ehd = rel_err(gh, oh), rel_err(gc, oc), rel_err(g["logits"], ol)
+                print(f"[{tag}] cell in isolation: h {ech:.2e} c {ecc:.2e} head {ehd:.2e}",
                       flush=True)
-                assert eh <= 2e-2 and ec <= 2e-2, f"{tag}: recurrent state h {eh:.3e} c {ec:.3e}"
+                assert max(ech, ecc, ehd) <= TOL_CELL, f"{tag}: cell h {ech:.3e} c {ecc:.3e} head {ehd:.3e}"
+                h_prev, c_prev = gh, gc
+                # end to end against the fp32 oracle
+                stats = [rel_err(gh, a["h"]), rel_err(gc, a["c"]), rms_rel(gh, a["h"]),
+                         rms_rel(gc, a["c"])]
+                print(f"[{tag}] state vs fp32 oracle: max-norm h {stats[0]:.2e} c {stats[1]:.2e}; "
+                      f"rms h {stats[2]:.2e} c {stats[3]:.2e}", flush=True)
+                assert max(stats[0], stats[1]) <= TOL_STATE_MAX and max(stats[2], stats[3]) <= TOL_STATE_RMS, \
+                    f"{tag}: recurrent state drift {stats}"
     finally:
         s.close()
     print(f"[{tag}] logits max-norm error vs fp32 oracle per frame: "
@@ -151,8 +172,12 @@ def test_partition_admission_and_masked_results_identical(hs, ctx):
             hs.hs_set_partition(b.app, hs.cu_mask_words(range(half - 4, n_cus)),
                                 hs.cu_mask_words(range(half - 4, n_cus)))
         assert ei.value.status == hs.HS_E_OVERSUBSCRIBED
-        with pytest.raises(hs.HsError):                          # CU the device does not have
-            hs.hs_set_partition(b.app, hs.cu_mask_words([n_cus]), hs.cu_mask_words([n_cus]))
+        if n_cus < 256:                                          # CU the device does not have
+            with pytest.raises(hs.HsError):
+                hs.hs_set_partition(b.app, hs.cu_mask_words([n_cus]), hs.cu_mask_words([n_cus]))
+        with pytest.raises(hs.HsError) as ei:                    # empty overlay mask
+            hs.hs_set_partition(b.app, hs.cu_mask_words(range(half, n_cus)), hs.cu_mask_words([]))
+        assert ei.value.status == hs.HS_E_OVERSUBSCRIBED
         hs.hs_set_partition(b.app, hs.cu_mask_words(range(half, n_cus)),
                             hs.cu_mask_words(range(half, n_cus)))
         assert a.submit(d_in, o2, 1) == hs.HS_OK
