@@ -98,9 +98,9 @@ typedef struct {
  * that stage's end and the overlay's end.  End-to-end latency = t_overlay_done_ns -
  * t_submit_ns (Section II-C).
  *
- * Device pointers alias the application's workspace (slot frame_id % queue_depth ...
- * strictly: the slot the frame was given) and stay valid until queue_depth further
- * frames have been submitted to the same application.
+ * Device pointers alias the queue slot the frame was given inside the application's
+ * workspace and stay valid until queue_depth further frames have been submitted to the
+ * same application.
  *   d_net_input     fp16, pixel-interleaved with 4 channels per pixel (R,G,B,0),
  *                   net_h rows of net_w pixels, row pitch net_input_pitch_bytes
  *   d_net_input_f32 fp32 planar [3][net_h][net_w], or NULL unless net_fp32_input
