@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--paced-frames", type=int, default=60)
     ap.add_argument("--distinct-frames", type=int, default=8)
     ap.add_argument("--queue-depth", type=int, default=4)
+    ap.add_argument("--launch-mode", choices=["graph", "eager"], default="graph",
+                    help="stages 1-3 as one HIP graph per frame, or kernel by kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=6)
     return ap.parse_args()
@@ -80,6 +82,8 @@ def main():
         s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW,
                       net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
                       queue_depth=args.queue_depth)
+        hs.hs_set_launch_mode(s.app, hs.HS_LAUNCH_GRAPH if args.launch_mode == "graph"
+                              else hs.HS_LAUNCH_EAGER)
         streams.append(s)
         seed = 1 if args.streams == 1 else 2 + i
         frames.append([s.upload_frame(f)
@@ -204,7 +208,8 @@ def main():
                                "ResNet-18-style + ConvLSTM(256) + 8-ch head, sigmoid/threshold/"
                                "argmax, alpha-blend overlay on the 1080p frame",
                    "streams": args.streams, "partition": args.partition,
-                   "queue_depth": args.queue_depth, "device_cus": n_cus},
+                   "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
+                   "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),

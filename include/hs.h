@@ -93,7 +93,9 @@ typedef struct {
  * CLOCK_MONOTONIC nanoseconds. t_submit_ns is taken on entry to hs_submit_frame
  * (arrival at the first stage). t_overlay_done_ns is taken by the library's completion
  * thread when the overlay kernel's completion event fires (departure from the last
- * stage) -- independent of when the caller polls; t_observed_ns is the poll time.
+ * stage) -- independent of when the caller polls; t_observed_ns is the poll time;
+ * t_enqueued_ns is when hs_submit_frame had handed all work to the GPU queues (host
+ * launch cost = t_enqueued_ns - t_submit_ns).
  * The three intermediate stamps are t_overlay_done_ns minus the GPU-event time between
  * that stage's end and the overlay's end.  End-to-end latency = t_overlay_done_ns -
  * t_submit_ns (Section II-C).
@@ -111,8 +113,8 @@ typedef struct {
  */
 typedef struct {
   uint64_t frame_id;
-  uint64_t t_submit_ns, t_pre_done_ns, t_infer_done_ns, t_post_done_ns, t_overlay_done_ns,
-      t_observed_ns;
+  uint64_t t_submit_ns, t_enqueued_ns, t_pre_done_ns, t_infer_done_ns, t_post_done_ns,
+      t_overlay_done_ns, t_observed_ns;
   int32_t argmax_idx[HS_NUM_TOOLS]; /* row-major index y*map_w+x of the channel maximum,  */
                                     /* lowest index among equal maxima                    */
   uint8_t present[HS_NUM_TOOLS];    /* 1 if the channel maximum exceeds the threshold     */
@@ -216,6 +218,14 @@ hs_status hs_poll_result(hs_app* app, hs_result* out);
 /* As hs_poll_result, but sleeps until a frame has finished or timeout_ns elapsed
  * (HS_E_NOT_READY on time-out). */
 hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns);
+
+/* How hs_submit_frame hands stages 1-3 to the GPU: as one pre-built HIP graph per queue slot
+ * (default; one launch call per frame instead of ~35) or kernel by kernel. Results are
+ * identical. Kernel timing (below) always uses the kernel-by-kernel path.
+ * HS_E_STATE while frames are in flight. */
+#define HS_LAUNCH_GRAPH 0
+#define HS_LAUNCH_EAGER 1
+hs_status hs_set_launch_mode(hs_app* app, int mode);
 
 /* ---- measurement ------------------------------------------------------------------ */
 

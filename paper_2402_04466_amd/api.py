@@ -19,7 +19,7 @@ __all__ = [
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
-    "hs_poll_result", "hs_wait_result", "hs_latency_metrics_compute", "hs_set_kernel_timing",
+    "hs_poll_result", "hs_wait_result", "hs_latency_metrics_compute", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
     "hs_get_kernel_times", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
@@ -27,6 +27,7 @@ HS_OK, HS_E_INVAL, HS_E_NOMEM, HS_E_OVERSUBSCRIBED = 0, -1, -2, -3
 HS_E_QUEUE_FULL, HS_E_NOT_READY, HS_E_DEVICE, HS_E_STATE = -4, -5, -6, -7
 HS_NET_TINY4, HS_NET_RESNET18_CONVLSTM = 1, 2
 HS_NUM_TOOLS, HS_MAX_CU_WORDS = 8, 8
+HS_LAUNCH_GRAPH, HS_LAUNCH_EAGER = 0, 1
 
 _STATUS_NAME = {0: "HS_OK", -1: "HS_E_INVAL", -2: "HS_E_NOMEM", -3: "HS_E_OVERSUBSCRIBED",
                 -4: "HS_E_QUEUE_FULL", -5: "HS_E_NOT_READY", -6: "HS_E_DEVICE", -7: "HS_E_STATE"}
@@ -52,7 +53,7 @@ class hs_app_desc(C.Structure):
 class hs_result(C.Structure):
     _fields_ = [
         ("frame_id", C.c_uint64),
-        ("t_submit_ns", C.c_uint64), ("t_pre_done_ns", C.c_uint64),
+        ("t_submit_ns", C.c_uint64), ("t_enqueued_ns", C.c_uint64), ("t_pre_done_ns", C.c_uint64),
         ("t_infer_done_ns", C.c_uint64), ("t_post_done_ns", C.c_uint64),
         ("t_overlay_done_ns", C.c_uint64), ("t_observed_ns", C.c_uint64),
         ("argmax_idx", C.c_int32 * HS_NUM_TOOLS), ("present", C.c_uint8 * HS_NUM_TOOLS),
@@ -110,6 +111,7 @@ def load() -> C.CDLL:
         "hs_latency_metrics_compute": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int,
                                                  P(hs_latency_metrics)]),
         "hs_set_kernel_timing": (C.c_int, [C.c_void_p, C.c_int]),
+        "hs_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_get_kernel_times": (C.c_int, [C.c_void_p, P(hs_kernel_time), C.c_int, P(C.c_int)]),
         "hs_last_error": (C.c_char_p, []),
         "hs_version": (C.c_char_p, []),
@@ -267,6 +269,10 @@ def hs_latency_metrics_compute(latencies, trim: bool = True) -> dict:
     _check(load().hs_latency_metrics_compute(x.ctypes.data, x.size, 1 if trim else 0,
                                              C.byref(m)))
     return {k: getattr(m, k) for k, _ in hs_latency_metrics._fields_}
+
+
+def hs_set_launch_mode(app: int, mode: int) -> None:
+    _check(load().hs_set_launch_mode(app, mode))
 
 
 def hs_set_kernel_timing(app: int, enable: bool) -> None:

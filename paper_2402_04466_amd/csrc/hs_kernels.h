@@ -11,6 +11,14 @@ namespace hs {
 
 typedef _Float16 f16;
 
+// How to launch a kernel whose single argument is one of the parameter blocks below:
+// hipLaunchKernel(func, grid, block, {&params}, shmem, stream), or the same as a graph node.
+struct KernelDesc {
+  const void* func;
+  dim3 grid, block;
+  unsigned shmem;
+};
+
 // ---- stage 1: bilinear resize (exact integer) + normalise + interleave ----------------
 struct ResizeParams {
   const uint8_t* src;   // frame, RGB bytes, row pitch src_pitch (16-byte multiple)
@@ -23,7 +31,7 @@ struct ResizeParams {
   const f16* lut16;     // 256 entries
   float rcp_dx, rcp_dy, rcp_d;  // 1/(2*wo), 1/(2*ho), 1/(4*wo*ho): division estimates
 };
-void launch_resize_norm(const ResizeParams& p, hipStream_t s);
+KernelDesc describe(const ResizeParams& p);
 
 // ---- stage 2: implicit-GEMM convolution on fp16 MFMA ------------------------------------
 // Activations are pixel-major ("NHWC"): element (y, x, c) at in[(y*win + x)*cin_pitch + c].
@@ -39,13 +47,14 @@ struct ConvParams {
   int hout, wout, m;    // m = hout*wout output pixels
   int cout, cout_pad;   // cout_pad: multiple of the block's N tile
   int kc;               // 16, 32 or 64
+  int depth;            // prefetch depth in chunks: 4, or 8 (kc == 64 only)
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;
   // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)
   int nsplit, chunks_per_split;
-  int use_partial;      // 1: store fp32 partial sums instead of running the fused epilogue
+  int use_partial;      // 1: store fp32 partial sums for a reduction kernel, no epilogue here
   float* partial;       // [nsplit][m][cout_pad] fp32
-  // fused epilogue (use_partial == 0, nsplit == 1)
+  // fused epilogue (use_partial == 0)
   f16* out;             // out[m*out_pitch + n]
   int out_pitch;
   const f16* res;       // optional residual, res[m*res_pitch + n]
@@ -53,14 +62,14 @@ struct ConvParams {
   int relu;
   float* out_f32;       // if set: planar fp32 out_f32[n*m_total + m] instead of `out`
 };
-void launch_conv_mfma(const ConvParams& p, hipStream_t s);
+KernelDesc describe(const ConvParams& p);
 
-// Sum split-K partials, add residual, ReLU, store fp16 (or planar fp32).
+// Sum split-K partials in split order, add residual, ReLU, store fp16 (or planar fp32).
 struct SplitKEpilogueParams {
   const float* partial; int nsplit; int m; int cout; int cout_pad;
   f16* out; int out_pitch; const f16* res; int res_pitch; int relu; float* out_f32;
 };
-void launch_splitk_epilogue(const SplitKEpilogueParams& p, hipStream_t s);
+KernelDesc describe(const SplitKEpilogueParams& p);
 
 // ConvLSTM gate non-linearities and state update from the gate pre-activations.
 // partial: [nsplit][m][4*hid] with channels ordered i, f, g, o (hid each).
@@ -69,15 +78,11 @@ struct LstmEpilogueParams {
   const float* partial; int nsplit; int m; int hid;
   float* c; f16* h_out; int h_pitch;
 };
-void launch_lstm_epilogue(const LstmEpilogueParams& p, hipStream_t s);
+KernelDesc describe(const LstmEpilogueParams& p);
 
 // 3x3 stride-2 pad-1 max-pool on pixel-major fp16, c multiple of 8.
 struct MaxPoolParams { const f16* in; f16* out; int hin, win, hout, wout, c; };
-void launch_maxpool(const MaxPoolParams& p, hipStream_t s);
-
-// 1x1 head: logits[k][m] = sum_j w[k][j] * h[m*h_pitch + j], fp32 planar output.
-struct HeadParams { const f16* h; int h_pitch; const f16* w; int cin; int m; float* logits; };
-void launch_head(const HeadParams& p, hipStream_t s);
+KernelDesc describe(const MaxPoolParams& p);
 
 // ---- stage 3: postprocess -----------------------------------------------------------------
 struct PostRecord {           // written by the kernel into pinned host memory
@@ -91,7 +96,15 @@ struct PostParams {
   float* heat; uint8_t* mask;    // [8][n]
   PostRecord* rec;               // host-visible
 };
-void launch_postprocess(const PostParams& p, hipStream_t s);
+KernelDesc describe(const PostParams& p);
+
+// 1x1 head (cin <= 512 -> 8 channels, fp16 weights w[k][cin]) fused with the postprocess:
+// logits[k][m] = sum_j w[k][j] * h[m*h_pitch + j] in fp32, then heat / mask / record.
+struct HeadPostParams {
+  const f16* h; int h_pitch; const f16* w; int cin; int m;
+  float theta; float* logits; float* heat; uint8_t* mask; PostRecord* rec;
+};
+KernelDesc describe(const HeadPostParams& p);
 
 // ---- stage 4: overlay ---------------------------------------------------------------------
 struct OverlayParams {
@@ -100,7 +113,7 @@ struct OverlayParams {
   int a;                             // Q8 alpha, 0..256
   uint32_t pal[8];                   // R | G<<8 | B<<16
 };
-void launch_overlay(const OverlayParams& p, hipStream_t s);
+KernelDesc describe(const OverlayParams& p);
 
 // ---- helpers ------------------------------------------------------------------------------
 void launch_fill_zero(void* d, size_t bytes, hipStream_t s);   // bytes multiple of 16

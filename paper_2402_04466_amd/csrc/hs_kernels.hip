@@ -7,6 +7,7 @@ namespace hs {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // plain 16-byte register value
 
 // floor(num / d) for num, d < 2^31 where the quotient is < 2^22: float estimate, exact fix-up.
 __device__ __forceinline__ uint32_t udiv_est(uint32_t num, uint32_t d, float rcp_d) {
@@ -82,9 +83,9 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
   }
 }
 
-void launch_resize_norm(const ResizeParams& p, hipStream_t s) {
-  const size_t lds = (size_t)((3 * p.wi + 15) >> 4) * 16 * 2;
-  hipLaunchKernelGGL(k_resize_norm, dim3(p.ho), dim3(256), lds, s, p);
+KernelDesc describe(const ResizeParams& p) {
+  const unsigned lds = (unsigned)((3 * p.wi + 15) >> 4) * 16 * 2;
+  return KernelDesc{(const void*)k_resize_norm, dim3(p.ho), dim3(256), lds};
 }
 
 // =============================================================================================
@@ -93,130 +94,232 @@ void launch_resize_norm(const ResizeParams& p, hipStream_t s) {
 // v_mfma_f32_32x32x16_f16.  The MFMA "A" operand is the weight tile and the "B" operand the
 // pixel tile, so a lane ends up holding 4 consecutive output channels of one pixel per
 // accumulator quad -> 8-byte fp16 stores into the pixel-major output.
-// Global -> register prefetch of chunk q+1 overlaps the MFMAs of chunk q.
+//
+// Latency hiding: at batch 1 a grid is only 1-2 workgroups per CU, so the K loop keeps DEPTH
+// chunks of global loads in flight in registers (the loads of chunk q+DEPTH are issued right
+// after chunk q has been handed to LDS); LDS is double buffered, one barrier per chunk.
+//
+// Split-K: blockIdx.z owns a contiguous range of chunks and stores fp32 partial sums; the
+// reduction kernels below sum them in split order and run the epilogue.
 // =============================================================================================
-template <int KC>
+__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
+
+// residual add, ReLU and store of 4 consecutive output channels n..n+3 of pixel m
+__device__ __forceinline__ void store_quad(const ConvParams& p, int m, int n, float v[4]) {
+  if (p.res) {
+    const half4 r = *reinterpret_cast<const half4*>(p.res + (size_t)m * p.res_pitch + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += (float)r[j];
+  }
+  if (p.relu) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.0f);
+  }
+  if (p.out_f32) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) p.out_f32[(size_t)(n + j) * p.m + m] = v[j];
+  } else {
+    half4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = (f16)v[j];
+    *reinterpret_cast<half4*>(p.out + (size_t)m * p.out_pitch + n) = o;
+  }
+}
+
+template <int KC, int DEPTH>
 __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
   constexpr int BM = 64, BN = 64;
   constexpr int PITCH = KC + 8;            // halves; +16 bytes keeps ds_read_b128 conflict-free
   constexpr int VPR = KC / 8;              // 16-byte vectors per tile row
   constexpr int NV = BM * VPR;             // vectors per tile (pixel tile and weight tile alike)
   constexpr int NP = (NV + 255) / 256;     // vectors per thread
-  __shared__ __align__(16) f16 s_x[BM * PITCH];
-  __shared__ __align__(16) f16 s_w[BN * PITCH];
+  __shared__ __align__(16) f16 s_x[2][BM * PITCH];
+  __shared__ __align__(16) f16 s_w[2][BN * PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
   const int q_begin = blockIdx.z * p.chunks_per_split;
   const int q_end = min(p.nchunks, q_begin + p.chunks_per_split);
 
-  // per-thread loader coordinates (fixed over the K loop)
-  int l_row[NP], l_kv[NP], l_iy0[NP], l_ix0[NP];
-  bool l_act[NP], l_ok[NP];
+  // Per-thread loader state, fixed over the K loop: for every 16-byte vector this thread
+  // fetches, the address of tap (0,0) / channel 0 of its pixel, the address of its weight
+  // row, and one validity bit per tap (zero padding, ragged last tile).  Per chunk only a
+  // wave-uniform offset is added, so the inner loop carries almost no address arithmetic.
+  const f16* l_abase[NP];
+  const f16* l_wbase[NP];
+  uint32_t l_tapmask[NP];
+  int l_lds[NP];
+  bool l_act[NP];
 #pragma unroll
   for (int i = 0; i < NP; ++i) {
     const int v = tid + i * 256;
     l_act[i] = v < NV;
-    l_row[i] = v / VPR;
-    l_kv[i] = v % VPR;
-    const int m = m0 + l_row[i];
-    l_ok[i] = l_act[i] && m < p.m;
+    const int row = (v / VPR) % BM;      // threads beyond the tile re-load a valid row, unused
+    const int kv = v % VPR;
+    const int m = m0 + row;
     const int oy = m / p.wout, ox = m - oy * p.wout;
-    l_iy0[i] = oy * p.stride - p.pad;
-    l_ix0[i] = ox * p.stride - p.pad;
-  }
-
-  uint4 rx[NP], rw[NP];
-  auto load_chunk = [&](int q) {
-    const int tap = q / p.chunks_per_tap;
-    const int cc = q - tap * p.chunks_per_tap;
-    const int ky = tap / p.kw, kx = tap - ky * p.kw;
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      if (!l_act[i]) continue;
-      const int iy = l_iy0[i] + ky, ix = l_ix0[i] + kx;
-      const bool inb = l_ok[i] && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (inb) {
-        const f16* a = p.in + ((size_t)iy * p.win + ix) * p.cin_pitch + cc * KC + l_kv[i] * 8;
-        v = *reinterpret_cast<const uint4*>(a);
-      }
-      rx[i] = v;
-      const f16* b = p.wt + (size_t)(n0 + l_row[i]) * p.ktot + (size_t)q * KC + l_kv[i] * 8;
-      rw[i] = *reinterpret_cast<const uint4*>(b);
+    const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
+    uint32_t mask = 0;
+    for (int t = 0; t < p.ntaps; ++t) {
+      const int ky = t / p.kw, kx = t - ky * p.kw;
+      const int iy = iy0 + ky, ix = ix0 + kx;
+      if (m < p.m && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win) mask |= 1u << t;
     }
-  };
+    l_tapmask[i] = mask;
+    l_abase[i] = p.in + ((long)iy0 * p.win + ix0) * p.cin_pitch + kv * 8;
+    l_wbase[i] = p.wt + (size_t)(n0 + row) * p.ktot + kv * 8;
+    l_lds[i] = row * PITCH + kv * 8;
+  }
+  const f16* const a_safe = p.in;         // any valid address: out-of-range taps read it, unused
+
+  // Loads are unconditional (out-of-range taps read a valid dummy address and are zeroed
+  // when handed to LDS): with no branch around a load the compiler can count outstanding
+  // loads exactly and waits only for the oldest stage.  Stage registers are indexed with
+  // compile-time constants only (macro, fully unrolled) so that they stay in VGPRs.
+  // Chunks are fetched strictly in order; (ld_q, ld_tap, ld_cc, ld_ky, ld_kx) is the next one
+  // and stops advancing at the last chunk of this workgroup's range.
+  u32x4 st_x[DEPTH][NP], st_w[DEPTH][NP];
+  uint32_t st_inb[DEPTH];
+  int ld_q = q_begin;
+  int ld_tap = q_begin / p.chunks_per_tap;
+  int ld_cc = q_begin - ld_tap * p.chunks_per_tap;
+  int ld_ky = ld_tap / p.kw, ld_kx = ld_tap - ld_ky * p.kw;
+#define HS_LOAD_CHUNK(D_)                                                                      \
+  {                                                                                            \
+    const long a_off_ = ((long)ld_ky * p.win + ld_kx) * p.cin_pitch + ld_cc * KC;              \
+    const long w_off_ = (long)ld_q * KC;                                                       \
+    uint32_t mask_ = 0;                                                                        \
+    _Pragma("unroll") for (int i = 0; i < NP; ++i) {                                           \
+      const bool inb_ = (l_tapmask[i] >> ld_tap) & 1u;                                         \
+      mask_ |= (inb_ ? 1u : 0u) << i;                                                          \
+      const f16* a_ = inb_ ? l_abase[i] + a_off_ : a_safe;                                     \
+      st_x[D_][i] = *reinterpret_cast<const u32x4*>(a_);                                       \
+      st_w[D_][i] = *reinterpret_cast<const u32x4*>(l_wbase[i] + w_off_);                      \
+    }                                                                                          \
+    st_inb[D_] = mask_;                                                                        \
+    const bool adv_ = ld_q + 1 < q_end;                                                        \
+    const bool wrap_c_ = ld_cc + 1 == p.chunks_per_tap;                                        \
+    const bool wrap_x_ = wrap_c_ && (ld_kx + 1 == p.kw);                                       \
+    ld_q += adv_ ? 1 : 0;                                                                      \
+    ld_cc = !adv_ ? ld_cc : (wrap_c_ ? 0 : ld_cc + 1);                                         \
+    ld_tap += (adv_ && wrap_c_) ? 1 : 0;                                                       \
+    ld_ky += (adv_ && wrap_x_) ? 1 : 0;                                                        \
+    ld_kx = !(adv_ && wrap_c_) ? ld_kx : (wrap_x_ ? 0 : ld_kx + 1);                            \
+  }
 
   floatx16 acc;
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
 
   const int wm = wave & 1, wn = wave >> 1;
-  const f16* fx = s_x + (wm * 32 + (lane & 31)) * PITCH + (lane >> 5) * 8;
-  const f16* fw = s_w + (wn * 32 + (lane & 31)) * PITCH + (lane >> 5) * 8;
+  const int fx_off = (wm * 32 + (lane & 31)) * PITCH + (lane >> 5) * 8;
+  const int fw_off = (wn * 32 + (lane & 31)) * PITCH + (lane >> 5) * 8;
 
-  if (q_begin < q_end) load_chunk(q_begin);
-  for (int q = q_begin; q < q_end; ++q) {
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      if (!l_act[i]) continue;
-      *reinterpret_cast<uint4*>(s_x + l_row[i] * PITCH + l_kv[i] * 8) = rx[i];
-      *reinterpret_cast<uint4*>(s_w + l_row[i] * PITCH + l_kv[i] * 8) = rw[i];
-    }
-    __syncthreads();
-    if (q + 1 < q_end) load_chunk(q + 1);
-#pragma unroll
-    for (int ks = 0; ks < KC / 16; ++ks) {
-      const half8 a = *reinterpret_cast<const half8*>(fw + ks * 16);
-      const half8 b = *reinterpret_cast<const half8*>(fx + ks * 16);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
-    }
-    __syncthreads();
+  static_assert(DEPTH == 4 || DEPTH == 8, "the pipeline below is written out for 4 or 8 stages");
+  // Prologue: fill all four stages.  Chunk indices are clamped instead of guarded so that
+  // there is no branch around a load (a short K range re-loads its last chunk, unused).
+  HS_LOAD_CHUNK(0)
+  HS_LOAD_CHUNK(1)
+  HS_LOAD_CHUNK(2)
+  HS_LOAD_CHUNK(3)
+  if constexpr (DEPTH > 4) {
+    HS_LOAD_CHUNK(4)
+    HS_LOAD_CHUNK(5)
+    HS_LOAD_CHUNK(6)
+    HS_LOAD_CHUNK(7)
   }
+
+  // One pipeline step for stage D_ (a literal, so every register index is a constant):
+  // hand chunk q to LDS, barrier, refill the stage with chunk q + DEPTH, MFMAs on chunk q.
+  // REFILL_ is the refill condition: `true` in the steady-state loop (branch-free body, so
+  // the wait before the LDS hand-over is for the oldest stage only), a test in the tail.
+#define HS_STEP(D_, REFILL_)                                                                   \
+  {                                                                                            \
+    const int q = qb + (D_);                                                                   \
+    (void)q;                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < NP; ++i) {                                           \
+      if constexpr (NV % 256 != 0) { if (!l_act[i]) continue; }                                \
+      const u32x4 zero = {0u, 0u, 0u, 0u};                                                     \
+      *reinterpret_cast<u32x4*>(&s_x[buf][l_lds[i]]) =                                         \
+          ((st_inb[D_] >> i) & 1u) ? st_x[D_][i] : zero;                                       \
+      *reinterpret_cast<u32x4*>(&s_w[buf][l_lds[i]]) = st_w[D_][i];                            \
+    }                                                                                          \
+    __syncthreads();                                                                           \
+    if (REFILL_) HS_LOAD_CHUNK(D_)                                                  \
+    const f16* fx = &s_x[buf][fx_off];                                                         \
+    const f16* fw = &s_w[buf][fw_off];                                                         \
+    _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                   \
+      const half8 a = *reinterpret_cast<const half8*>(fw + ks * 16);                           \
+      const half8 b = *reinterpret_cast<const half8*>(fx + ks * 16);                           \
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);                        \
+    }                                                                                          \
+    buf ^= 1;                                                                                  \
+  }
+
+  int buf = 0;
+  int qb = q_begin;
+  for (; qb + 2 * DEPTH <= q_end; qb += DEPTH) {   // steady state: every refill is in range
+    HS_STEP(0, true)
+    HS_STEP(1, true)
+    HS_STEP(2, true)
+    HS_STEP(3, true)
+    if constexpr (DEPTH > 4) {
+      HS_STEP(4, true)
+      HS_STEP(5, true)
+      HS_STEP(6, true)
+      HS_STEP(7, true)
+    }
+  }
+  for (; qb < q_end; qb += DEPTH) {                // tail: at most 2*DEPTH - 1 chunks
+    if (qb + 0 < q_end) HS_STEP(0, q + DEPTH < q_end)
+    if (qb + 1 < q_end) HS_STEP(1, q + DEPTH < q_end)
+    if (qb + 2 < q_end) HS_STEP(2, q + DEPTH < q_end)
+    if (qb + 3 < q_end) HS_STEP(3, q + DEPTH < q_end)
+    if constexpr (DEPTH > 4) {
+      if (qb + 4 < q_end) HS_STEP(4, q + DEPTH < q_end)
+      if (qb + 5 < q_end) HS_STEP(5, q + DEPTH < q_end)
+      if (qb + 6 < q_end) HS_STEP(6, q + DEPTH < q_end)
+      if (qb + 7 < q_end) HS_STEP(7, q + DEPTH < q_end)
+    }
+  }
+#undef HS_STEP
 
   // accumulator register 4*i + j holds channel n_base + 8*i + j of pixel m
   const int m = m0 + wm * 32 + (lane & 31);
   const int n_base = n0 + wn * 32 + (lane >> 5) * 4;
-  if (m >= p.m) return;
-  if (p.use_partial) {
+  if (!p.use_partial) {
+    if (m >= p.m) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = n_base + 8 * i;
+      if (n >= p.cout) continue;
+      float v[4] = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
+      store_quad(p, m, n, v);
+    }
+    return;
+  }
+
+  // ---- split-K: store fp32 partial sums; a separate kernel reduces them.  (Reducing inside
+  // this kernel would need a device-wide release per workgroup, which on a multi-XCD part
+  // means a full L2 write-back each time -- measured 3x slower than the extra launch.)
+  if (m < p.m) {
     float* dst = p.partial + ((size_t)blockIdx.z * p.m + m) * p.cout_pad + n_base;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       *reinterpret_cast<float4*>(dst + 8 * i) =
           make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
-    return;
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int n = n_base + 8 * i;
-    if (n >= p.cout) continue;
-    float v[4] = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
-    if (p.res) {
-      const half4 r = *reinterpret_cast<const half4*>(p.res + (size_t)m * p.res_pitch + n);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] += (float)r[j];
-    }
-    if (p.relu) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.0f);
-    }
-    if (p.out_f32) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) p.out_f32[(size_t)(n + j) * p.m + m] = v[j];
-    } else {
-      half4 o;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) o[j] = (f16)v[j];
-      *reinterpret_cast<half4*>(p.out + (size_t)m * p.out_pitch + n) = o;
-    }
   }
 }
 
-void launch_conv_mfma(const ConvParams& p, hipStream_t s) {
+#undef HS_LOAD_CHUNK
+
+KernelDesc describe(const ConvParams& p) {
   const dim3 grid((p.m + 63) / 64, p.cout_pad / 64, p.nsplit);
-  if (p.kc == 16) hipLaunchKernelGGL(k_conv_mfma<16>, grid, dim3(256), 0, s, p);
-  else if (p.kc == 32) hipLaunchKernelGGL(k_conv_mfma<32>, grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL(k_conv_mfma<64>, grid, dim3(256), 0, s, p);
+  const void* f = p.kc == 16   ? (const void*)k_conv_mfma<16, 4>
+                  : p.kc == 32 ? (const void*)k_conv_mfma<32, 4>
+                  : p.depth == 8 ? (const void*)k_conv_mfma<64, 8>
+                               : (const void*)k_conv_mfma<64, 4>;
+  return KernelDesc{f, grid, dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -254,16 +357,14 @@ __global__ __launch_bounds__(256) void k_splitk_epilogue(SplitKEpilogueParams p)
   }
 }
 
-void launch_splitk_epilogue(const SplitKEpilogueParams& p, hipStream_t s) {
+KernelDesc describe(const SplitKEpilogueParams& p) {
   const size_t n = (size_t)p.m * (p.cout >> 2);
-  hipLaunchKernelGGL(k_splitk_epilogue, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p);
+  return KernelDesc{(const void*)k_splitk_epilogue, dim3((unsigned)((n + 255) / 256)), dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------
 // ConvLSTM epilogue: one thread per (pixel, hidden channel); fp32 math, c kept in fp32.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
-
 __global__ __launch_bounds__(256) void k_lstm_epilogue(LstmEpilogueParams p) {
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= (size_t)p.m * p.hid) return;
@@ -281,9 +382,9 @@ __global__ __launch_bounds__(256) void k_lstm_epilogue(LstmEpilogueParams p) {
   p.h_out[(size_t)m * p.h_pitch + j] = (f16)(go * tanhf(c_new));
 }
 
-void launch_lstm_epilogue(const LstmEpilogueParams& p, hipStream_t s) {
+KernelDesc describe(const LstmEpilogueParams& p) {
   const size_t n = (size_t)p.m * p.hid;
-  hipLaunchKernelGGL(k_lstm_epilogue, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p);
+  return KernelDesc{(const void*)k_lstm_epilogue, dim3((unsigned)((n + 255) / 256)), dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -316,46 +417,9 @@ __global__ __launch_bounds__(256) void k_maxpool(MaxPoolParams p) {
   *reinterpret_cast<half8*>(p.out + (size_t)pix * p.c + v * 8) = best;
 }
 
-void launch_maxpool(const MaxPoolParams& p, hipStream_t s) {
+KernelDesc describe(const MaxPoolParams& p) {
   const size_t n = (size_t)p.hout * p.wout * (p.c >> 3);
-  hipLaunchKernelGGL(k_maxpool, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p);
-}
-
-// ---------------------------------------------------------------------------------------------
-// 1x1 head (8 output channels): one wavefront per pixel; lane l covers input channels
-// l*8 .. l*8+7 (cin <= 512), butterfly-reduced with DPP-friendly shuffles.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_head(HeadParams p) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (m >= p.m) return;
-  float acc[8];
-#pragma unroll
-  for (int k = 0; k < 8; ++k) acc[k] = 0.0f;
-  for (int c0 = lane * 8; c0 < p.cin; c0 += 512) {
-    const half8 x = *reinterpret_cast<const half8*>(p.h + (size_t)m * p.h_pitch + c0);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const half8 w = *reinterpret_cast<const half8*>(p.w + (size_t)k * p.cin + c0);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[k] += (float)x[j] * (float)w[j];
-    }
-  }
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc[k] += __shfl_xor(acc[k], off, 64);
-  }
-  if (lane < 8) {
-    float v = acc[0];
-#pragma unroll
-    for (int k = 1; k < 8; ++k) v = (lane == k) ? acc[k] : v;
-    p.logits[(size_t)lane * p.m + m] = v;
-  }
-}
-
-void launch_head(const HeadParams& p, hipStream_t s) {
-  hipLaunchKernelGGL(k_head, dim3((p.m + 3) / 4), dim3(256), 0, s, p);
+  return KernelDesc{(const void*)k_maxpool, dim3((unsigned)((n + 255) / 256)), dim3(256), 0};
 }
 
 // =============================================================================================
@@ -397,8 +461,56 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
   }
 }
 
-void launch_postprocess(const PostParams& p, hipStream_t s) {
-  hipLaunchKernelGGL(k_postprocess, dim3(8), dim3(256), 0, s, p);
+KernelDesc describe(const PostParams&) {
+  return KernelDesc{(const void*)k_postprocess, dim3(8), dim3(256), 0};
+}
+
+// ---------------------------------------------------------------------------------------------
+// 1x1 head fused with stage 3: workgroup k computes logits[k][m] = sum_j w[k][j] * h[m][j]
+// (fp32 accumulate, fixed order) for every pixel, then postprocesses its own channel.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_head_post(HeadPostParams p) {
+  __shared__ __align__(16) f16 s_wk[512];
+  __shared__ float s_v[4];
+  __shared__ int s_i[4];
+  const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int c = tid; c < p.cin; c += 256) s_wk[c] = p.w[(size_t)k * p.cin + c];
+  __syncthreads();
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int m = tid; m < p.m; m += 256) {
+    const f16* hrow = p.h + (size_t)m * p.h_pitch;
+    float acc = 0.0f;
+    for (int c0 = 0; c0 < p.cin; c0 += 8) {
+      const half8 x = *reinterpret_cast<const half8*>(hrow + c0);
+      const half8 w = *reinterpret_cast<const half8*>(s_wk + c0);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc += (float)x[j] * (float)w[j];
+    }
+    p.logits[(size_t)k * p.m + m] = acc;
+    p.heat[(size_t)k * p.m + m] = 1.0f / (1.0f + expf(-acc));
+    p.mask[(size_t)k * p.m + m] = acc > p.theta ? 1 : 0;
+    if (better(acc, m, bv, bi)) { bv = acc; bi = m; }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+    p.rec->argmax_idx[k] = bi;
+    p.rec->peak[k] = 1.0f / (1.0f + expf(-bv));
+    p.rec->present[k] = bv > p.theta ? 1 : 0;
+  }
+}
+
+KernelDesc describe(const HeadPostParams&) {
+  return KernelDesc{(const void*)k_head_post, dim3(8), dim3(256), 0};
 }
 
 // =============================================================================================
@@ -462,8 +574,8 @@ __global__ __launch_bounds__(128) void k_overlay(OverlayParams p) {
   }
 }
 
-void launch_overlay(const OverlayParams& p, hipStream_t s) {
-  hipLaunchKernelGGL(k_overlay, dim3(p.hf), dim3(128), (size_t)p.wm, s, p);
+KernelDesc describe(const OverlayParams& p) {
+  return KernelDesc{(const void*)k_overlay, dim3(p.hf), dim3(128), (unsigned)p.wm};
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -38,9 +38,9 @@ static inline uint64_t now_ns() {
   } while (0)
 
 // ---- kernel families (for timing) ----------------------------------------------------------
-enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_MAXPOOL, F_HEAD, F_POST, F_OVERLAY, F_COUNT };
+enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_MAXPOOL, F_HEADPOST, F_POST, F_OVERLAY, F_COUNT };
 static const char* kFamilyName[F_COUNT] = {"resize_norm", "conv_mfma", "splitk_epilogue",
-                                           "lstm_epilogue", "maxpool", "head", "postprocess",
+                                           "lstm_epilogue", "maxpool", "head_post", "postprocess",
                                            "overlay"};
 
 struct Op {
@@ -51,23 +51,41 @@ struct Op {
   SplitKEpilogueParams splitk;
   LstmEpilogueParams lstm;
   MaxPoolParams pool;
-  HeadParams head;
+  HeadPostParams headpost;
   PostParams post;
   OverlayParams overlay;
 };
 
-static void launch_op(const Op& op, hipStream_t s) {
+static KernelDesc op_desc(const Op& op) {
   switch (op.fam) {
-    case F_RESIZE: launch_resize_norm(op.resize, s); break;
-    case F_CONV: launch_conv_mfma(op.conv, s); break;
-    case F_SPLITK: launch_splitk_epilogue(op.splitk, s); break;
-    case F_LSTM: launch_lstm_epilogue(op.lstm, s); break;
-    case F_MAXPOOL: launch_maxpool(op.pool, s); break;
-    case F_HEAD: launch_head(op.head, s); break;
-    case F_POST: launch_postprocess(op.post, s); break;
-    case F_OVERLAY: launch_overlay(op.overlay, s); break;
-    default: break;
+    case F_RESIZE: return describe(op.resize);
+    case F_CONV: return describe(op.conv);
+    case F_SPLITK: return describe(op.splitk);
+    case F_LSTM: return describe(op.lstm);
+    case F_MAXPOOL: return describe(op.pool);
+    case F_HEADPOST: return describe(op.headpost);
+    case F_POST: return describe(op.post);
+    default: return describe(op.overlay);
   }
+}
+
+static void* op_params(Op& op) {
+  switch (op.fam) {
+    case F_RESIZE: return &op.resize;
+    case F_CONV: return &op.conv;
+    case F_SPLITK: return &op.splitk;
+    case F_LSTM: return &op.lstm;
+    case F_MAXPOOL: return &op.pool;
+    case F_HEADPOST: return &op.headpost;
+    case F_POST: return &op.post;
+    default: return &op.overlay;
+  }
+}
+
+static hipError_t launch_op(Op& op, hipStream_t s) {
+  const KernelDesc d = op_desc(op);
+  void* args[1] = {op_params(op)};
+  return hipLaunchKernel(d.func, d.grid, d.block, args, d.shmem, s);
 }
 
 // ---- workspace carving -----------------------------------------------------------------------
@@ -96,8 +114,12 @@ struct Slot {
   std::vector<Op> infer;   // stage 2
   std::vector<Op> post;    // stage 3
   Op overlay;              // stage 4
-  hipEvent_t ev_begin = nullptr, ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr,
-             ev_overlay = nullptr;
+  hipEvent_t ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr, ev_overlay = nullptr;
+  // stages 1-3 as one HIP graph (kernel nodes chained in order, event-record nodes at the
+  // stage boundaries); only the frame pointer of the first node changes from frame to frame
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  hipGraphNode_t resize_node = nullptr;
   PostRecord* rec = nullptr;   // pinned host memory, written by the stage-3 kernel
   f16* d_netin = nullptr;
   float* d_netin_f32 = nullptr;
@@ -148,6 +170,7 @@ struct hs_app {
   std::thread completer;
   bool stop = false;
   std::string completer_error;
+  int launch_mode = HS_LAUNCH_GRAPH;
   // kernel timing
   bool timing = false;
   std::vector<TimedLaunch> timed;
@@ -184,6 +207,7 @@ static void pack_rowtap(const float* w, int cout, int k, int chunk_px, int cout_
               (f16)w[(((size_t)n * 3 + ch) * k + ky) * k + px];
 }
 
+static int g_depth = getenv("HS_DEPTH") ? atoi(getenv("HS_DEPTH")) : 8;   // experiment knob
 // ---- plan builder ------------------------------------------------------------------------------
 static inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -232,8 +256,8 @@ struct Builder {
     c.nsplit = (c.nchunks + c.chunks_per_split - 1) / c.chunks_per_split;
   }
 
-  // Appends the convolution and, when it is split along K, its reduction epilogue.
-  // keep_partial: leave the partial sums in the scratch buffer for a later kernel.
+  // Appends the convolution and, when it is split along K, its reduction kernel.
+  // keep_partial: leave the partial sums in the scratch buffer for a later kernel (ConvLSTM).
   // Returns the index of the convolution op.
   int add_conv(ConvParams c, size_t w_off, const Tensor* res, const Tensor* out, bool relu,
                bool want_f32, bool keep_partial, double flops) {
@@ -242,6 +266,7 @@ struct Builder {
     op.flops = flops;
     c.wt = d_w ? d_w + w_off : nullptr;
     choose_split(c);
+    c.depth = (c.kc == 64 && c.chunks_per_split >= 12) ? g_depth : 4;
     const bool partial = c.nsplit > 1 || keep_partial;
     c.use_partial = partial ? 1 : 0;
     c.partial = nullptr;   // patched when the scratch buffer is carved
@@ -402,16 +427,17 @@ struct Builder {
       op.bytes = (double)ops[lstm_conv].conv.nsplit * mf * 1024 * 4.0 + (double)mf * 256 * 10.0;
       ops.push_back(op);
     }
-    // head weights: 8 x 256 fp16, plain [k][c]
+    // head weights: 8 x 256 fp16, plain [k][c]; the head kernel also runs stage 3
     const size_t w_off = reserve_w(2048);
     if (pack)
       for (int i = 0; i < 2048; ++i) host_w[w_off + i] = (f16)blob[at + i];
     at += 2048;
     {
       Op op;
-      op.fam = F_HEAD;
-      op.head = HeadParams{concat ? concat + 512 : nullptr, 768, d_w ? d_w + w_off : nullptr, 256,
-                           mf, nullptr};
+      op.fam = F_HEADPOST;
+      op.headpost = HeadPostParams{concat ? concat + 512 : nullptr, 768,
+                                   d_w ? d_w + w_off : nullptr, 256, mf, 0.0f, nullptr, nullptr,
+                                   nullptr, nullptr};
       op.flops = 2.0 * mf * 8 * 256;
       ops.push_back(op);
       logits_op = (int)ops.size() - 1;
@@ -584,14 +610,21 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     s.infer = b.ops;
     s.infer[b.first_conv_op].conv.in = s.d_netin;
     Op& lo = s.infer[b.logits_op];
-    if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits;
-    else if (lo.fam == F_SPLITK) lo.splitk.out_f32 = s.d_logits;
-    else lo.head.logits = s.d_logits;
-    Op p;
-    p.fam = F_POST;
-    p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec};
-    p.bytes = 8.0 * n_map * (4 + 4 + 1);
-    s.post.push_back(p);
+    if (lo.fam == F_CONV || lo.fam == F_SPLITK) {
+      if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits; else lo.splitk.out_f32 = s.d_logits;
+      Op p;
+      p.fam = F_POST;
+      p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec};
+      p.bytes = 8.0 * n_map * (4 + 4 + 1);
+      s.post.push_back(p);
+    } else {
+      // the head kernel computes the logits and postprocesses them: it is stage 3's launch
+      HeadPostParams& hp = lo.headpost;
+      hp.theta = (float)theta_d; hp.logits = s.d_logits; hp.heat = s.d_heat; hp.mask = s.d_mask;
+      hp.rec = s.rec;
+      s.post.push_back(lo);
+      s.infer.erase(s.infer.begin() + b.logits_op);
+    }
     Op& o = s.overlay;
     o.fam = F_OVERLAY;
     OverlayParams& op = o.overlay;
@@ -602,7 +635,6 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
                   ((uint32_t)d->palette[k][2] << 16);
     o.bytes = 6.0 * d->frame_w * d->frame_h + 8.0 * n_map;
-    HS_HIP(hipEventCreate(&s.ev_begin));
     HS_HIP(hipEventCreate(&s.ev_pre));
     HS_HIP(hipEventCreate(&s.ev_infer));
     HS_HIP(hipEventCreate(&s.ev_post));
@@ -697,21 +729,63 @@ static void collect_timing(hs_app* app) {
   app->timed.clear();
 }
 
-static hs_status run_ops(hs_app* app, const std::vector<Op>& ops, hipStream_t st) {
-  for (const Op& op : ops) {
+static hs_status run_ops(hs_app* app, std::vector<Op>& ops, hipStream_t st) {
+  for (Op& op : ops) {
     if (app->timing) {
       TimedLaunch t{op.fam, op.flops, op.bytes, nullptr, nullptr};
       HS_HIP(hipEventCreate(&t.e0));
       HS_HIP(hipEventCreate(&t.e1));
       HS_HIP(hipEventRecord(t.e0, st));
-      launch_op(op, st);
+      HS_HIP(launch_op(op, st));
       HS_HIP(hipEventRecord(t.e1, st));
       app->timed.push_back(t);
     } else {
-      launch_op(op, st);
+      HS_HIP(launch_op(op, st));
     }
   }
-  HS_HIP(hipGetLastError());
+  return HS_OK;
+}
+
+static hipKernelNodeParams node_params(Op& op, void** args) {
+  const KernelDesc d = op_desc(op);
+  hipKernelNodeParams kp;
+  std::memset(&kp, 0, sizeof(kp));
+  kp.func = const_cast<void*>(d.func);
+  kp.gridDim = d.grid;
+  kp.blockDim = d.block;
+  kp.sharedMemBytes = d.shmem;
+  args[0] = op_params(op);
+  kp.kernelParams = args;
+  kp.extra = nullptr;
+  return kp;
+}
+
+// Stages 1-3 of one queue slot as a linear HIP graph: resize, [event], network kernels,
+// [event], postprocess.  Built once; per frame only the resize node's source pointer changes.
+static hs_status build_slot_graph(Slot& s) {
+  HS_HIP(hipGraphCreate(&s.graph, 0));
+  hipGraphNode_t prev = nullptr;
+  auto add_kernel = [&](Op& op, hipGraphNode_t* out) -> hipError_t {
+    void* args[1];
+    hipKernelNodeParams kp = node_params(op, args);
+    hipGraphNode_t n = nullptr;
+    hipError_t e = hipGraphAddKernelNode(&n, s.graph, prev ? &prev : nullptr, prev ? 1 : 0, &kp);
+    prev = n;
+    if (out) *out = n;
+    return e;
+  };
+  auto add_event = [&](hipEvent_t ev) -> hipError_t {
+    hipGraphNode_t n = nullptr;
+    hipError_t e = hipGraphAddEventRecordNode(&n, s.graph, &prev, 1, ev);
+    prev = n;
+    return e;
+  };
+  HS_HIP(add_kernel(s.pre[0], &s.resize_node));
+  HS_HIP(add_event(s.ev_pre));
+  for (Op& op : s.infer) HS_HIP(add_kernel(op, nullptr));
+  HS_HIP(add_event(s.ev_infer));
+  for (Op& op : s.post) HS_HIP(add_kernel(op, nullptr));
+  HS_HIP(hipGraphInstantiate(&s.graph_exec, s.graph, nullptr, nullptr, 0));
   return HS_OK;
 }
 
@@ -793,10 +867,12 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
   app->depth = desc->queue_depth;
   size_t need = 0;
   st = build_plan(desc, app, &need);
+  for (size_t i = 0; st == HS_OK && i < app->slots.size(); ++i) st = build_slot_graph(app->slots[i]);
   if (st == HS_OK) st = make_streams(app, nullptr, nullptr, 0);
   if (st != HS_OK) {
     for (Slot& s : app->slots) {
-      if (s.ev_begin) (void)hipEventDestroy(s.ev_begin);
+      if (s.graph_exec) (void)hipGraphExecDestroy(s.graph_exec);
+      if (s.graph) (void)hipGraphDestroy(s.graph);
       if (s.ev_pre) (void)hipEventDestroy(s.ev_pre);
       if (s.ev_infer) (void)hipEventDestroy(s.ev_infer);
       if (s.ev_post) (void)hipEventDestroy(s.ev_post);
@@ -828,7 +904,8 @@ hs_status hs_destroy_app(hs_app* app) {
   (void)hipStreamSynchronize(app->s_overlay);
   collect_timing(app);
   for (Slot& s : app->slots) {
-    (void)hipEventDestroy(s.ev_begin);
+    if (s.graph_exec) (void)hipGraphExecDestroy(s.graph_exec);
+    if (s.graph) (void)hipGraphDestroy(s.graph);
     (void)hipEventDestroy(s.ev_pre);
     (void)hipEventDestroy(s.ev_infer);
     (void)hipEventDestroy(s.ev_post);
@@ -965,21 +1042,29 @@ hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overla
   s->overlay.overlay.src = d_frame;
   s->overlay.overlay.dst = d_overlay_out;
 
-  HS_HIP(hipEventRecord(s->ev_begin, app->s_infer));
-  hs_status st = run_ops(app, s->pre, app->s_infer);
-  if (st != HS_OK) return st;
-  HS_HIP(hipEventRecord(s->ev_pre, app->s_infer));
-  st = run_ops(app, s->infer, app->s_infer);
-  if (st != HS_OK) return st;
-  HS_HIP(hipEventRecord(s->ev_infer, app->s_infer));
-  st = run_ops(app, s->post, app->s_infer);
-  if (st != HS_OK) return st;
+  hs_status st = HS_OK;
+  if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
+    void* args[1];
+    hipKernelNodeParams kp = node_params(s->pre[0], args);
+    HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_node, &kp));
+    HS_HIP(hipGraphLaunch(s->graph_exec, app->s_infer));
+  } else {
+    st = run_ops(app, s->pre, app->s_infer);
+    if (st != HS_OK) return st;
+    HS_HIP(hipEventRecord(s->ev_pre, app->s_infer));
+    st = run_ops(app, s->infer, app->s_infer);
+    if (st != HS_OK) return st;
+    HS_HIP(hipEventRecord(s->ev_infer, app->s_infer));
+    st = run_ops(app, s->post, app->s_infer);
+    if (st != HS_OK) return st;
+  }
   HS_HIP(hipEventRecord(s->ev_post, app->s_infer));
   HS_HIP(hipStreamWaitEvent(app->s_overlay, s->ev_post, 0));
   std::vector<Op> ov(1, s->overlay);
   st = run_ops(app, ov, app->s_overlay);
   if (st != HS_OK) return st;
   HS_HIP(hipEventRecord(s->ev_overlay, app->s_overlay));
+  r.t_enqueued_ns = now_ns();
   {
     std::lock_guard<std::mutex> lk(app->mu);
     s->state = SLOT_INFLIGHT;
@@ -1023,6 +1108,17 @@ hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns) {
     return HS_E_NOT_READY;
   }
   return deliver_locked(app, out);
+}
+
+hs_status hs_set_launch_mode(hs_app* app, int mode) {
+  if (!app) { set_error("hs_set_launch_mode: NULL"); return HS_E_INVAL; }
+  if (mode != HS_LAUNCH_GRAPH && mode != HS_LAUNCH_EAGER) {
+    set_error("hs_set_launch_mode: unknown mode %d", mode);
+    return HS_E_INVAL;
+  }
+  if (frames_in_flight(app)) { set_error("hs_set_launch_mode: frames in flight"); return HS_E_STATE; }
+  app->launch_mode = mode;
+  return HS_OK;
 }
 
 hs_status hs_set_kernel_timing(hs_app* app, int enable) {

@@ -150,6 +150,38 @@ def test_reset_state_and_queue_semantics(hs, ctx):
         s.close()
 
 
+def test_graph_and_kernel_by_kernel_launch_paths_agree(hs, ctx):
+    """The pre-built HIP graph of stages 1-3 is replayed for several frames (with the host's
+    own synchronisation and read-backs between replays) and must give, frame by frame and
+    bit for bit, what the kernel-by-kernel path gives, state included."""
+    from paper_2402_04466_amd.harness import AppStream
+    frames = list(si.tool_scene_frames(5, 360, 640, 11))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    kw = dict(net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=640, frame_h=360, net_w=288, net_h=160,
+              blob=blob, palette=PAL, queue_depth=2)
+    a, b = AppStream(ctx, **kw), AppStream(ctx, **kw)
+    try:
+        hs.hs_set_launch_mode(a.app, hs.HS_LAUNCH_GRAPH)
+        hs.hs_set_launch_mode(b.app, hs.HS_LAUNCH_EAGER)
+        for i, f in enumerate(frames):
+            outs = []
+            for s in (a, b):
+                d_in, d_out = s.upload_frame(f), s.new_output()
+                assert s.submit(d_in, d_out, i) == hs.HS_OK
+                r = s.wait()
+                assert r.t_submit_ns <= r.t_enqueued_ns
+                assert r.t_submit_ns <= r.t_pre_done_ns <= r.t_infer_done_ns <= r.t_post_done_ns \
+                    <= r.t_overlay_done_ns
+                g = s.fetch(r, d_out)
+                g["h"], g["c"] = s.state(r)
+                outs.append(g)
+            for k in outs[0]:
+                assert np.array_equal(outs[0][k], outs[1][k]), (i, k)
+    finally:
+        a.close()
+        b.close()
+
+
 def test_partition_admission_and_masked_results_identical(hs, ctx):
     """Two applications on disjoint CU sets; an overlapping request is refused and changes
     nothing; results under a CU mask equal the unpartitioned ones bit for bit."""
