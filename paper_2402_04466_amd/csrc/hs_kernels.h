@@ -48,10 +48,16 @@ struct ConvParams {
   int cout, cout_pad;   // cout_pad: multiple of the block's N tile
   int kc;               // 16, 32 or 64
   int depth;            // prefetch depth in chunks: 4, or 8 (kc == 64 only)
+  int variant;          // 0: generic tile of 64 consecutive pixels (k_conv_mfma)
+                        // 1, 2: 3x3/1 layers, spatial tile 8 x 8 / 8 x 16 with a shared input
+                        //       patch (k_conv3x3_halo<1|2>); needs cin % 64 == 0
+  int tiles_x;          // variant 1, 2: spatial tiles per output row
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;
   // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)
   int nsplit, chunks_per_split;
+  int tiles_m, tiles_n; // 64x64 output tiles; the grid is 8 * tiles_per_xcd workgroups
+  int tiles_per_xcd;    // ceil(tiles_m * tiles_n * nsplit / 8)
   int use_partial;      // 1: store fp32 partial sums for a reduction kernel, no epilogue here
   float* partial;       // [nsplit][m][cout_pad] fp32
   // fused epilogue (use_partial == 0)

@@ -137,8 +137,17 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
   __shared__ __align__(16) f16 s_w[2][BN * PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-  const int q_begin = blockIdx.z * p.chunks_per_split;
+  // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (workgroup id % 8),
+  // each with its own L2.  Tile t = (id % 8) * tiles_per_xcd + id / 8 gives every XCD a run of
+  // consecutive tiles (pixel tile fastest, then channel tile, then K split): the workgroups
+  // that share a weight slice, and neighbouring pixel tiles, meet in the same L2.
+  const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if (tile >= p.tiles_m * p.tiles_n * p.nsplit) return;
+  const int tile_m = tile % p.tiles_m;
+  const int tile_n = (tile / p.tiles_m) % p.tiles_n;
+  const int split = tile / (p.tiles_m * p.tiles_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int q_begin = split * p.chunks_per_split;
   const int q_end = min(p.nchunks, q_begin + p.chunks_per_split);
 
   // Per-thread loader state, fixed over the K loop: for every 16-byte vector this thread
@@ -303,7 +312,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
   // this kernel would need a device-wide release per workgroup, which on a multi-XCD part
   // means a full L2 write-back each time -- measured 3x slower than the extra launch.)
   if (m < p.m) {
-    float* dst = p.partial + ((size_t)blockIdx.z * p.m + m) * p.cout_pad + n_base;
+    float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       *reinterpret_cast<float4*>(dst + 8 * i) =
@@ -313,8 +322,165 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
 
 #undef HS_LOAD_CHUNK
 
+// =============================================================================================
+// Stage 2, 3x3 stride-1 pad-1 layers (13 of the 21 convolutions, 85 % of the flops): the same
+// implicit GEMM, but the workgroup's output tile is a SPATIAL block (8 rows x 8*MT columns),
+// so that the nine taps read one shared (8+2) x (8*MT+2) input patch.  Per 64-channel chunk
+// of Cin the patch goes to LDS once and serves all nine taps; only the weight tile (64 x 64
+// halves per tap) is streamed per tap.  Global traffic per tap drops from 16 KB to
+// 8 KB + patch/9 -- these layers are bound by bytes fetched per workgroup, not by MFMA rate.
+// Pipeline: three weight stages in registers (9 taps = 3 x 3, so the stage of a tap is a
+// literal), the next chunk's patch is prefetched during the first taps of the current one;
+// the nine steps of a chunk are written out, loads are unconditional and branch-free.
+// Wavefront (wm, wn): pixel rows 4*wm .. 4*wm+3 (MT groups of 4 x 8 pixels), channels
+// 32*wn .. +31.  chunks_per_split / nchunks count Cin chunks here (split-K over Cin).
+// =============================================================================================
+template <int MT>
+__global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
+  constexpr int KC = 64, TH = 8, TW = 8 * MT, PH = TH + 2, PW = TW + 2, NPIX = PH * PW;
+  constexpr int PITCH = KC + 8;
+  constexpr int PV = NPIX * 8;               // 16-byte vectors in a patch
+  constexpr int PL = (PV + 255) / 256;       // patch vectors per thread (4 or 6)
+  static_assert(PL <= 9, "patch prefetch is spread over the nine taps");
+  __shared__ __align__(16) f16 s_patch[2][NPIX * PITCH];
+  __shared__ __align__(16) f16 s_w[2][64 * PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if (tile >= p.tiles_m * p.tiles_n * p.nsplit) return;
+  const int tile_m = tile % p.tiles_m;
+  const int tile_n = (tile / p.tiles_m) % p.tiles_n;
+  const int split = tile / (p.tiles_m * p.tiles_n);
+  const int ty = tile_m / p.tiles_x, tx = tile_m - ty * p.tiles_x;
+  const int y0 = ty * TH, x0 = tx * TW, n0 = tile_n * 64;
+  const int cc_begin = split * p.chunks_per_split;
+  const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
+
+  // loop-invariant loader state
+  const f16* l_wbase[2];
+  int l_wlds[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int v = tid + 256 * i, row = v >> 3, kv = v & 7;
+    l_wbase[i] = p.wt + (size_t)(n0 + row) * p.ktot + kv * 8;
+    l_wlds[i] = row * PITCH + kv * 8;
+  }
+  const f16* l_pbase[PL];
+  int l_plds[PL];
+  bool l_pact[PL], l_pinb[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) {
+    const int v = tid + 256 * i;
+    const int pix = min(v >> 3, NPIX - 1), kv = v & 7;
+    const int py = pix / PW, px = pix - py * PW;
+    const int iy = y0 + py - 1, ix = x0 + px - 1;
+    l_pact[i] = v < PV;
+    l_pinb[i] = l_pact[i] && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+    l_pbase[i] = l_pinb[i] ? p.in + ((long)iy * p.win + ix) * p.cin_pitch + kv * 8 : p.in;
+    l_plds[i] = pix * PITCH + kv * 8;
+  }
+
+  floatx16 acc[MT];
+#pragma unroll
+  for (int g = 0; g < MT; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
+
+  const int wm = wave & 1, wn = wave >> 1;
+  // fragment bases: weights row (32*wn + r); pixel (4*wm + r/8, r%8) of column group g
+  const int fw_off = (wn * 32 + r) * PITCH + h * 8;
+  const int fp_off = ((4 * wm + (r >> 3)) * PW + (r & 7)) * PITCH + h * 8;
+
+  u32x4 st_w[3][2];
+  u32x4 st_p[PL];
+#define HS_LOAD_W(S_, CC_, TAP_)                                                               \
+  {                                                                                            \
+    const long off_ = ((long)(TAP_) * p.chunks_per_tap + (CC_)) * KC;                          \
+    st_w[S_][0] = *reinterpret_cast<const u32x4*>(l_wbase[0] + off_);                          \
+    st_w[S_][1] = *reinterpret_cast<const u32x4*>(l_wbase[1] + off_);                          \
+  }
+#define HS_LOAD_P(I_, CC_)                                                                     \
+  st_p[I_] = *reinterpret_cast<const u32x4*>(l_pinb[I_] ? l_pbase[I_] + (long)(CC_) * KC : p.in);
+
+  // One tap of chunk cc.  TAP_ and LAST_ are literals: every register index and every
+  // refill decision is resolved at compile time.
+#define HS_TAP(TAP_, LAST_)                                                                    \
+  {                                                                                            \
+    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[0]]) = st_w[(TAP_) % 3][0];                     \
+    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[1]]) = st_w[(TAP_) % 3][1];                     \
+    if ((TAP_) == 0) {                                                                         \
+      const u32x4 zero_ = {0u, 0u, 0u, 0u};                                                    \
+      _Pragma("unroll") for (int i = 0; i < PL; ++i)                                           \
+        if (l_pact[i])                                                                         \
+          *reinterpret_cast<u32x4*>(&s_patch[pb][l_plds[i]]) = l_pinb[i] ? st_p[i] : zero_;    \
+    }                                                                                          \
+    __syncthreads();                                                                           \
+    if ((TAP_) + 3 < 9) HS_LOAD_W((TAP_) % 3, cc, (TAP_) + 3)                                  \
+    else if (!(LAST_)) HS_LOAD_W((TAP_) % 3, cc + 1, (TAP_) + 3 - 9)                           \
+    if (!(LAST_) && (TAP_) < PL) { HS_LOAD_P((TAP_) < PL ? (TAP_) : 0, cc + 1) }               \
+    const f16* fw_ = &s_w[buf][fw_off];                                                        \
+    const f16* fp_ = &s_patch[pb][fp_off + (((TAP_) / 3) * PW + ((TAP_) % 3)) * PITCH];        \
+    _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                   \
+      const half8 a_ = *reinterpret_cast<const half8*>(fw_ + ks * 16);                         \
+      _Pragma("unroll") for (int g = 0; g < MT; ++g) {                                         \
+        const half8 b_ = *reinterpret_cast<const half8*>(fp_ + g * 8 * PITCH + ks * 16);       \
+        acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_, b_, acc[g], 0, 0, 0);              \
+      }                                                                                        \
+    }                                                                                          \
+    buf ^= 1;                                                                                  \
+  }
+#define HS_CHUNK(LAST_)                                                                        \
+  HS_TAP(0, LAST_) HS_TAP(1, LAST_) HS_TAP(2, LAST_) HS_TAP(3, LAST_) HS_TAP(4, LAST_)         \
+  HS_TAP(5, LAST_) HS_TAP(6, LAST_) HS_TAP(7, LAST_) HS_TAP(8, LAST_)
+
+  int buf = 0, pb = 0;
+  int cc = cc_begin;
+#pragma unroll
+  for (int i = 0; i < PL; ++i) HS_LOAD_P(i, cc)
+  HS_LOAD_W(0, cc, 0)
+  HS_LOAD_W(1, cc, 1)
+  HS_LOAD_W(2, cc, 2)
+  for (; cc + 1 < cc_end; ++cc) {
+    HS_CHUNK(false)
+    pb ^= 1;
+  }
+  HS_CHUNK(true)
+#undef HS_CHUNK
+#undef HS_TAP
+#undef HS_LOAD_P
+#undef HS_LOAD_W
+
+  // accumulator quad i of group g: channels n_base + 8*i .. +3 of pixel (oy, ox_g)
+  const int oy = y0 + 4 * wm + (r >> 3);
+  const int n_base = n0 + wn * 32 + h * 4;
+#pragma unroll
+  for (int g = 0; g < MT; ++g) {
+    const int ox = x0 + 8 * g + (r & 7);
+    if (oy >= p.hout || ox >= p.wout) continue;
+    const int m = oy * p.wout + ox;
+    if (p.use_partial) {
+      float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<float4*>(dst + 8 * i) = make_float4(
+            acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = n_base + 8 * i;
+        if (n >= p.cout) continue;
+        float v[4] = {acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]};
+        store_quad(p, m, n, v);
+      }
+    }
+  }
+}
+
 KernelDesc describe(const ConvParams& p) {
-  const dim3 grid((p.m + 63) / 64, p.cout_pad / 64, p.nsplit);
+  // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
+  const dim3 grid(8u * (unsigned)p.tiles_per_xcd);
+  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1>, grid, dim3(256), 0};
+  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2>, grid, dim3(256), 0};
   const void* f = p.kc == 16   ? (const void*)k_conv_mfma<16, 4>
                   : p.kc == 32 ? (const void*)k_conv_mfma<32, 4>
                   : p.depth == 8 ? (const void*)k_conv_mfma<64, 8>

@@ -207,7 +207,6 @@ static void pack_rowtap(const float* w, int cout, int k, int chunk_px, int cout_
               (f16)w[(((size_t)n * 3 + ch) * k + ky) * k + px];
 }
 
-static int g_depth = getenv("HS_DEPTH") ? atoi(getenv("HS_DEPTH")) : 8;   // experiment knob
 // ---- plan builder ------------------------------------------------------------------------------
 static inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -248,12 +247,37 @@ struct Builder {
     return off;
   }
 
+  // Picks the kernel variant, the tile grid and the split along K.
   static void choose_split(ConvParams& c) {
-    const int tiles = ((c.m + 63) / 64) * (c.cout_pad / 64);
-    int ns = 1;
-    if (tiles < 192) ns = std::max(1, std::min((320 + tiles - 1) / tiles, c.nchunks / 4));
-    c.chunks_per_split = (c.nchunks + ns - 1) / ns;
-    c.nsplit = (c.nchunks + c.chunks_per_split - 1) / c.chunks_per_split;
+    const bool halo = c.ntaps == 9 && c.kw == 3 && c.stride == 1 && c.pad == 1 && c.kc == 64;
+    if (halo) {
+      // spatial tiles of 8 x 16 pixels when that still yields enough workgroups, else 8 x 8
+      const int ty = (c.hout + 7) / 8;
+      const int wide = ty * ((c.wout + 15) / 16) * (c.cout_pad / 64);
+      c.variant = wide >= 192 ? 2 : 1;
+      const int tw = c.variant == 2 ? 16 : 8;
+      c.tiles_x = (c.wout + tw - 1) / tw;
+      c.tiles_m = ty * c.tiles_x;
+      c.tiles_n = c.cout_pad / 64;
+      const int tiles = c.tiles_m * c.tiles_n;
+      const int units = c.chunks_per_tap;        // split over Cin chunks
+      int ns = 1;
+      if (tiles < 192) ns = std::max(1, std::min((256 + tiles - 1) / tiles, units / 2));
+      c.chunks_per_split = (units + ns - 1) / ns;
+      c.nsplit = (units + c.chunks_per_split - 1) / c.chunks_per_split;
+    } else {
+      c.variant = 0;
+      c.tiles_x = 0;
+      c.tiles_m = (c.m + 63) / 64;
+      c.tiles_n = c.cout_pad / 64;
+      const int tiles = c.tiles_m * c.tiles_n;
+      int ns = 1;
+      if (tiles < 192) ns = std::max(1, std::min((320 + tiles - 1) / tiles, c.nchunks / 4));
+      c.chunks_per_split = (c.nchunks + ns - 1) / ns;
+      c.nsplit = (c.nchunks + c.chunks_per_split - 1) / c.chunks_per_split;
+    }
+    c.depth = (c.kc == 64 && c.chunks_per_split >= 12) ? 8 : 4;
+    c.tiles_per_xcd = (c.tiles_m * c.tiles_n * c.nsplit + 7) / 8;
   }
 
   // Appends the convolution and, when it is split along K, its reduction kernel.
@@ -266,7 +290,6 @@ struct Builder {
     op.flops = flops;
     c.wt = d_w ? d_w + w_off : nullptr;
     choose_split(c);
-    c.depth = (c.kc == 64 && c.chunks_per_split >= 12) ? g_depth : 4;
     const bool partial = c.nsplit > 1 || keep_partial;
     c.use_partial = partial ? 1 : 0;
     c.partial = nullptr;   // patched when the scratch buffer is carved
