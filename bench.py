@@ -48,15 +48,19 @@ def parse():
     return ap.parse_args()
 
 
-def equal_partitions(n_cus: int, n_streams: int, overlay_cus: int = 6, spare: int = 4):
-    """n_streams disjoint CU sets of equal size; inside each, the last overlay_cus CUs
-    serve the overlay stream and the rest the inference stream; `spare` CUs stay unclaimed
-    (the paper's appendix recommends leaving headroom)."""
-    per = (n_cus - spare) // n_streams
+def equal_partitions(n_cus: int, n_streams: int, overlay_groups: int = 1, spare_groups: int = 2,
+                     n_xcd: int = 8):
+    """n_streams disjoint CU sets of equal size, built from groups of n_xcd consecutive CUs
+    (CU i sits on XCD i mod n_xcd and a mask needs a CU on every XCD).  Inside each set the
+    last overlay_groups groups serve the overlay stream, the rest the inference stream;
+    spare_groups groups stay unclaimed (the paper's appendix recommends leaving headroom)."""
+    groups = n_cus // n_xcd - spare_groups
+    per = groups // n_streams
     parts = []
     for i in range(n_streams):
-        cus = list(range(i * per, (i + 1) * per))
-        parts.append((cus[:-overlay_cus], cus[-overlay_cus:]))
+        cus = list(range(i * per * n_xcd, (i + 1) * per * n_xcd))
+        k = overlay_groups * n_xcd
+        parts.append((cus[:-k], cus[-k:]))
     return parts
 
 

@@ -189,7 +189,9 @@ hs_status hs_get_features(hs_app* app, float* x_out);
  * The two masks may be equal or disjoint (compute / visualisation isolation).
  * Admission control: refused with HS_E_OVERSUBSCRIBED, changing nothing, if a mask is
  * empty, names a CU the device does not have, or intersects CUs claimed by another
- * application of the context. Passing NULL for both masks releases the claim and
+ * application of the context. On MI355X CU i belongs to XCD i mod 8 and every mask must
+ * contain at least one CU of each XCD (HS_E_INVAL otherwise): build masks from whole groups
+ * of 8 consecutive CUs. Passing NULL for both masks releases the claim and
  * returns the application to the unpartitioned state (all CUs, claims nothing).
  * HS_E_STATE while frames are in flight. */
 hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,

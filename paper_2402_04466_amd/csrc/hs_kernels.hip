@@ -632,51 +632,64 @@ KernelDesc describe(const PostParams&) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// 1x1 head fused with stage 3: workgroup k computes logits[k][m] = sum_j w[k][j] * h[m][j]
-// (fp32 accumulate, fixed order) for every pixel, then postprocesses its own channel.
+// 1x1 head fused with stage 3: workgroup k owns tool channel k.  Half a wavefront (32 lanes
+// x 8 channels = 256 input channels per round, coalesced 512-byte rows) forms the dot
+// product of one pixel, logits[k][m] = sum_j w[k][j] * h[m][j] (fp32, fixed order: lane
+// partial sums, then a 5-step butterfly); its first lane postprocesses the pixel and keeps
+// the running (best value, lowest index).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_head_post(HeadPostParams p) {
-  __shared__ __align__(16) f16 s_wk[512];
-  __shared__ float s_v[4];
-  __shared__ int s_i[4];
-  const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int c = tid; c < p.cin; c += 256) s_wk[c] = p.w[(size_t)k * p.cin + c];
-  __syncthreads();
+__global__ __launch_bounds__(512) void k_head_post(HeadPostParams p) {
+  __shared__ float s_v[16];
+  __shared__ int s_i[16];
+  const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, l32 = tid & 31, half_id = tid >> 5;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int m = tid; m < p.m; m += 256) {
-    const f16* hrow = p.h + (size_t)m * p.h_pitch;
-    float acc = 0.0f;
-    for (int c0 = 0; c0 < p.cin; c0 += 8) {
-      const half8 x = *reinterpret_cast<const half8*>(hrow + c0);
-      const half8 w = *reinterpret_cast<const half8*>(s_wk + c0);
+  constexpr int U = 8;                              // pixels in flight per half-wavefront
+  for (int m0 = 0; m0 < p.m; m0 += 16 * U) {        // 16 half-wavefronts x U pixels per round
+    float acc[U];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc += (float)x[j] * (float)w[j];
+    for (int u = 0; u < U; ++u) acc[u] = 0.0f;
+    for (int c0 = l32 * 8; c0 < p.cin; c0 += 256) {
+      const half8 w = *reinterpret_cast<const half8*>(p.w + (size_t)k * p.cin + c0);
+      half8 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int mc = min(m0 + half_id + 16 * u, p.m - 1);
+        x[u] = *reinterpret_cast<const half8*>(p.h + (size_t)mc * p.h_pitch + c0);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[u] += (float)x[u][j] * (float)w[j];
     }
-    p.logits[(size_t)k * p.m + m] = acc;
-    p.heat[(size_t)k * p.m + m] = 1.0f / (1.0f + expf(-acc));
-    p.mask[(size_t)k * p.m + m] = acc > p.theta ? 1 : 0;
-    if (better(acc, m, bv, bi)) { bv = acc; bi = m; }
-  }
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const float ov = __shfl_xor(bv, off, 64);
-    const int oi = __shfl_xor(bi, off, 64);
-    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    for (int u = 0; u < U; ++u) {
+      float a = acc[u];
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) a += __shfl_xor(a, off, 64);
+      const int m = m0 + half_id + 16 * u;
+      if (l32 == 0 && m < p.m) {
+        p.logits[(size_t)k * p.m + m] = a;
+        p.heat[(size_t)k * p.m + m] = 1.0f / (1.0f + expf(-a));
+        p.mask[(size_t)k * p.m + m] = a > p.theta ? 1 : 0;
+        if (better(a, m, bv, bi)) { bv = a; bi = m; }
+      }
+    }
   }
-  if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+  if (l32 == 0) { s_v[half_id] = bv; s_i[half_id] = bi; }
   __syncthreads();
   if (tid == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < 16; ++w)
       if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
     p.rec->argmax_idx[k] = bi;
     p.rec->peak[k] = 1.0f / (1.0f + expf(-bv));
     p.rec->present[k] = bv > p.theta ? 1 : 0;
   }
+  (void)lane;
 }
 
 KernelDesc describe(const HeadPostParams&) {
-  return KernelDesc{(const void*)k_head_post, dim3(8), dim3(256), 0};
+  return KernelDesc{(const void*)k_head_post, dim3(8), dim3(512), 0};
 }
 
 // =============================================================================================

@@ -758,9 +758,11 @@ static hs_status run_ops(hs_app* app, std::vector<Op>& ops, hipStream_t st) {
       TimedLaunch t{op.fam, op.flops, op.bytes, nullptr, nullptr};
       HS_HIP(hipEventCreate(&t.e0));
       HS_HIP(hipEventCreate(&t.e1));
-      HS_HIP(hipEventRecord(t.e0, st));
-      HS_HIP(launch_op(op, st));
-      HS_HIP(hipEventRecord(t.e1, st));
+      // events attached to the dispatch itself: elapsed = the kernel's own begin -> end
+      // time stamps, without the gap between consecutive dispatches
+      const KernelDesc d = op_desc(op);
+      void* args[1] = {op_params(op)};
+      HS_HIP(hipExtLaunchKernel(d.func, d.grid, d.block, args, d.shmem, st, t.e0, t.e1, 0));
       app->timed.push_back(t);
     } else {
       HS_HIP(launch_op(op, st));
@@ -1020,6 +1022,23 @@ hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
       for (int w = 0; w < HS_MAX_CU_WORDS; ++w) others[w] |= o->claim[w];
   hs_status st = admission_check(others, cu_mask_infer, cu_mask_overlay, n_words, ctx->n_cus);
   if (st != HS_OK) return st;
+  // The device deals workgroups to all of its XCDs, and CU i sits on XCD i mod n_xcd: a mask
+  // that leaves an XCD without a CU cannot be bound to a queue (the runtime refuses it).
+  const int n_xcd = std::max(1, ctx->n_cus / 32);
+  for (int which = 0; which < 2; ++which) {
+    const uint32_t* m = which ? cu_mask_overlay : cu_mask_infer;
+    for (int x = 0; x < n_xcd; ++x) {
+      bool any = false;
+      for (int cu = x; cu < 32 * n_words && cu < ctx->n_cus; cu += n_xcd)
+        any = any || ((m[cu / 32] >> (cu % 32)) & 1u);
+      if (!any) {
+        set_error("hs_set_partition: %s mask has no CU on XCD %d (CU i is on XCD i mod %d); "
+                  "use whole groups of %d consecutive CUs", which ? "overlay" : "inference", x,
+                  n_xcd, n_xcd);
+        return HS_E_INVAL;
+      }
+    }
+  }
   st = make_streams(app, cu_mask_infer, cu_mask_overlay, n_words);
   if (st != HS_OK) return st;
   std::memset(app->claim, 0, sizeof(app->claim));
