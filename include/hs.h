@@ -83,7 +83,12 @@ typedef struct {
                             /* [Cout][Cin][kh][kw]; copied and repacked to fp16 at create */
   size_t weight_floats;     /* number of floats in the blob; must match the network      */
   uint8_t palette[HS_NUM_TOOLS][3]; /* overlay colour per tool channel, RGB              */
-  int queue_depth;          /* frames that may be in flight or unpolled, 1..64           */
+  int queue_depth;          /* frames (batches) that may be in flight or unpolled, 1..64 */
+  int batch;                /* streams served by this application, 1..16. With batch > 1  */
+                            /* the streams share one weight copy and every submit carries */
+                            /* one frame of each stream; stages 1, 3, 4 run per stream,   */
+                            /* the network runs once over the whole batch (ConvLSTM state */
+                            /* per stream). Use hs_submit_batch / hs_poll_batch then.     */
   void* d_workspace;        /* DEVICE memory owned by the caller, 256-byte aligned       */
   size_t workspace_bytes;   /* >= hs_query_workspace(); plays the role of the per-client  */
                             /* device-memory limit of the paper's partitions              */
@@ -176,11 +181,11 @@ hs_status hs_reset_state(hs_app* app);
 /* Copy the ConvLSTM state of the last completed frame to HOST buffers, as fp32 planar
  * [256][map_h][map_w] each (either may be NULL). HS_E_STATE while frames are in flight,
  * HS_E_INVAL for a stateless network. For tests and for checkpointing a stream. */
-hs_status hs_get_state(hs_app* app, float* h_out, float* c_out);
+hs_status hs_get_state(hs_app* app, int stream, float* h_out, float* c_out);
 /* Copy the backbone's output for the last completed frame (the ConvLSTM cell's input x_t)
  * to a HOST buffer as fp32 planar [512][map_h][map_w]. Same status rules as hs_get_state.
- * Lets a test check the recurrent cell in isolation. */
-hs_status hs_get_features(hs_app* app, float* x_out);
+ * Lets a test check the recurrent cell in isolation. `stream` < batch in both calls. */
+hs_status hs_get_features(hs_app* app, int stream, float* x_out);
 
 /* ---- spatial partition + admission control (Section IV-A) ------------------------- */
 
@@ -220,6 +225,16 @@ hs_status hs_poll_result(hs_app* app, hs_result* out);
 /* As hs_poll_result, but sleeps until a frame has finished or timeout_ns elapsed
  * (HS_E_NOT_READY on time-out). */
 hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns);
+
+/* Batched applications (desc.batch = B > 1): one frame of each of the B streams per call.
+ * d_frames / d_overlay_outs are HOST arrays of B device pointers (same rules per frame as
+ * hs_submit_frame). The B frames share the time stamps of the call; results come back as B
+ * consecutive hs_result entries (stream order) written to out[0..B-1]. The single-frame
+ * calls above return HS_E_STATE on a batched application; with B = 1 both forms work. */
+hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
+                          uint8_t* const* d_overlay_outs, uint64_t frame_id);
+hs_status hs_poll_batch(hs_app* app, hs_result* out);
+hs_status hs_wait_batch(hs_app* app, hs_result* out, uint64_t timeout_ns);
 
 /* How hs_submit_frame hands stages 1-3 to the GPU: as one pre-built HIP graph per queue slot
  * (default; one launch call per frame instead of ~35) or kernel by kernel. Results are

@@ -19,7 +19,7 @@ __all__ = [
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
-    "hs_poll_result", "hs_wait_result", "hs_latency_metrics_compute", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
+    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch", "hs_latency_metrics_compute", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
     "hs_get_kernel_times", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
@@ -45,7 +45,7 @@ class hs_app_desc(C.Structure):
         ("net_w", C.c_int), ("net_h", C.c_int), ("net_fp32_input", C.c_int),
         ("mean", C.c_float), ("std", C.c_float), ("threshold", C.c_float), ("alpha", C.c_float),
         ("net", C.c_int), ("weights", C.c_void_p), ("weight_floats", C.c_size_t),
-        ("palette", (C.c_uint8 * 3) * HS_NUM_TOOLS), ("queue_depth", C.c_int),
+        ("palette", (C.c_uint8 * 3) * HS_NUM_TOOLS), ("queue_depth", C.c_int), ("batch", C.c_int),
         ("d_workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -101,8 +101,11 @@ def load() -> C.CDLL:
         "hs_create_app": (C.c_int, [C.c_void_p, P(hs_app_desc), P(C.c_void_p)]),
         "hs_destroy_app": (C.c_int, [C.c_void_p]),
         "hs_reset_state": (C.c_int, [C.c_void_p]),
-        "hs_get_state": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
-        "hs_get_features": (C.c_int, [C.c_void_p, C.c_void_p]),
+        "hs_get_state": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
+        "hs_get_features": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
+        "hs_submit_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
+        "hs_poll_batch": (C.c_int, [C.c_void_p, P(hs_result)]),
+        "hs_wait_batch": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
         "hs_set_partition": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
         "hs_admission_check": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
         "hs_submit_frame": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
@@ -139,7 +142,7 @@ def _check(status: int, soft=()) -> int:
 
 def make_desc(*, frame_w, frame_h, net_w, net_h, net, weights, palette, d_workspace=0,
               workspace_bytes=0, frame_pitch=None, net_fp32_input=0, mean=0.5, std=0.25,
-              threshold=0.5, alpha=0.5, queue_depth=2) -> hs_app_desc:
+              threshold=0.5, alpha=0.5, queue_depth=2, batch=1) -> hs_app_desc:
     """Fill an hs_app_desc.  ``weights`` is a contiguous float32 NumPy array (kept alive by
     the returned object); ``palette`` an (8, 3) uint8 array."""
     d = hs_app_desc()
@@ -157,6 +160,7 @@ def make_desc(*, frame_w, frame_h, net_w, net_h, net, weights, palette, d_worksp
         for c in range(3):
             d.palette[k][c] = int(pal[k, c])
     d.queue_depth = int(queue_depth)
+    d.batch = int(batch)
     d.d_workspace = int(d_workspace)
     d.workspace_bytes = int(workspace_bytes)
     return d
@@ -206,18 +210,18 @@ def hs_reset_state(app: int) -> None:
     _check(load().hs_reset_state(app))
 
 
-def hs_get_state(app: int, map_h: int, map_w: int, hid: int = 256):
-    """Returns (h, c) as float32 arrays of shape (hid, map_h, map_w)."""
+def hs_get_state(app: int, map_h: int, map_w: int, hid: int = 256, stream: int = 0):
+    """Returns (h, c) of one stream as float32 arrays of shape (hid, map_h, map_w)."""
     h = np.empty((hid, map_h, map_w), dtype=np.float32)
     c = np.empty((hid, map_h, map_w), dtype=np.float32)
-    _check(load().hs_get_state(app, h.ctypes.data, c.ctypes.data))
+    _check(load().hs_get_state(app, stream, h.ctypes.data, c.ctypes.data))
     return h, c
 
 
-def hs_get_features(app: int, map_h: int, map_w: int, ch: int = 512) -> np.ndarray:
+def hs_get_features(app: int, map_h: int, map_w: int, ch: int = 512, stream: int = 0) -> np.ndarray:
     """Returns the ConvLSTM cell's input of the last frame, float32 (ch, map_h, map_w)."""
     x = np.empty((ch, map_h, map_w), dtype=np.float32)
-    _check(load().hs_get_features(app, x.ctypes.data))
+    _check(load().hs_get_features(app, stream, x.ctypes.data))
     return x
 
 
@@ -261,6 +265,29 @@ def hs_wait_result(app: int, timeout_ns: int = 10_000_000_000):
     r = hs_result()
     st = _check(load().hs_wait_result(app, C.byref(r), timeout_ns), soft=(HS_E_NOT_READY,))
     return r if st == HS_OK else None
+
+
+def hs_submit_batch(app: int, d_frames, d_overlay_outs, frame_id: int) -> int:
+    """d_frames / d_overlay_outs: sequences of device pointers (ints), one per stream.
+    Returns HS_OK or HS_E_QUEUE_FULL; raises on any other status."""
+    n = len(d_frames)
+    fr = (C.c_void_p * n)(*[int(x) for x in d_frames])
+    ou = (C.c_void_p * n)(*[int(x) for x in d_overlay_outs])
+    return _check(load().hs_submit_batch(app, fr, ou, frame_id), soft=(HS_E_QUEUE_FULL,))
+
+
+def hs_poll_batch(app: int, batch: int):
+    """Returns a list of `batch` hs_result (stream order), or None if nothing has finished."""
+    r = (hs_result * batch)()
+    st = _check(load().hs_poll_batch(app, r), soft=(HS_E_NOT_READY,))
+    return list(r) if st == HS_OK else None
+
+
+def hs_wait_batch(app: int, batch: int, timeout_ns: int = 10_000_000_000):
+    """Returns a list of `batch` hs_result (stream order), or None on time-out."""
+    r = (hs_result * batch)()
+    st = _check(load().hs_wait_batch(app, r, timeout_ns), soft=(HS_E_NOT_READY,))
+    return list(r) if st == HS_OK else None
 
 
 def hs_latency_metrics_compute(latencies, trim: bool = True) -> dict:

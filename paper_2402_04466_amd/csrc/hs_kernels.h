@@ -44,7 +44,8 @@ struct ConvParams {
   const f16* in;
   const f16* wt;        // packed [cout_pad][ktot], ktot = nchunks*KC, zero rows above cout
   int hin, win, cin_pitch;
-  int hout, wout, m;    // m = hout*wout output pixels
+  int hout, wout, m;    // m = batch*hout*wout output pixels (images stacked along m)
+  int batch, img_m;     // images per launch, pixels per image (hout*wout)
   int cout, cout_pad;   // cout_pad: multiple of the block's N tile
   int kc;               // 16, 32 or 64
   int depth;            // prefetch depth in chunks: 4, or 8 (kc == 64 only)
@@ -73,7 +74,7 @@ KernelDesc describe(const ConvParams& p);
 // Sum split-K partials in split order, add residual, ReLU, store fp16 (or planar fp32).
 struct SplitKEpilogueParams {
   const float* partial; int nsplit; int m; int cout; int cout_pad;
-  f16* out; int out_pitch; const f16* res; int res_pitch; int relu; float* out_f32;
+  f16* out; int out_pitch; const f16* res; int res_pitch; int relu; float* out_f32; int img_m;
 };
 KernelDesc describe(const SplitKEpilogueParams& p);
 
@@ -87,7 +88,7 @@ struct LstmEpilogueParams {
 KernelDesc describe(const LstmEpilogueParams& p);
 
 // 3x3 stride-2 pad-1 max-pool on pixel-major fp16, c multiple of 8.
-struct MaxPoolParams { const f16* in; f16* out; int hin, win, hout, wout, c; };
+struct MaxPoolParams { const f16* in; f16* out; int hin, win, hout, wout, c, batch; };
 KernelDesc describe(const MaxPoolParams& p);
 
 // ---- stage 3: postprocess -----------------------------------------------------------------
@@ -101,6 +102,7 @@ struct PostParams {
   float theta;                   // logit threshold
   float* heat; uint8_t* mask;    // [8][n]
   PostRecord* rec;               // host-visible
+  int batch;                     // images: logits/heat/mask are [batch][8][n], rec[batch]
 };
 KernelDesc describe(const PostParams& p);
 
@@ -109,6 +111,7 @@ KernelDesc describe(const PostParams& p);
 struct HeadPostParams {
   const f16* h; int h_pitch; const f16* w; int cin; int m;
   float theta; float* logits; float* heat; uint8_t* mask; PostRecord* rec;
+  int batch;   // images: h is [batch*m] pixels, outputs [batch][8][m], rec[batch]
 };
 KernelDesc describe(const HeadPostParams& p);
 

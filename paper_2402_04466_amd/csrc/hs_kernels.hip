@@ -116,8 +116,10 @@ __device__ __forceinline__ void store_quad(const ConvParams& p, int m, int n, fl
     for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.0f);
   }
   if (p.out_f32) {
+    // planar per image: out_f32[(image * cout + channel) * img_m + pixel in image]
+    const int b = m / p.img_m, ml = m - b * p.img_m;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) p.out_f32[(size_t)(n + j) * p.m + m] = v[j];
+    for (int j = 0; j < 4; ++j) p.out_f32[((size_t)b * p.cout + n + j) * p.img_m + ml] = v[j];
   } else {
     half4 o;
 #pragma unroll
@@ -166,7 +168,8 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
     const int row = (v / VPR) % BM;      // threads beyond the tile re-load a valid row, unused
     const int kv = v % VPR;
     const int m = m0 + row;
-    const int oy = m / p.wout, ox = m - oy * p.wout;
+    const int img = m / p.img_m, ml = m - img * p.img_m;   // image of the batch, pixel in it
+    const int oy = ml / p.wout, ox = ml - oy * p.wout;
     const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
     uint32_t mask = 0;
     for (int t = 0; t < p.ntaps; ++t) {
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
       if (m < p.m && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win) mask |= 1u << t;
     }
     l_tapmask[i] = mask;
-    l_abase[i] = p.in + ((long)iy0 * p.win + ix0) * p.cin_pitch + kv * 8;
+    l_abase[i] = p.in + (((long)img * p.hin + iy0) * p.win + ix0) * p.cin_pitch + kv * 8;
     l_wbase[i] = p.wt + (size_t)(n0 + row) * p.ktot + kv * 8;
     l_lds[i] = row * PITCH + kv * 8;
   }
@@ -351,7 +354,9 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   const int tile_m = tile % p.tiles_m;
   const int tile_n = (tile / p.tiles_m) % p.tiles_n;
   const int split = tile / (p.tiles_m * p.tiles_n);
-  const int ty = tile_m / p.tiles_x, tx = tile_m - ty * p.tiles_x;
+  const int tiles_img = p.tiles_m / p.batch;            // spatial tiles per image
+  const int img = tile_m / tiles_img, tile_s = tile_m - img * tiles_img;
+  const int ty = tile_s / p.tiles_x, tx = tile_s - ty * p.tiles_x;
   const int y0 = ty * TH, x0 = tx * TW, n0 = tile_n * 64;
   const int cc_begin = split * p.chunks_per_split;
   const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
@@ -376,7 +381,8 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     const int iy = y0 + py - 1, ix = x0 + px - 1;
     l_pact[i] = v < PV;
     l_pinb[i] = l_pact[i] && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
-    l_pbase[i] = l_pinb[i] ? p.in + ((long)iy * p.win + ix) * p.cin_pitch + kv * 8 : p.in;
+    l_pbase[i] = l_pinb[i] ? p.in + (((long)img * p.hin + iy) * p.win + ix) * p.cin_pitch + kv * 8
+                           : p.in;
     l_plds[i] = pix * PITCH + kv * 8;
   }
 
@@ -457,7 +463,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   for (int g = 0; g < MT; ++g) {
     const int ox = x0 + 8 * g + (r & 7);
     if (oy >= p.hout || ox >= p.wout) continue;
-    const int m = oy * p.wout + ox;
+    const int m = img * p.img_m + oy * p.wout + ox;
     if (p.use_partial) {
       float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;
 #pragma unroll
@@ -513,8 +519,9 @@ __global__ __launch_bounds__(256) void k_splitk_epilogue(SplitKEpilogueParams p)
     for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.0f);
   }
   if (p.out_f32) {
+    const int b = m / p.img_m, ml = m - b * p.img_m;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) p.out_f32[(size_t)(n + j) * p.m + m] = v[j];
+    for (int j = 0; j < 4; ++j) p.out_f32[((size_t)b * p.cout + n + j) * p.img_m + ml] = v[j];
   } else {
     half4 o;
 #pragma unroll
@@ -559,10 +566,12 @@ KernelDesc describe(const LstmEpilogueParams& p) {
 __global__ __launch_bounds__(256) void k_maxpool(MaxPoolParams p) {
   const int cv = p.c >> 3;
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)p.hout * p.wout * cv) return;
+  if (t >= (size_t)p.batch * p.hout * p.wout * cv) return;
   const int v = (int)(t % cv);
-  const int pix = (int)(t / cv);
-  const int oy = pix / p.wout, ox = pix - oy * p.wout;
+  const int pix = (int)(t / cv);                     // output pixel over the whole batch
+  const int img = pix / (p.hout * p.wout), pl = pix - img * (p.hout * p.wout);
+  const int oy = pl / p.wout, ox = pl - oy * p.wout;
+  const f16* in = p.in + (size_t)img * p.hin * p.win * p.c;
   half8 best;
   bool first = true;
   for (int ky = 0; ky < 3; ++ky) {
@@ -572,7 +581,7 @@ __global__ __launch_bounds__(256) void k_maxpool(MaxPoolParams p) {
       const int ix = 2 * ox + kx - 1;
       if (ix < 0 || ix >= p.win) continue;
       const half8 x =
-          *reinterpret_cast<const half8*>(p.in + ((size_t)iy * p.win + ix) * p.c + v * 8);
+          *reinterpret_cast<const half8*>(in + ((size_t)iy * p.win + ix) * p.c + v * 8);
       if (first) { best = x; first = false; }
       else {
 #pragma unroll
@@ -584,7 +593,7 @@ __global__ __launch_bounds__(256) void k_maxpool(MaxPoolParams p) {
 }
 
 KernelDesc describe(const MaxPoolParams& p) {
-  const size_t n = (size_t)p.hout * p.wout * (p.c >> 3);
+  const size_t n = (size_t)p.batch * p.hout * p.wout * (p.c >> 3);
   return KernelDesc{(const void*)k_maxpool, dim3((unsigned)((n + 255) / 256)), dim3(256), 0};
 }
 
@@ -601,7 +610,9 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
   __shared__ float s_v[4];
   __shared__ int s_i[4];
   const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* L = p.logits + (size_t)k * p.n;
+  const size_t img_off = (size_t)blockIdx.y * 8 * p.n;   // image blockIdx.y of the batch
+  p.heat += img_off; p.mask += img_off; p.rec += blockIdx.y;
+  const float* L = p.logits + img_off + (size_t)k * p.n;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
   for (int i = tid; i < p.n; i += 256) {
@@ -627,8 +638,8 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
   }
 }
 
-KernelDesc describe(const PostParams&) {
-  return KernelDesc{(const void*)k_postprocess, dim3(8), dim3(256), 0};
+KernelDesc describe(const PostParams& p) {
+  return KernelDesc{(const void*)k_postprocess, dim3(8, p.batch), dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -642,6 +653,10 @@ __global__ __launch_bounds__(512) void k_head_post(HeadPostParams p) {
   __shared__ float s_v[16];
   __shared__ int s_i[16];
   const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, l32 = tid & 31, half_id = tid >> 5;
+  // image blockIdx.y of the batch: its m pixels, its [8][m] outputs, its record
+  p.h += (size_t)blockIdx.y * p.m * p.h_pitch;
+  p.logits += (size_t)blockIdx.y * 8 * p.m; p.heat += (size_t)blockIdx.y * 8 * p.m;
+  p.mask += (size_t)blockIdx.y * 8 * p.m; p.rec += blockIdx.y;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
   constexpr int U = 8;                              // pixels in flight per half-wavefront
@@ -688,8 +703,8 @@ __global__ __launch_bounds__(512) void k_head_post(HeadPostParams p) {
   (void)lane;
 }
 
-KernelDesc describe(const HeadPostParams&) {
-  return KernelDesc{(const void*)k_head_post, dim3(8), dim3(512), 0};
+KernelDesc describe(const HeadPostParams& p) {
+  return KernelDesc{(const void*)k_head_post, dim3(8, p.batch), dim3(512), 0};
 }
 
 // =============================================================================================

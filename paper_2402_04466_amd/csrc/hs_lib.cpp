@@ -110,24 +110,24 @@ struct Tensor {
 enum SlotState { SLOT_FREE = 0, SLOT_INFLIGHT = 1, SLOT_DONE = 2 };
 
 struct Slot {
-  std::vector<Op> pre;     // stage 1
-  std::vector<Op> infer;   // stage 2
+  std::vector<Op> pre;     // stage 1: one resize per stream of the batch
+  std::vector<Op> infer;   // stage 2: the network over the whole batch
   std::vector<Op> post;    // stage 3
-  Op overlay;              // stage 4
+  std::vector<Op> overlay; // stage 4: one overlay per stream of the batch
   hipEvent_t ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr, ev_overlay = nullptr;
   // stages 1-3 as one HIP graph (kernel nodes chained in order, event-record nodes at the
   // stage boundaries); only the frame pointer of the first node changes from frame to frame
   hipGraph_t graph = nullptr;
   hipGraphExec_t graph_exec = nullptr;
-  hipGraphNode_t resize_node = nullptr;
-  PostRecord* rec = nullptr;   // pinned host memory, written by the stage-3 kernel
-  f16* d_netin = nullptr;
+  std::vector<hipGraphNode_t> resize_nodes;
+  PostRecord* rec = nullptr;   // [batch], pinned host memory, written by the stage-3 kernel
+  f16* d_netin = nullptr;      // [batch] padded images
   float* d_netin_f32 = nullptr;
-  float* d_logits = nullptr;
+  float* d_logits = nullptr;   // [batch][8][n]
   float* d_heat = nullptr;
   uint8_t* d_mask = nullptr;
   int state = SLOT_FREE;
-  hs_result result;
+  std::vector<hs_result> results;   // one per stream of the batch
 };
 
 struct TimedLaunch {
@@ -151,6 +151,7 @@ struct hs_app {
   hs_ctx* ctx = nullptr;
   hs_app_desc desc;
   int map_w = 0, map_h = 0;
+  int batch = 1;
   int netin_w = 0, netin_h = 0, netin_pad = 0;   // padded stage-1 output geometry
   bool stateful = false;
   // recurrent state
@@ -253,11 +254,11 @@ struct Builder {
     if (halo) {
       // spatial tiles of 8 x 16 pixels when that still yields enough workgroups, else 8 x 8
       const int ty = (c.hout + 7) / 8;
-      const int wide = ty * ((c.wout + 15) / 16) * (c.cout_pad / 64);
+      const int wide = c.batch * ty * ((c.wout + 15) / 16) * (c.cout_pad / 64);
       c.variant = wide >= 192 ? 2 : 1;
       const int tw = c.variant == 2 ? 16 : 8;
       c.tiles_x = (c.wout + tw - 1) / tw;
-      c.tiles_m = ty * c.tiles_x;
+      c.tiles_m = c.batch * ty * c.tiles_x;
       c.tiles_n = c.cout_pad / 64;
       const int tiles = c.tiles_m * c.tiles_n;
       const int units = c.chunks_per_tap;        // split over Cin chunks
@@ -317,6 +318,7 @@ struct Builder {
       s.res = res ? res->p : nullptr; s.res_pitch = res ? res->pitch : 0;
       s.relu = relu ? 1 : 0;
       s.out_f32 = nullptr;
+      s.img_m = c.img_m;
       ops.push_back(e);
       if (want_f32) logits_op = (int)ops.size() - 1;
     }
@@ -332,7 +334,7 @@ struct Builder {
     std::memset(&g, 0, sizeof(g));
     g.in = in.p; g.hin = in.h; g.win = in.w; g.cin_pitch = in.pitch;
     g.hout = conv_out(in.h, k, stride, pad); g.wout = conv_out(in.w, k, stride, pad);
-    g.m = g.hout * g.wout;
+    g.batch = d.batch; g.img_m = g.hout * g.wout; g.m = g.batch * g.img_m;
     g.cout = cout; g.cout_pad = round_up(cout, 64);
     g.kc = (cin % 64 == 0) ? 64 : (cin % 32 == 0 ? 32 : 16);
     g.ntaps = k * k; g.kw = k; g.chunks_per_tap = cin / g.kc;
@@ -354,7 +356,7 @@ struct Builder {
     g.in = nullptr;   // per slot
     g.hin = pad_img_h; g.win = pad_img_w; g.cin_pitch = 4;
     g.hout = conv_out(d.net_h, k, 2, pad); g.wout = conv_out(d.net_w, k, 2, pad);
-    g.m = g.hout * g.wout;
+    g.batch = d.batch; g.img_m = g.hout * g.wout; g.m = g.batch * g.img_m;
     g.cout = cout; g.cout_pad = round_up(cout, 64);
     g.kc = chunk_px * 4;
     g.ntaps = k; g.kw = 1; g.chunks_per_tap = 1; g.nchunks = k; g.ktot = k * g.kc;
@@ -370,9 +372,10 @@ struct Builder {
     const int h1 = conv_out(d.net_h, 3, 2, 1), w1 = conv_out(d.net_w, 3, 2, 1);
     const int h2 = conv_out(h1, 3, 2, 1), w2 = conv_out(w1, 3, 2, 1);
     Tensor t1, t2, t3, lg;
-    t1.p = acts<f16>((size_t)h1 * w1 * 16); t1.pitch = 16;
-    t2.p = acts<f16>((size_t)h2 * w2 * 32); t2.pitch = 32;
-    t3.p = acts<f16>((size_t)h2 * w2 * 32); t3.pitch = 32;
+    const size_t nb = (size_t)d.batch;
+    t1.p = acts<f16>(nb * h1 * w1 * 16); t1.pitch = 16;
+    t2.p = acts<f16>(nb * h2 * w2 * 32); t2.pitch = 32;
+    t3.p = acts<f16>(nb * h2 * w2 * 32); t3.pitch = 32;
     size_t at = 0;
     first_layer(at, ph, pw, 16, 3, &t1);                                 at += 16 * 3 * 9;
     conv_layer(t1, at, 32, 3, 2, 1, true, nullptr, &t2, false, false);   at += 32 * 16 * 9;
@@ -387,11 +390,12 @@ struct Builder {
     const int hp = conv_out(hs_, 3, 2, 1), wp = conv_out(ws_, 3, 2, 1);
     int hf = hp, wf = wp;
     for (int i = 0; i < 3; ++i) { hf = conv_out(hf, 3, 2, 1); wf = conv_out(wf, 3, 2, 1); }
-    const int mf = hf * wf;
+    const size_t nb = (size_t)d.batch;
+    const int mf = (int)nb * hf * wf;                    // feature-map pixels over the batch
     Tensor stem;
-    stem.p = acts<f16>((size_t)hs_ * ws_ * 64); stem.pitch = 64;
+    stem.p = acts<f16>(nb * hs_ * ws_ * 64); stem.pitch = 64;
     Tensor buf[4];
-    for (int i = 0; i < 4; ++i) buf[i].p = acts<f16>((size_t)hp * wp * 64);
+    for (int i = 0; i < 4; ++i) buf[i].p = acts<f16>(nb * hp * wp * 64);
     f16* concat = acts<f16>((size_t)mf * 768);
     float* cstate = acts<float>((size_t)mf * 256);
 
@@ -401,8 +405,8 @@ struct Builder {
     {
       Op op;
       op.fam = F_MAXPOOL;
-      op.pool = MaxPoolParams{stem.p, buf[0].p, hs_, ws_, hp, wp, 64};
-      op.bytes = ((double)hs_ * ws_ + (double)hp * wp) * 64 * 2;
+      op.pool = MaxPoolParams{stem.p, buf[0].p, hs_, ws_, hp, wp, 64, d.batch};
+      op.bytes = nb * ((double)hs_ * ws_ + (double)hp * wp) * 64 * 2;
       ops.push_back(op);
     }
     int cur = 0;
@@ -459,8 +463,8 @@ struct Builder {
       Op op;
       op.fam = F_HEADPOST;
       op.headpost = HeadPostParams{concat ? concat + 512 : nullptr, 768,
-                                   d_w ? d_w + w_off : nullptr, 256, mf, 0.0f, nullptr, nullptr,
-                                   nullptr, nullptr};
+                                   d_w ? d_w + w_off : nullptr, 256, hf * wf, 0.0f, nullptr,
+                                   nullptr, nullptr, nullptr, d.batch};
       op.flops = 2.0 * mf * 8 * 256;
       ops.push_back(op);
       logits_op = (int)ops.size() - 1;
@@ -525,6 +529,10 @@ static hs_status validate_desc(const hs_app_desc* d) {
     set_error("std must be > 0, threshold in (0,1), alpha in [0,1]");
     return HS_E_INVAL;
   }
+  if (d->batch < 1 || d->batch > 16) {
+    set_error("batch must be 1..16");
+    return HS_E_INVAL;
+  }
   if (d->queue_depth < 1 || d->queue_depth > 64) {
     set_error("queue_depth must be 1..64");
     return HS_E_INVAL;
@@ -563,15 +571,16 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   f16* d_lut16 = b.carve.take<f16>(256);
   const int mh = b.map_h, mw = b.map_w;
   const size_t n_map = (size_t)mh * mw;
+  const int B = d->batch;
   struct SlotBuf { f16* netin; float* netin32; float* logits; float* heat; uint8_t* mask; };
   std::vector<SlotBuf> sb(depth);
   for (int i = 0; i < depth; ++i) {
-    sb[i].netin = b.carve.take<f16>((size_t)ph * pw * 4);
-    sb[i].netin32 = d->net_fp32_input ? b.carve.take<float>((size_t)3 * d->net_h * d->net_w)
+    sb[i].netin = b.carve.take<f16>((size_t)B * ph * pw * 4);
+    sb[i].netin32 = d->net_fp32_input ? b.carve.take<float>((size_t)B * 3 * d->net_h * d->net_w)
                                       : nullptr;
-    sb[i].logits = b.carve.take<float>(8 * n_map);
-    sb[i].heat = b.carve.take<float>(8 * n_map);
-    sb[i].mask = b.carve.take<uint8_t>(8 * n_map);
+    sb[i].logits = b.carve.take<float>(B * 8 * n_map);
+    sb[i].heat = b.carve.take<float>(B * 8 * n_map);
+    sb[i].mask = b.carve.take<uint8_t>(B * 8 * n_map);
   }
   const size_t total = round_up_sz(b.carve.off, 256);
   if (bytes_out) *bytes_out = total;
@@ -581,7 +590,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     set_error("workspace too small: %zu bytes given, %zu needed", d->workspace_bytes, total);
     return HS_E_NOMEM;
   }
-  app->map_h = mh; app->map_w = mw; app->stateful = b.stateful;
+  app->map_h = mh; app->map_w = mw; app->stateful = b.stateful; app->batch = B;
   app->d_c = b.d_c; app->d_concat = b.d_concat; app->concat_pitch = 768; app->hid = 256;
   app->x_ch = 512;
 
@@ -598,10 +607,10 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     HS_HIP(hipMemcpy(d_lut16, lut16, sizeof(lut16), hipMemcpyHostToDevice));
   }
   for (int i = 0; i < depth; ++i)
-    HS_HIP(hipMemset(sb[i].netin, 0, (size_t)ph * pw * 4 * sizeof(f16)));
+    HS_HIP(hipMemset(sb[i].netin, 0, (size_t)B * ph * pw * 4 * sizeof(f16)));
   if (app->stateful) {
-    HS_HIP(hipMemset(app->d_c, 0, n_map * 256 * sizeof(float)));
-    HS_HIP(hipMemset(app->d_concat, 0, n_map * 768 * sizeof(f16)));
+    HS_HIP(hipMemset(app->d_c, 0, B * n_map * 256 * sizeof(float)));
+    HS_HIP(hipMemset(app->d_concat, 0, B * n_map * 768 * sizeof(f16)));
   }
   HS_HIP(hipDeviceSynchronize());
 
@@ -610,26 +619,30 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   const double theta_d = std::log((double)d->threshold / (1.0 - (double)d->threshold));
   int a_q8 = (int)lrint(256.0 * (double)d->alpha);
   a_q8 = std::max(0, std::min(256, a_q8));
-  HS_HIP(hipHostMalloc(&app->pinned, sizeof(PostRecord) * depth, hipHostMallocDefault));
-  std::memset(app->pinned, 0, sizeof(PostRecord) * depth);
+  HS_HIP(hipHostMalloc(&app->pinned, sizeof(PostRecord) * depth * B, hipHostMallocDefault));
+  std::memset(app->pinned, 0, sizeof(PostRecord) * depth * B);
   app->slots.resize(depth);
   for (int i = 0; i < depth; ++i) {
     Slot& s = app->slots[i];
     s.d_netin = sb[i].netin; s.d_netin_f32 = sb[i].netin32;
     s.d_logits = sb[i].logits; s.d_heat = sb[i].heat; s.d_mask = sb[i].mask;
-    s.rec = (PostRecord*)app->pinned + i;
-    Op r;
-    r.fam = F_RESIZE;
-    ResizeParams& rp = r.resize;
-    rp.src = nullptr; rp.src_pitch = d->frame_pitch;
-    rp.wi = d->frame_w; rp.hi = d->frame_h; rp.wo = d->net_w; rp.ho = d->net_h;
-    rp.dst = s.d_netin; rp.dst_w = pw; rp.pad_l = pad; rp.pad_t = pad;
-    rp.dst_f32 = s.d_netin_f32; rp.lut32 = d_lut32; rp.lut16 = d_lut16;
-    rp.rcp_dx = 1.0f / (2.0f * d->net_w); rp.rcp_dy = 1.0f / (2.0f * d->net_h);
-    rp.rcp_d = 1.0f / (4.0f * (float)d->net_w * (float)d->net_h);
-    r.bytes = 3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
-              (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0);
-    s.pre.push_back(r);
+    s.rec = (PostRecord*)app->pinned + (size_t)i * B;
+    s.results.resize(B);
+    for (int j = 0; j < B; ++j) {
+      Op r;
+      r.fam = F_RESIZE;
+      ResizeParams& rp = r.resize;
+      rp.src = nullptr; rp.src_pitch = d->frame_pitch;
+      rp.wi = d->frame_w; rp.hi = d->frame_h; rp.wo = d->net_w; rp.ho = d->net_h;
+      rp.dst = s.d_netin + (size_t)j * ph * pw * 4; rp.dst_w = pw; rp.pad_l = pad; rp.pad_t = pad;
+      rp.dst_f32 = s.d_netin_f32 ? s.d_netin_f32 + (size_t)j * 3 * d->net_h * d->net_w : nullptr;
+      rp.lut32 = d_lut32; rp.lut16 = d_lut16;
+      rp.rcp_dx = 1.0f / (2.0f * d->net_w); rp.rcp_dy = 1.0f / (2.0f * d->net_h);
+      rp.rcp_d = 1.0f / (4.0f * (float)d->net_w * (float)d->net_h);
+      r.bytes = 3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
+                (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0);
+      s.pre.push_back(r);
+    }
     s.infer = b.ops;
     s.infer[b.first_conv_op].conv.in = s.d_netin;
     Op& lo = s.infer[b.logits_op];
@@ -637,8 +650,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits; else lo.splitk.out_f32 = s.d_logits;
       Op p;
       p.fam = F_POST;
-      p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec};
-      p.bytes = 8.0 * n_map * (4 + 4 + 1);
+      p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec, B};
+      p.bytes = B * 8.0 * n_map * (4 + 4 + 1);
       s.post.push_back(p);
     } else {
       // the head kernel computes the logits and postprocesses them: it is stage 3's launch
@@ -648,16 +661,20 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       s.post.push_back(lo);
       s.infer.erase(s.infer.begin() + b.logits_op);
     }
-    Op& o = s.overlay;
-    o.fam = F_OVERLAY;
-    OverlayParams& op = o.overlay;
-    op.src = nullptr; op.dst = nullptr; op.pitch = d->frame_pitch;
-    op.wf = d->frame_w; op.hf = d->frame_h; op.mask = s.d_mask; op.wm = mw; op.hm = mh;
-    op.a = a_q8;
-    for (int k = 0; k < 8; ++k)
-      op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
-                  ((uint32_t)d->palette[k][2] << 16);
-    o.bytes = 6.0 * d->frame_w * d->frame_h + 8.0 * n_map;
+    for (int j = 0; j < B; ++j) {
+      Op o;
+      o.fam = F_OVERLAY;
+      OverlayParams& op = o.overlay;
+      op.src = nullptr; op.dst = nullptr; op.pitch = d->frame_pitch;
+      op.wf = d->frame_w; op.hf = d->frame_h; op.mask = s.d_mask + (size_t)j * 8 * n_map;
+      op.wm = mw; op.hm = mh;
+      op.a = a_q8;
+      for (int k = 0; k < 8; ++k)
+        op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
+                    ((uint32_t)d->palette[k][2] << 16);
+      o.bytes = 6.0 * d->frame_w * d->frame_h + 8.0 * n_map;
+      s.overlay.push_back(o);
+    }
     HS_HIP(hipEventCreate(&s.ev_pre));
     HS_HIP(hipEventCreate(&s.ev_infer));
     HS_HIP(hipEventCreate(&s.ev_post));
@@ -679,8 +696,6 @@ static void completer_main(hs_app* app) {
     }
     hipError_t e = hipEventSynchronize(s->ev_overlay);
     const uint64_t t_done = now_ns();
-    hs_result& r = s->result;
-    r.t_overlay_done_ns = t_done;
     float ms_pre = 0, ms_inf = 0, ms_post = 0;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms_pre, s->ev_pre, s->ev_overlay);
     if (e == hipSuccess) e = hipEventElapsedTime(&ms_inf, s->ev_infer, s->ev_overlay);
@@ -689,12 +704,16 @@ static void completer_main(hs_app* app) {
       const double ns = (double)ms * 1e6;
       return t_done - (uint64_t)std::max(0.0, ns);
     };
-    r.t_pre_done_ns = back(ms_pre);
-    r.t_infer_done_ns = back(ms_inf);
-    r.t_post_done_ns = back(ms_post);
-    std::memcpy(r.argmax_idx, s->rec->argmax_idx, sizeof(r.argmax_idx));
-    std::memcpy(r.peak, s->rec->peak, sizeof(r.peak));
-    std::memcpy(r.present, s->rec->present, sizeof(r.present));
+    for (size_t j = 0; j < s->results.size(); ++j) {
+      hs_result& r = s->results[j];
+      r.t_overlay_done_ns = t_done;
+      r.t_pre_done_ns = back(ms_pre);
+      r.t_infer_done_ns = back(ms_inf);
+      r.t_post_done_ns = back(ms_post);
+      std::memcpy(r.argmax_idx, s->rec[j].argmax_idx, sizeof(r.argmax_idx));
+      std::memcpy(r.peak, s->rec[j].peak, sizeof(r.peak));
+      std::memcpy(r.present, s->rec[j].present, sizeof(r.present));
+    }
     {
       std::lock_guard<std::mutex> lk(app->mu);
       if (e != hipSuccess && app->completer_error.empty())
@@ -805,7 +824,8 @@ static hs_status build_slot_graph(Slot& s) {
     prev = n;
     return e;
   };
-  HS_HIP(add_kernel(s.pre[0], &s.resize_node));
+  s.resize_nodes.resize(s.pre.size());
+  for (size_t j = 0; j < s.pre.size(); ++j) HS_HIP(add_kernel(s.pre[j], &s.resize_nodes[j]));
   HS_HIP(add_event(s.ev_pre));
   for (Op& op : s.infer) HS_HIP(add_kernel(op, nullptr));
   HS_HIP(add_event(s.ev_infer));
@@ -953,7 +973,7 @@ hs_status hs_reset_state(hs_app* app) {
   if (frames_in_flight(app)) { set_error("hs_reset_state: frames in flight"); return HS_E_STATE; }
   if (!app->stateful) return HS_OK;
   HS_HIP(hipSetDevice(app->ctx->device));
-  const size_t n = (size_t)app->map_w * app->map_h;
+  const size_t n = (size_t)app->map_w * app->map_h * app->batch;
   launch_fill_zero(app->d_c, n * app->hid * sizeof(float), app->s_infer);
   launch_fill_zero(app->d_concat, n * app->concat_pitch * sizeof(f16), app->s_infer);
   HS_HIP(hipGetLastError());
@@ -961,22 +981,25 @@ hs_status hs_reset_state(hs_app* app) {
   return HS_OK;
 }
 
-hs_status hs_get_state(hs_app* app, float* h_out, float* c_out) {
+hs_status hs_get_state(hs_app* app, int stream, float* h_out, float* c_out) {
   if (!app) { set_error("hs_get_state: NULL"); return HS_E_INVAL; }
   if (!app->stateful) { set_error("hs_get_state: network has no recurrent state"); return HS_E_INVAL; }
+  if (stream < 0 || stream >= app->batch) { set_error("hs_get_state: no stream %d", stream); return HS_E_INVAL; }
   if (frames_in_flight(app)) { set_error("hs_get_state: frames in flight"); return HS_E_STATE; }
   HS_HIP(hipSetDevice(app->ctx->device));
   const size_t n = (size_t)app->map_w * app->map_h;
   const int hid = app->hid;
   if (c_out) {
     std::vector<float> tmp(n * hid);
-    HS_HIP(hipMemcpy(tmp.data(), app->d_c, tmp.size() * sizeof(float), hipMemcpyDeviceToHost));
+    HS_HIP(hipMemcpy(tmp.data(), app->d_c + (size_t)stream * n * hid, tmp.size() * sizeof(float),
+                     hipMemcpyDeviceToHost));
     for (size_t m = 0; m < n; ++m)
       for (int j = 0; j < hid; ++j) c_out[(size_t)j * n + m] = tmp[m * hid + j];
   }
   if (h_out) {
     std::vector<f16> tmp(n * app->concat_pitch);
-    HS_HIP(hipMemcpy(tmp.data(), app->d_concat, tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
+    HS_HIP(hipMemcpy(tmp.data(), app->d_concat + (size_t)stream * n * app->concat_pitch,
+                     tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
     for (size_t m = 0; m < n; ++m)
       for (int j = 0; j < hid; ++j)
         h_out[(size_t)j * n + m] = (float)tmp[m * app->concat_pitch + app->x_ch + j];
@@ -984,14 +1007,16 @@ hs_status hs_get_state(hs_app* app, float* h_out, float* c_out) {
   return HS_OK;
 }
 
-hs_status hs_get_features(hs_app* app, float* x_out) {
+hs_status hs_get_features(hs_app* app, int stream, float* x_out) {
   if (!app || !x_out) { set_error("hs_get_features: NULL"); return HS_E_INVAL; }
   if (!app->stateful) { set_error("hs_get_features: network has no recurrent cell"); return HS_E_INVAL; }
+  if (stream < 0 || stream >= app->batch) { set_error("hs_get_features: no stream %d", stream); return HS_E_INVAL; }
   if (frames_in_flight(app)) { set_error("hs_get_features: frames in flight"); return HS_E_STATE; }
   HS_HIP(hipSetDevice(app->ctx->device));
   const size_t n = (size_t)app->map_w * app->map_h;
   std::vector<f16> tmp(n * app->concat_pitch);
-  HS_HIP(hipMemcpy(tmp.data(), app->d_concat, tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
+  HS_HIP(hipMemcpy(tmp.data(), app->d_concat + (size_t)stream * n * app->concat_pitch,
+                   tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
   for (size_t m = 0; m < n; ++m)
     for (int j = 0; j < app->x_ch; ++j)
       x_out[(size_t)j * n + m] = (float)tmp[m * app->concat_pitch + j];
@@ -1047,15 +1072,19 @@ hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
   return HS_OK;
 }
 
-hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
-                          uint64_t frame_id) {
+hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
+                          uint8_t* const* d_overlay_outs, uint64_t frame_id) {
   const uint64_t t_submit = now_ns();
-  if (!app || !d_frame || !d_overlay_out) { set_error("hs_submit_frame: NULL argument"); return HS_E_INVAL; }
-  if (((uintptr_t)d_frame & 15) || ((uintptr_t)d_overlay_out & 15)) {
-    set_error("hs_submit_frame: frame pointers must be 16-byte aligned");
-    return HS_E_INVAL;
+  if (!app || !d_frames || !d_overlay_outs) { set_error("hs_submit_batch: NULL argument"); return HS_E_INVAL; }
+  const int B = app->batch;
+  for (int j = 0; j < B; ++j) {
+    if (!d_frames[j] || !d_overlay_outs[j]) { set_error("hs_submit_batch: NULL frame pointer"); return HS_E_INVAL; }
+    if (((uintptr_t)d_frames[j] & 15) || ((uintptr_t)d_overlay_outs[j] & 15)) {
+      set_error("hs_submit_batch: frame pointers must be 16-byte aligned");
+      return HS_E_INVAL;
+    }
+    if (d_frames[j] == d_overlay_outs[j]) { set_error("hs_submit_batch: output aliases input"); return HS_E_INVAL; }
   }
-  if (d_frame == d_overlay_out) { set_error("hs_submit_frame: output aliases input"); return HS_E_INVAL; }
   Slot* s = nullptr;
   {
     std::lock_guard<std::mutex> lk(app->mu);
@@ -1064,31 +1093,42 @@ hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overla
       return HS_E_DEVICE;
     }
     if (app->n_submitted - app->n_delivered >= (uint64_t)app->depth) {
-      set_error("hs_submit_frame: queue full (%d slots)", app->depth);
+      set_error("hs_submit_batch: queue full (%d slots)", app->depth);
       return HS_E_QUEUE_FULL;
     }
     s = &app->slots[app->n_submitted % app->depth];
   }
   HS_HIP(hipSetDevice(app->ctx->device));
-  hs_result& r = s->result;
-  std::memset(&r, 0, sizeof(r));
-  r.frame_id = frame_id;
-  r.t_submit_ns = t_submit;
-  r.map_w = app->map_w; r.map_h = app->map_h;
-  r.net_input_pitch_bytes = (size_t)app->netin_w * 4 * sizeof(f16);
-  r.d_overlay = d_overlay_out;
-  r.d_mask = s->d_mask; r.d_heat = s->d_heat; r.d_logits = s->d_logits;
-  r.d_net_input = s->d_netin + ((size_t)app->netin_pad * app->netin_w + app->netin_pad) * 4;
-  r.d_net_input_f32 = s->d_netin_f32;
-  s->pre[0].resize.src = d_frame;
-  s->overlay.overlay.src = d_frame;
-  s->overlay.overlay.dst = d_overlay_out;
+  const size_t n_map = (size_t)app->map_w * app->map_h;
+  const size_t netin_img = (size_t)app->netin_h * app->netin_w * 4;
+  for (int j = 0; j < B; ++j) {
+    hs_result& r = s->results[j];
+    std::memset(&r, 0, sizeof(r));
+    r.frame_id = frame_id;
+    r.t_submit_ns = t_submit;
+    r.map_w = app->map_w; r.map_h = app->map_h;
+    r.net_input_pitch_bytes = (size_t)app->netin_w * 4 * sizeof(f16);
+    r.d_overlay = d_overlay_outs[j];
+    r.d_mask = s->d_mask + j * 8 * n_map;
+    r.d_heat = s->d_heat + j * 8 * n_map;
+    r.d_logits = s->d_logits + j * 8 * n_map;
+    r.d_net_input = s->d_netin + j * netin_img +
+                    ((size_t)app->netin_pad * app->netin_w + app->netin_pad) * 4;
+    r.d_net_input_f32 = s->d_netin_f32
+                            ? s->d_netin_f32 + (size_t)j * 3 * app->desc.net_h * app->desc.net_w
+                            : nullptr;
+    s->pre[j].resize.src = d_frames[j];
+    s->overlay[j].overlay.src = d_frames[j];
+    s->overlay[j].overlay.dst = d_overlay_outs[j];
+  }
 
   hs_status st = HS_OK;
   if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
-    void* args[1];
-    hipKernelNodeParams kp = node_params(s->pre[0], args);
-    HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_node, &kp));
+    for (int j = 0; j < B; ++j) {
+      void* args[1];
+      hipKernelNodeParams kp = node_params(s->pre[j], args);
+      HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_nodes[j], &kp));
+    }
     HS_HIP(hipGraphLaunch(s->graph_exec, app->s_infer));
   } else {
     st = run_ops(app, s->pre, app->s_infer);
@@ -1102,11 +1142,11 @@ hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overla
   }
   HS_HIP(hipEventRecord(s->ev_post, app->s_infer));
   HS_HIP(hipStreamWaitEvent(app->s_overlay, s->ev_post, 0));
-  std::vector<Op> ov(1, s->overlay);
-  st = run_ops(app, ov, app->s_overlay);
+  st = run_ops(app, s->overlay, app->s_overlay);
   if (st != HS_OK) return st;
   HS_HIP(hipEventRecord(s->ev_overlay, app->s_overlay));
-  r.t_enqueued_ns = now_ns();
+  const uint64_t t_enq = now_ns();
+  for (int j = 0; j < B; ++j) s->results[j].t_enqueued_ns = t_enq;
   {
     std::lock_guard<std::mutex> lk(app->mu);
     s->state = SLOT_INFLIGHT;
@@ -1116,10 +1156,24 @@ hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overla
   return HS_OK;
 }
 
+hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
+                          uint64_t frame_id) {
+  if (!app) { set_error("hs_submit_frame: NULL argument"); return HS_E_INVAL; }
+  if (app->batch != 1) {
+    set_error("hs_submit_frame: the application batches %d streams; use hs_submit_batch", app->batch);
+    return HS_E_STATE;
+  }
+  return hs_submit_batch(app, &d_frame, &d_overlay_out, frame_id);
+}
+
+// Copies the oldest finished batch's results (one per stream) out and frees its slot.
 static hs_status deliver_locked(hs_app* app, hs_result* out) {
   Slot& s = app->slots[app->n_delivered % app->depth];
-  *out = s.result;
-  out->t_observed_ns = now_ns();
+  const uint64_t t_obs = now_ns();
+  for (size_t j = 0; j < s.results.size(); ++j) {
+    out[j] = s.results[j];
+    out[j].t_observed_ns = t_obs;
+  }
   s.state = SLOT_FREE;
   app->n_delivered++;
   if (!app->completer_error.empty()) {
@@ -1129,27 +1183,43 @@ static hs_status deliver_locked(hs_app* app, hs_result* out) {
   return HS_OK;
 }
 
-hs_status hs_poll_result(hs_app* app, hs_result* out) {
-  if (!app || !out) { set_error("hs_poll_result: NULL argument"); return HS_E_INVAL; }
+hs_status hs_poll_batch(hs_app* app, hs_result* out) {
+  if (!app || !out) { set_error("hs_poll_batch: NULL argument"); return HS_E_INVAL; }
   std::lock_guard<std::mutex> lk(app->mu);
   if (app->n_delivered >= app->n_completed) {
-    set_error("hs_poll_result: no finished frame");
+    set_error("hs_poll_batch: no finished frame");
     return HS_E_NOT_READY;
   }
   return deliver_locked(app, out);
 }
 
-hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns) {
-  if (!app || !out) { set_error("hs_wait_result: NULL argument"); return HS_E_INVAL; }
+hs_status hs_wait_batch(hs_app* app, hs_result* out, uint64_t timeout_ns) {
+  if (!app || !out) { set_error("hs_wait_batch: NULL argument"); return HS_E_INVAL; }
   std::unique_lock<std::mutex> lk(app->mu);
   const bool ok = app->cv_done.wait_for(lk, std::chrono::nanoseconds(timeout_ns), [&] {
     return app->n_delivered < app->n_completed;
   });
   if (!ok) {
-    set_error("hs_wait_result: timed out");
+    set_error("hs_wait_batch: timed out");
     return HS_E_NOT_READY;
   }
   return deliver_locked(app, out);
+}
+
+hs_status hs_poll_result(hs_app* app, hs_result* out) {
+  if (app && app->batch != 1) {
+    set_error("hs_poll_result: the application batches %d streams; use hs_poll_batch", app->batch);
+    return HS_E_STATE;
+  }
+  return hs_poll_batch(app, out);
+}
+
+hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns) {
+  if (app && app->batch != 1) {
+    set_error("hs_wait_result: the application batches %d streams; use hs_wait_batch", app->batch);
+    return HS_E_STATE;
+  }
+  return hs_wait_batch(app, out, timeout_ns);
 }
 
 hs_status hs_set_launch_mode(hs_app* app, int mode) {

@@ -20,7 +20,7 @@ class AppStream:
     def __init__(self, ctx: int, *, net: int, frame_w: int, frame_h: int, net_w: int, net_h: int,
                  blob: np.ndarray, palette: np.ndarray, queue_depth: int = 2,
                  net_fp32_input: bool = False, frame_pitch: int | None = None, mean: float = 0.5,
-                 std: float = 0.25, threshold: float = 0.5, alpha: float = 0.5,
+                 std: float = 0.25, threshold: float = 0.5, alpha: float = 0.5, batch: int = 1,
                  device: str = "cuda:0"):
         self.ctx = ctx
         self.frame_w, self.frame_h = frame_w, frame_h
@@ -30,7 +30,8 @@ class AppStream:
         kw = dict(frame_w=frame_w, frame_h=frame_h, net_w=net_w, net_h=net_h, net=net,
                   weights=blob, palette=palette, frame_pitch=self.frame_pitch,
                   net_fp32_input=int(net_fp32_input), mean=mean, std=std, threshold=threshold,
-                  alpha=alpha, queue_depth=queue_depth)
+                  alpha=alpha, queue_depth=queue_depth, batch=batch)
+        self.batch = batch
         need = api.hs_query_workspace(api.make_desc(**kw))
         self.workspace = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
         base = (self.workspace.data_ptr() + 255) // 256 * 256
@@ -59,6 +60,27 @@ class AppStream:
         if st == api.HS_OK:
             self._held[frame_id] = (d_frame, d_out)      # keep alive until polled
         return st
+
+    def submit_batch(self, d_frames, d_outs, frame_id: int) -> int:
+        """One frame per stream of a batched application (lists of device tensors)."""
+        st = api.hs_submit_batch(self.app, [t.data_ptr() for t in d_frames],
+                                 [t.data_ptr() for t in d_outs], frame_id)
+        if st == api.HS_OK:
+            self._held[frame_id] = (list(d_frames), list(d_outs))
+        return st
+
+    def wait_batch(self, timeout_s: float = 30.0):
+        rs = api.hs_wait_batch(self.app, self.batch, int(timeout_s * 1e9))
+        if rs is None:
+            raise TimeoutError("no result within %.1f s" % timeout_s)
+        self._held.pop(rs[0].frame_id, None)
+        return rs
+
+    def poll_batch(self):
+        rs = api.hs_poll_batch(self.app, self.batch)
+        if rs is not None:
+            self._held.pop(rs[0].frame_id, None)
+        return rs
 
     def poll(self):
         r = api.hs_poll_result(self.app)
@@ -104,11 +126,11 @@ class AppStream:
                 self.frame_h, self.frame_w, 3)
         return out
 
-    def state(self, r):
-        return api.hs_get_state(self.app, r.map_h, r.map_w)
+    def state(self, r, stream: int = 0):
+        return api.hs_get_state(self.app, r.map_h, r.map_w, stream=stream)
 
-    def features(self, r):
-        return api.hs_get_features(self.app, r.map_h, r.map_w)
+    def features(self, r, stream: int = 0):
+        return api.hs_get_features(self.app, r.map_h, r.map_w, stream=stream)
 
     def close(self):
         if self.app:

@@ -150,6 +150,48 @@ def test_reset_state_and_queue_semantics(hs, ctx):
         s.close()
 
 
+@pytest.mark.parametrize("net,net_name,layers,fw,fh,nw,nh,fp32,seed", [
+    ("HS_NET_RESNET18_CONVLSTM", "resnet18_convlstm", "RESNET18_CONVLSTM_LAYERS", 640, 360, 288, 160,
+     False, 1),
+    ("HS_NET_TINY4", "tiny4", "TINY4_LAYERS", 320, 240, 128, 128, True, 0),
+])
+def test_batched_streams_match_per_stream_oracles(hs, ctx, net, net_name, layers, fw, fh, nw, nh,
+                                                  fp32, seed):
+    """Cross-stream batched inference: 3 streams through ONE batched application (one shared
+    weight copy, the network run once over the batch, ConvLSTM state per stream) against 3
+    independent oracle streams, 3 frames each."""
+    from paper_2402_04466_amd.harness import AppStream
+    B, T = 3, 3
+    blob = si.he_normal_blob(getattr(si, layers), seed)
+    if net_name == "tiny4":
+        frames = [list(si.uniform_frames(T, fh, fw, 20 + j)) for j in range(B)]
+    else:
+        frames = [list(si.tool_scene_frames(T, fh, fw, 20 + j)) for j in range(B)]
+    s = AppStream(ctx, net=getattr(hs, net), frame_w=fw, frame_h=fh, net_w=nw, net_h=nh, blob=blob,
+                  palette=PAL, queue_depth=2, net_fp32_input=fp32, batch=B)
+    oracles = [make_oracles(net_name, blob, nw, nh, not fp32, PAL) for _ in range(B)]
+    try:
+        with pytest.raises(hs.HsError):                     # single-frame call on a batched app
+            hs.hs_submit_frame(s.app, 256, 512, 0)
+        for t in range(T):
+            print(f"[batch-{net_name}] frame {t}", flush=True)
+            d_in = [s.upload_frame(frames[j][t]) for j in range(B)]
+            d_out = [s.new_output() for _ in range(B)]
+            assert s.submit_batch(d_in, d_out, t) == hs.HS_OK
+            rs = s.wait_batch()
+            assert len(rs) == B and all(r.frame_id == t for r in rs)
+            for j in range(B):
+                g = s.fetch(rs[j], d_out[j])
+                a, b = oracles[j][0].process(frames[j][t]), oracles[j][1].process(frames[j][t])
+                check_frame(g, frames[j][t], a, b, threshold=0.5, alpha=0.5, palette=PAL,
+                            fp32_input=fp32, tag=f"batch-{net_name}/stream{j}/frame{t}")
+                if net_name != "tiny4":
+                    gh, gc = s.state(rs[j], stream=j)
+                    assert rms_rel(gh, a["h"]) <= TOL_STATE_RMS and rms_rel(gc, a["c"]) <= TOL_STATE_RMS
+    finally:
+        s.close()
+
+
 def test_graph_and_kernel_by_kernel_launch_paths_agree(hs, ctx):
     """The pre-built HIP graph of stages 1-3 is replayed for several frames (with the host's
     own synchronisation and read-backs between replays) and must give, frame by frame and
