@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--streams", type=int, default=1, help="concurrent application streams")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="streams per application, batched through the network together "
+                         "(--streams counts applications; 12 with --fps 30 is the saturation case)")
     ap.add_argument("--fps", type=float, default=60.0, help="pacing of the latency run")
     ap.add_argument("--partition", choices=["none", "equal"], default="none",
                     help="equal: disjoint CU-masked partitions, inference/overlay split")
@@ -85,17 +88,23 @@ def main():
     for i in range(args.streams):
         s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW,
                       net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
-                      queue_depth=args.queue_depth)
+                      queue_depth=args.queue_depth, batch=args.batch)
         hs.hs_set_launch_mode(s.app, hs.HS_LAUNCH_GRAPH if args.launch_mode == "graph"
                               else hs.HS_LAUNCH_EAGER)
         streams.append(s)
-        seed = 1 if args.streams == 1 else 2 + i
-        frames.append([s.upload_frame(f)
-                       for f in si.tool_scene_frames(args.distinct_frames, FH, FW, seed)])
+        per_stream = []
+        for j in range(args.batch):
+            seed = 1 if args.streams * args.batch == 1 else 2 + i * args.batch + j
+            per_stream.append([s.upload_frame(f) for f in
+                               si.tool_scene_frames(args.distinct_frames, FH, FW, seed)])
+        # frames[i][k] = what is submitted as frame k of application i (one tensor per stream)
+        frames.append([[per_stream[j][k] for j in range(args.batch)]
+                       for k in range(args.distinct_frames)])
     if args.partition == "equal":
         for s, (ci, co) in zip(streams, equal_partitions(n_cus, args.streams)):
             hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
-    outs = [[s.new_output() for _ in range(args.queue_depth)] for s in streams]
+    outs = [[[s.new_output() for _ in range(args.batch)] for _ in range(args.queue_depth)]
+            for s in streams]
     torch.cuda.synchronize()
 
     def run_back_to_back(n_frames: int):
@@ -104,11 +113,11 @@ def main():
             s, fr, ou = streams[i], frames[i], outs[i]
             done = 0
             for k in range(n_frames):
-                while s.submit(fr[k % len(fr)], ou[k % len(ou)], k) != hs.HS_OK:
-                    s.wait()
+                while s.submit_batch(fr[k % len(fr)], ou[k % len(ou)], k) != hs.HS_OK:
+                    s.wait_batch()
                     done += 1
             while done < n_frames:
-                s.wait()
+                s.wait_batch()
                 done += 1
         th = [threading.Thread(target=worker, args=(i,)) for i in range(len(streams))]
         torch.cuda.synchronize()
@@ -123,7 +132,7 @@ def main():
     # ---- throughput: W warm-up steps, then exactly K timed steps per stream ---------------
     run_back_to_back(args.warmup)
     elapsed = run_back_to_back(args.steps)
-    total_frames = args.steps * args.streams
+    total_frames = args.steps * args.streams * args.batch
     fps = total_frames / elapsed
 
     # ---- latency determinism at a fixed frame rate (paper Section V-A metrics) -------------
@@ -134,16 +143,17 @@ def main():
     results, dropped = run_paced(streams, paced, args.fps, outs)
     lat_ms = []
     for rs in results:
-        per = [(r.t_overlay_done_ns - r.t_submit_ns) / 1e6 for r in rs]
-        t = min(10, len(per) // 6)
-        lat_ms.extend(per[t:len(per) - t])       # trim each stream's warm-up / cool-down
+        for j in range(args.batch):
+            per = [(r[j].t_overlay_done_ns - r[j].t_submit_ns) / 1e6 for r in rs]
+            t = min(10, len(per) // 6)
+            lat_ms.extend(per[t:len(per) - t])   # trim each stream's warm-up / cool-down
     m = hs.hs_latency_metrics_compute(lat_ms, trim=False)
     stage_ms = {}
     for name, a, b in (("pre", "t_submit_ns", "t_pre_done_ns"),
                        ("infer", "t_pre_done_ns", "t_infer_done_ns"),
                        ("post", "t_infer_done_ns", "t_post_done_ns"),
                        ("overlay", "t_post_done_ns", "t_overlay_done_ns")):
-        v = [(getattr(r, b) - getattr(r, a)) / 1e6 for rs in results for r in rs]
+        v = [(getattr(r[0], b) - getattr(r[0], a)) / 1e6 for rs in results for r in rs]
         stage_ms[name] = round(float(np.median(v)), 4)
 
     # ---- roofline of the dominant kernel: HIP events around every launch -------------------
@@ -151,8 +161,9 @@ def main():
     hs.hs_set_kernel_timing(s0.app, True)
     n_prof = 20
     for k in range(n_prof):
-        assert s0.submit(frames[0][k % len(frames[0])], outs[0][k % len(outs[0])], k) == hs.HS_OK
-        s0.wait()
+        assert s0.submit_batch(frames[0][k % len(frames[0])], outs[0][k % len(outs[0])],
+                               k) == hs.HS_OK
+        s0.wait_batch()
     kt = hs.hs_get_kernel_times(s0.app)
     hs.hs_set_kernel_timing(s0.app, False)
     dom = max(kt, key=lambda e: e["total_ms"])
@@ -208,10 +219,10 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(1e3 * elapsed / args.steps, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
-        "config": {"workload": f"{args.streams} stream(s) x 1920x1080 RGB uint8 -> 854x480 fp16, "
+        "config": {"workload": f"{args.streams * args.batch} stream(s) x 1920x1080 RGB uint8 -> 854x480 fp16, "
                                "ResNet-18-style + ConvLSTM(256) + 8-ch head, sigmoid/threshold/"
                                "argmax, alpha-blend overlay on the 1080p frame",
-                   "streams": args.streams, "partition": args.partition,
+                   "streams": args.streams, "batch": args.batch, "partition": args.partition,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
                    "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),

@@ -20,8 +20,13 @@ struct KernelDesc {
 };
 
 // ---- stage 1: bilinear resize (exact integer) + normalise + interleave ----------------
+constexpr int kMaxBatch = 16;   // streams one launch can serve (blockIdx.y = stream)
+
 struct ResizeParams {
-  const uint8_t* src;   // frame, RGB bytes, row pitch src_pitch (16-byte multiple)
+  const uint8_t* src[kMaxBatch];   // per stream: frame, RGB bytes, row pitch src_pitch (x16)
+  int batch;
+  size_t dst_img_stride;           // halves between the streams' padded images
+  size_t dst32_img_stride;         // floats between the streams' planar fp32 tensors
   size_t src_pitch;
   int wi, hi, wo, ho;
   f16* dst;             // padded 4-channel fp16 image: pixel (y+pad_t, x+pad_l), pitch dst_w px
@@ -78,12 +83,14 @@ struct SplitKEpilogueParams {
 };
 KernelDesc describe(const SplitKEpilogueParams& p);
 
-// ConvLSTM gate non-linearities and state update from the gate pre-activations.
-// partial: [nsplit][m][4*hid] with channels ordered i, f, g, o (hid each).
-// c: fp32 [m][hid] updated in place; h: fp16 written to h_out[m*h_pitch + j].
+// ConvLSTM gate non-linearities and state update from the gate pre-activations, plus the 1x1
+// head on the new h.  partial: [nsplit][m][4*hid], channels ordered i, f, g, o (hid each);
+// hid must be 256.  c: fp32 [m][hid] updated in place; h: fp16 written to h_out[m*h_pitch + j];
+// logits[(image*8 + k)*img_m + pixel] = sum_j w_head[k][j] * h[pixel][j] (fp16 weights).
 struct LstmEpilogueParams {
   const float* partial; int nsplit; int m; int hid;
   float* c; f16* h_out; int h_pitch;
+  const f16* w_head; float* logits; int img_m;
 };
 KernelDesc describe(const LstmEpilogueParams& p);
 
@@ -106,19 +113,11 @@ struct PostParams {
 };
 KernelDesc describe(const PostParams& p);
 
-// 1x1 head (cin <= 512 -> 8 channels, fp16 weights w[k][cin]) fused with the postprocess:
-// logits[k][m] = sum_j w[k][j] * h[m*h_pitch + j] in fp32, then heat / mask / record.
-struct HeadPostParams {
-  const f16* h; int h_pitch; const f16* w; int cin; int m;
-  float theta; float* logits; float* heat; uint8_t* mask; PostRecord* rec;
-  int batch;   // images: h is [batch*m] pixels, outputs [batch][8][m], rec[batch]
-};
-KernelDesc describe(const HeadPostParams& p);
-
 // ---- stage 4: overlay ---------------------------------------------------------------------
 struct OverlayParams {
-  const uint8_t* src; uint8_t* dst; size_t pitch; int wf, hf;
-  const uint8_t* mask; int wm, hm;   // [8][hm][wm]
+  const uint8_t* src[kMaxBatch]; uint8_t* dst[kMaxBatch];   // per stream
+  int batch; size_t pitch; int wf, hf;
+  const uint8_t* mask; int wm, hm;   // [batch][8][hm][wm]
   int a;                             // Q8 alpha, 0..256
   uint32_t pal[8];                   // R | G<<8 | B<<16
 };

@@ -28,6 +28,9 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
   __shared__ f16 s_lut16[256];
   const int tid = threadIdx.x;
   const int Y = blockIdx.x;
+  const uint8_t* const src = p.src[blockIdx.y];          // stream blockIdx.y of the batch
+  f16* const dst = p.dst + blockIdx.y * p.dst_img_stride;
+  float* const dst_f32 = p.dst_f32 ? p.dst_f32 + blockIdx.y * p.dst32_img_stride : nullptr;
   const uint32_t dy = 2u * (uint32_t)p.ho, dx = 2u * (uint32_t)p.wo;
   int ny = (2 * Y + 1) * p.hi - p.ho;
   ny = max(0, min(ny, (p.hi - 1) * (int)dy));
@@ -36,8 +39,8 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
   const uint32_t y1 = min(y0 + 1u, (uint32_t)(p.hi - 1));
 
   const int row_vecs = (3 * p.wi + 15) >> 4;          // 16-byte vectors per source row
-  const uint4* r0 = reinterpret_cast<const uint4*>(p.src + (size_t)y0 * p.src_pitch);
-  const uint4* r1 = reinterpret_cast<const uint4*>(p.src + (size_t)y1 * p.src_pitch);
+  const uint4* r0 = reinterpret_cast<const uint4*>(src + (size_t)y0 * p.src_pitch);
+  const uint4* r1 = reinterpret_cast<const uint4*>(src + (size_t)y1 * p.src_pitch);
   uint4* l0 = reinterpret_cast<uint4*>(lds);
   uint4* l1 = l0 + row_vecs;
   for (int v = tid; v < row_vecs; v += 256) {
@@ -72,10 +75,10 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
     px[1] = s_lut16[q[1]];
     px[2] = s_lut16[q[2]];
     px[3] = (f16)0.0f;
-    *reinterpret_cast<half4*>(p.dst + ((size_t)(Y + p.pad_t) * p.dst_w + (X + p.pad_l)) * 4) = px;
-    if (p.dst_f32) {
+    *reinterpret_cast<half4*>(dst + ((size_t)(Y + p.pad_t) * p.dst_w + (X + p.pad_l)) * 4) = px;
+    if (dst_f32) {
       const size_t plane = (size_t)p.ho * p.wo;
-      float* o = p.dst_f32 + (size_t)Y * p.wo + X;
+      float* o = dst_f32 + (size_t)Y * p.wo + X;
       o[0] = s_lut32[q[0]];
       o[plane] = s_lut32[q[1]];
       o[2 * plane] = s_lut32[q[2]];
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
 
 KernelDesc describe(const ResizeParams& p) {
   const unsigned lds = (unsigned)((3 * p.wi + 15) >> 4) * 16 * 2;
-  return KernelDesc{(const void*)k_resize_norm, dim3(p.ho), dim3(256), lds};
+  return KernelDesc{(const void*)k_resize_norm, dim3(p.ho, p.batch), dim3(256), lds};
 }
 
 // =============================================================================================
@@ -536,12 +539,16 @@ KernelDesc describe(const SplitKEpilogueParams& p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// ConvLSTM epilogue: one thread per (pixel, hidden channel); fp32 math, c kept in fp32.
+// ConvLSTM epilogue + 1x1 head: one workgroup per pixel, one thread per hidden channel
+// (hid == 256).  Gates and state update in fp32 (c kept in fp32, h stored fp16); the head's
+// eight logits of the pixel are the workgroup-wide sums of w[k][j] * h[j] over the stored
+// (fp16) h: wavefront butterflies, then the four wavefront sums in order.
+// logits: planar per image, logits[(image*8 + k)*img_m + pixel in image].
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_lstm_epilogue(LstmEpilogueParams p) {
-  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)p.m * p.hid) return;
-  const int m = (int)(t / p.hid), j = (int)(t - (size_t)m * p.hid);
+  __shared__ float s_part[4][8];
+  const int m = blockIdx.x, j = threadIdx.x, lane = j & 63, wave = j >> 6;
+  const size_t t = (size_t)m * p.hid + j;
   const int n4 = 4 * p.hid;
   float g[4] = {0.f, 0.f, 0.f, 0.f};
   for (int sidx = 0; sidx < p.nsplit; ++sidx) {
@@ -552,12 +559,31 @@ __global__ __launch_bounds__(256) void k_lstm_epilogue(LstmEpilogueParams p) {
   const float gi = sigmoid_f(g[0]), gf = sigmoid_f(g[1]), gg = tanhf(g[2]), go = sigmoid_f(g[3]);
   const float c_new = gf * p.c[t] + gi * gg;
   p.c[t] = c_new;
-  p.h_out[(size_t)m * p.h_pitch + j] = (f16)(go * tanhf(c_new));
+  const f16 h16 = (f16)(go * tanhf(c_new));
+  p.h_out[(size_t)m * p.h_pitch + j] = h16;
+
+  const float hv = (float)h16;
+  float v[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) v[k] = hv * (float)p.w_head[k * p.hid + j];
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v[k] += __shfl_xor(v[k], off, 64);
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s_part[wave][k] = v[k];
+  }
+  __syncthreads();
+  if (j < 8) {
+    const float sum = ((s_part[0][j] + s_part[1][j]) + s_part[2][j]) + s_part[3][j];
+    const int img = m / p.img_m, ml = m - img * p.img_m;
+    p.logits[((size_t)img * 8 + j) * p.img_m + ml] = sum;
+  }
 }
 
 KernelDesc describe(const LstmEpilogueParams& p) {
-  const size_t n = (size_t)p.m * p.hid;
-  return KernelDesc{(const void*)k_lstm_epilogue, dim3((unsigned)((n + 255) / 256)), dim3(256), 0};
+  return KernelDesc{(const void*)k_lstm_epilogue, dim3((unsigned)p.m), dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -611,14 +637,16 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
   __shared__ int s_i[4];
   const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const size_t img_off = (size_t)blockIdx.y * 8 * p.n;   // image blockIdx.y of the batch
-  p.heat += img_off; p.mask += img_off; p.rec += blockIdx.y;
+  float* const heat = p.heat + img_off;
+  uint8_t* const mask = p.mask + img_off;
+  PostRecord* const rec = p.rec + blockIdx.y;
   const float* L = p.logits + img_off + (size_t)k * p.n;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
   for (int i = tid; i < p.n; i += 256) {
     const float x = L[i];
-    p.heat[(size_t)k * p.n + i] = 1.0f / (1.0f + expf(-x));
-    p.mask[(size_t)k * p.n + i] = x > p.theta ? 1 : 0;
+    heat[(size_t)k * p.n + i] = 1.0f / (1.0f + expf(-x));
+    mask[(size_t)k * p.n + i] = x > p.theta ? 1 : 0;
     if (better(x, i, bv, bi)) { bv = x; bi = i; }
   }
 #pragma unroll
@@ -632,79 +660,14 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
   if (tid == 0) {
     for (int w = 1; w < 4; ++w)
       if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
-    p.rec->argmax_idx[k] = bi;
-    p.rec->peak[k] = 1.0f / (1.0f + expf(-bv));
-    p.rec->present[k] = bv > p.theta ? 1 : 0;
+    rec->argmax_idx[k] = bi;
+    rec->peak[k] = 1.0f / (1.0f + expf(-bv));
+    rec->present[k] = bv > p.theta ? 1 : 0;
   }
 }
 
 KernelDesc describe(const PostParams& p) {
   return KernelDesc{(const void*)k_postprocess, dim3(8, p.batch), dim3(256), 0};
-}
-
-// ---------------------------------------------------------------------------------------------
-// 1x1 head fused with stage 3: workgroup k owns tool channel k.  Half a wavefront (32 lanes
-// x 8 channels = 256 input channels per round, coalesced 512-byte rows) forms the dot
-// product of one pixel, logits[k][m] = sum_j w[k][j] * h[m][j] (fp32, fixed order: lane
-// partial sums, then a 5-step butterfly); its first lane postprocesses the pixel and keeps
-// the running (best value, lowest index).
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void k_head_post(HeadPostParams p) {
-  __shared__ float s_v[16];
-  __shared__ int s_i[16];
-  const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, l32 = tid & 31, half_id = tid >> 5;
-  // image blockIdx.y of the batch: its m pixels, its [8][m] outputs, its record
-  p.h += (size_t)blockIdx.y * p.m * p.h_pitch;
-  p.logits += (size_t)blockIdx.y * 8 * p.m; p.heat += (size_t)blockIdx.y * 8 * p.m;
-  p.mask += (size_t)blockIdx.y * 8 * p.m; p.rec += blockIdx.y;
-  float bv = -INFINITY;
-  int bi = 0x7fffffff;
-  constexpr int U = 8;                              // pixels in flight per half-wavefront
-  for (int m0 = 0; m0 < p.m; m0 += 16 * U) {        // 16 half-wavefronts x U pixels per round
-    float acc[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) acc[u] = 0.0f;
-    for (int c0 = l32 * 8; c0 < p.cin; c0 += 256) {
-      const half8 w = *reinterpret_cast<const half8*>(p.w + (size_t)k * p.cin + c0);
-      half8 x[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int mc = min(m0 + half_id + 16 * u, p.m - 1);
-        x[u] = *reinterpret_cast<const half8*>(p.h + (size_t)mc * p.h_pitch + c0);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[u] += (float)x[u][j] * (float)w[j];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float a = acc[u];
-#pragma unroll
-      for (int off = 16; off >= 1; off >>= 1) a += __shfl_xor(a, off, 64);
-      const int m = m0 + half_id + 16 * u;
-      if (l32 == 0 && m < p.m) {
-        p.logits[(size_t)k * p.m + m] = a;
-        p.heat[(size_t)k * p.m + m] = 1.0f / (1.0f + expf(-a));
-        p.mask[(size_t)k * p.m + m] = a > p.theta ? 1 : 0;
-        if (better(a, m, bv, bi)) { bv = a; bi = m; }
-      }
-    }
-  }
-  if (l32 == 0) { s_v[half_id] = bv; s_i[half_id] = bi; }
-  __syncthreads();
-  if (tid == 0) {
-    for (int w = 1; w < 16; ++w)
-      if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
-    p.rec->argmax_idx[k] = bi;
-    p.rec->peak[k] = 1.0f / (1.0f + expf(-bv));
-    p.rec->present[k] = bv > p.theta ? 1 : 0;
-  }
-  (void)lane;
-}
-
-KernelDesc describe(const HeadPostParams& p) {
-  return KernelDesc{(const void*)k_head_post, dim3(8, p.batch), dim3(512), 0};
 }
 
 // =============================================================================================
@@ -718,12 +681,12 @@ __global__ __launch_bounds__(128) void k_overlay(OverlayParams p) {
   for (int x = tid; x < p.wm; x += 128) {
     uint8_t k = 0xff;
     for (int c = 7; c >= 0; --c)
-      if (p.mask[((size_t)c * p.hm + my) * p.wm + x]) k = (uint8_t)c;
+      if (p.mask[(((size_t)blockIdx.y * 8 + c) * p.hm + my) * p.wm + x]) k = (uint8_t)c;
     s_k[x] = k;
   }
   __syncthreads();
-  const uint8_t* srow = p.src + (size_t)Y * p.pitch;
-  uint8_t* drow = p.dst + (size_t)Y * p.pitch;
+  const uint8_t* srow = p.src[blockIdx.y] + (size_t)Y * p.pitch;
+  uint8_t* drow = p.dst[blockIdx.y] + (size_t)Y * p.pitch;
   const int ia = 256 - p.a;
   for (int X0 = tid * 16; X0 < p.wf; X0 += 128 * 16) {
     const int npx = min(16, p.wf - X0);
@@ -769,7 +732,7 @@ __global__ __launch_bounds__(128) void k_overlay(OverlayParams p) {
 }
 
 KernelDesc describe(const OverlayParams& p) {
-  return KernelDesc{(const void*)k_overlay, dim3(p.hf), dim3(128), (unsigned)p.wm};
+  return KernelDesc{(const void*)k_overlay, dim3(p.hf, p.batch), dim3(128), (unsigned)p.wm};
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -38,10 +38,9 @@ static inline uint64_t now_ns() {
   } while (0)
 
 // ---- kernel families (for timing) ----------------------------------------------------------
-enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_MAXPOOL, F_HEADPOST, F_POST, F_OVERLAY, F_COUNT };
+enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_MAXPOOL, F_POST, F_OVERLAY, F_COUNT };
 static const char* kFamilyName[F_COUNT] = {"resize_norm", "conv_mfma", "splitk_epilogue",
-                                           "lstm_epilogue", "maxpool", "head_post", "postprocess",
-                                           "overlay"};
+                                           "lstm_head", "maxpool", "postprocess", "overlay"};
 
 struct Op {
   Family fam;
@@ -51,7 +50,6 @@ struct Op {
   SplitKEpilogueParams splitk;
   LstmEpilogueParams lstm;
   MaxPoolParams pool;
-  HeadPostParams headpost;
   PostParams post;
   OverlayParams overlay;
 };
@@ -63,7 +61,6 @@ static KernelDesc op_desc(const Op& op) {
     case F_SPLITK: return describe(op.splitk);
     case F_LSTM: return describe(op.lstm);
     case F_MAXPOOL: return describe(op.pool);
-    case F_HEADPOST: return describe(op.headpost);
     case F_POST: return describe(op.post);
     default: return describe(op.overlay);
   }
@@ -76,7 +73,6 @@ static void* op_params(Op& op) {
     case F_SPLITK: return &op.splitk;
     case F_LSTM: return &op.lstm;
     case F_MAXPOOL: return &op.pool;
-    case F_HEADPOST: return &op.headpost;
     case F_POST: return &op.post;
     default: return &op.overlay;
   }
@@ -110,10 +106,10 @@ struct Tensor {
 enum SlotState { SLOT_FREE = 0, SLOT_INFLIGHT = 1, SLOT_DONE = 2 };
 
 struct Slot {
-  std::vector<Op> pre;     // stage 1: one resize per stream of the batch
+  std::vector<Op> pre;     // stage 1: one launch, blockIdx.y = stream of the batch
   std::vector<Op> infer;   // stage 2: the network over the whole batch
   std::vector<Op> post;    // stage 3
-  std::vector<Op> overlay; // stage 4: one overlay per stream of the batch
+  std::vector<Op> overlay; // stage 4: one launch, blockIdx.y = stream of the batch
   hipEvent_t ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr, ev_overlay = nullptr;
   // stages 1-3 as one HIP graph (kernel nodes chained in order, event-record nodes at the
   // stage boundaries); only the frame pointer of the first node changes from frame to frame
@@ -446,25 +442,18 @@ struct Builder {
     Tensor gates;
     const int lstm_conv = conv_layer(cat, at, 1024, 3, 1, 1, false, nullptr, &gates, false, true);
     at += (size_t)1024 * 768 * 9;
-    {
-      Op op;
-      op.fam = F_LSTM;
-      op.lstm = LstmEpilogueParams{nullptr, ops[lstm_conv].conv.nsplit, mf, 256, cstate,
-                                   concat ? concat + 512 : nullptr, 768};
-      op.bytes = (double)ops[lstm_conv].conv.nsplit * mf * 1024 * 4.0 + (double)mf * 256 * 10.0;
-      ops.push_back(op);
-    }
-    // head weights: 8 x 256 fp16, plain [k][c]; the head kernel also runs stage 3
+    // head weights: 8 x 256 fp16, plain [k][c]; the head runs inside the ConvLSTM epilogue
     const size_t w_off = reserve_w(2048);
     if (pack)
       for (int i = 0; i < 2048; ++i) host_w[w_off + i] = (f16)blob[at + i];
     at += 2048;
     {
       Op op;
-      op.fam = F_HEADPOST;
-      op.headpost = HeadPostParams{concat ? concat + 512 : nullptr, 768,
-                                   d_w ? d_w + w_off : nullptr, 256, hf * wf, 0.0f, nullptr,
-                                   nullptr, nullptr, nullptr, d.batch};
+      op.fam = F_LSTM;
+      op.lstm = LstmEpilogueParams{nullptr, ops[lstm_conv].conv.nsplit, mf, 256, cstate,
+                                   concat ? concat + 512 : nullptr, 768,
+                                   d_w ? d_w + w_off : nullptr, nullptr, hf * wf};
+      op.bytes = (double)ops[lstm_conv].conv.nsplit * mf * 1024 * 4.0 + (double)mf * 256 * 10.0;
       op.flops = 2.0 * mf * 8 * 256;
       ops.push_back(op);
       logits_op = (int)ops.size() - 1;
@@ -628,51 +617,48 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     s.d_logits = sb[i].logits; s.d_heat = sb[i].heat; s.d_mask = sb[i].mask;
     s.rec = (PostRecord*)app->pinned + (size_t)i * B;
     s.results.resize(B);
-    for (int j = 0; j < B; ++j) {
+    {
       Op r;
       r.fam = F_RESIZE;
       ResizeParams& rp = r.resize;
-      rp.src = nullptr; rp.src_pitch = d->frame_pitch;
+      std::memset(&rp, 0, sizeof(rp));
+      rp.batch = B; rp.src_pitch = d->frame_pitch;
+      rp.dst_img_stride = (size_t)ph * pw * 4;
+      rp.dst32_img_stride = (size_t)3 * d->net_h * d->net_w;
       rp.wi = d->frame_w; rp.hi = d->frame_h; rp.wo = d->net_w; rp.ho = d->net_h;
-      rp.dst = s.d_netin + (size_t)j * ph * pw * 4; rp.dst_w = pw; rp.pad_l = pad; rp.pad_t = pad;
-      rp.dst_f32 = s.d_netin_f32 ? s.d_netin_f32 + (size_t)j * 3 * d->net_h * d->net_w : nullptr;
-      rp.lut32 = d_lut32; rp.lut16 = d_lut16;
+      rp.dst = s.d_netin; rp.dst_w = pw; rp.pad_l = pad; rp.pad_t = pad;
+      rp.dst_f32 = s.d_netin_f32; rp.lut32 = d_lut32; rp.lut16 = d_lut16;
       rp.rcp_dx = 1.0f / (2.0f * d->net_w); rp.rcp_dy = 1.0f / (2.0f * d->net_h);
       rp.rcp_d = 1.0f / (4.0f * (float)d->net_w * (float)d->net_h);
-      r.bytes = 3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
-                (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0);
+      r.bytes = B * (3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
+                     (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0));
       s.pre.push_back(r);
     }
     s.infer = b.ops;
     s.infer[b.first_conv_op].conv.in = s.d_netin;
     Op& lo = s.infer[b.logits_op];
-    if (lo.fam == F_CONV || lo.fam == F_SPLITK) {
-      if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits; else lo.splitk.out_f32 = s.d_logits;
+    if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits;
+    else if (lo.fam == F_SPLITK) lo.splitk.out_f32 = s.d_logits;
+    else lo.lstm.logits = s.d_logits;
+    {
       Op p;
       p.fam = F_POST;
       p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec, B};
       p.bytes = B * 8.0 * n_map * (4 + 4 + 1);
       s.post.push_back(p);
-    } else {
-      // the head kernel computes the logits and postprocesses them: it is stage 3's launch
-      HeadPostParams& hp = lo.headpost;
-      hp.theta = (float)theta_d; hp.logits = s.d_logits; hp.heat = s.d_heat; hp.mask = s.d_mask;
-      hp.rec = s.rec;
-      s.post.push_back(lo);
-      s.infer.erase(s.infer.begin() + b.logits_op);
     }
-    for (int j = 0; j < B; ++j) {
+    {
       Op o;
       o.fam = F_OVERLAY;
       OverlayParams& op = o.overlay;
-      op.src = nullptr; op.dst = nullptr; op.pitch = d->frame_pitch;
-      op.wf = d->frame_w; op.hf = d->frame_h; op.mask = s.d_mask + (size_t)j * 8 * n_map;
-      op.wm = mw; op.hm = mh;
+      std::memset(&op, 0, sizeof(op));
+      op.batch = B; op.pitch = d->frame_pitch;
+      op.wf = d->frame_w; op.hf = d->frame_h; op.mask = s.d_mask; op.wm = mw; op.hm = mh;
       op.a = a_q8;
       for (int k = 0; k < 8; ++k)
         op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
                     ((uint32_t)d->palette[k][2] << 16);
-      o.bytes = 6.0 * d->frame_w * d->frame_h + 8.0 * n_map;
+      o.bytes = B * (6.0 * d->frame_w * d->frame_h + 8.0 * n_map);
       s.overlay.push_back(o);
     }
     HS_HIP(hipEventCreate(&s.ev_pre));
@@ -1117,18 +1103,16 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
     r.d_net_input_f32 = s->d_netin_f32
                             ? s->d_netin_f32 + (size_t)j * 3 * app->desc.net_h * app->desc.net_w
                             : nullptr;
-    s->pre[j].resize.src = d_frames[j];
-    s->overlay[j].overlay.src = d_frames[j];
-    s->overlay[j].overlay.dst = d_overlay_outs[j];
+    s->pre[0].resize.src[j] = d_frames[j];
+    s->overlay[0].overlay.src[j] = d_frames[j];
+    s->overlay[0].overlay.dst[j] = d_overlay_outs[j];
   }
 
   hs_status st = HS_OK;
   if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
-    for (int j = 0; j < B; ++j) {
-      void* args[1];
-      hipKernelNodeParams kp = node_params(s->pre[j], args);
-      HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_nodes[j], &kp));
-    }
+    void* args[1];
+    hipKernelNodeParams kp = node_params(s->pre[0], args);
+    HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_nodes[0], &kp));
     HS_HIP(hipGraphLaunch(s->graph_exec, app->s_infer));
   } else {
     st = run_ops(app, s->pre, app->s_infer);

@@ -139,17 +139,16 @@ class AppStream:
             self._held.clear()
 
 
-def run_paced(streams, frames, fps: float, outputs=None):
-    """Submit frame k of every stream at t0 + k/fps from one thread per stream and collect
-    the per-frame results.  ``frames[i]`` is a list of device frame tensors for stream i
-    (cycled if shorter than n).  Returns per-stream lists of hs_result plus the number of
-    frames dropped because the queue was full."""
+def run_paced(streams, frames, fps: float, outputs):
+    """Submit frame k of every application at t0 + k/fps from one thread per application and
+    collect the per-frame results.  ``frames[i][k]`` / ``outputs[i][q]`` are lists with one
+    device tensor per stream of application i (length ``batch``).  Returns, per application, the
+    list of per-frame result lists (one hs_result per stream), plus the number of frames dropped
+    because the queue was full."""
     n_streams = len(streams)
     results = [[] for _ in range(n_streams)]
     dropped = [0] * n_streams
     n = max(len(f) for f in frames)
-    if outputs is None:
-        outputs = [[s.new_output() for _ in range(s.queue_depth)] for s in streams]
     t0 = time.monotonic() + 0.05
     period = 1.0 / fps
 
@@ -159,18 +158,18 @@ def run_paced(streams, frames, fps: float, outputs=None):
         for k in range(n):
             deadline = t0 + k * period
             while True:
-                r = s.poll()
+                r = s.poll_batch()
                 if r is None:
                     break
                 results[i].append(r)
             dt = deadline - time.monotonic()
             if dt > 0:
                 time.sleep(dt)
-            st = s.submit(fr[k % len(fr)], outputs[i][k % len(outputs[i])], k)
+            st = s.submit_batch(fr[k % len(fr)], outputs[i][k % len(outputs[i])], k)
             if st != api.HS_OK:
                 dropped[i] += 1
         while len(results[i]) + dropped[i] < n:
-            results[i].append(s.wait())
+            results[i].append(s.wait_batch())
 
     threads = [threading.Thread(target=worker, args=(i,)) for i in range(n_streams)]
     for t in threads:
