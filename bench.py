@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--queue-depth", type=int, default=4)
     ap.add_argument("--launch-mode", choices=["graph", "eager"], default="graph",
                     help="stages 1-3 as one HIP graph per frame, or kernel by kernel")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="first run the library's plain copy kernel 4 times over this many MiB "
+                         "(reference dispatches for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=6)
     return ap.parse_args()
@@ -83,6 +86,14 @@ def main():
     FW, FH, NW, NH = 1920, 1080, 854, 480
     ctx = hs.hs_init(0)
     n_cus = hs.hs_device_cus(ctx)
+    if args.calibrate_copy:
+        nbytes = args.calibrate_copy << 20
+        a = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            hs.hs_device_copy(ctx, b.data_ptr(), a.data_ptr(), nbytes)
+        del a, b
     blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
     streams, frames = [], []
     for i in range(args.streams):
@@ -175,6 +186,17 @@ def main():
         ach = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    # HBM bytes per launch from committed rocprofv3 counter runs, valid only for the kernel
+    # source they were taken with
+    try:
+        from paper_2402_04466_amd.pmc_traffic import kernel_source_hash
+        tag = "config2_1stream" if args.streams * args.batch == 1 else f"batch{args.batch}"
+        with open(os.path.join(ROOT, "profiles", f"conv_traffic_{tag}.json")) as fh:
+            tr = json.load(fh)
+        if tr["kernel_source_sha256"] == kernel_source_hash() and dom["name"] == "conv_mfma":
+            roof["traffic"] = round(tr["conv_hbm_bytes_per_launch"]["total"])
+    except (OSError, KeyError, ValueError):
+        pass
     roof["kernel"] = dom["name"]
     roof["avg_launch_us"] = round(dom["total_ms"] * 1e3 / dom["launches"], 2)
     roof["launches_per_frame"] = dom["launches"] // n_prof

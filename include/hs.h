@@ -262,6 +262,12 @@ hs_status hs_set_kernel_timing(hs_app* app, int enable);
 hs_status hs_get_kernel_times(hs_app* app, hs_kernel_time* entries, int max_entries,
                               int* n_entries);
 
+/* Plain device-to-device streaming copy of `bytes` (multiple of 16, 16-byte aligned, no
+ * overlap) on the default stream, synchronous. Its only purpose is measurement: it is the
+ * kernel of known traffic against which hardware byte counters (rocprofv3 FETCH_SIZE /
+ * WRITE_SIZE) are scaled. */
+hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes);
+
 /* Thread-local, never NULL; valid until the next failing call on this thread. */
 const char* hs_last_error(void);
 /* Library version string. */

@@ -20,7 +20,7 @@ __all__ = [
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
     "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch", "hs_latency_metrics_compute", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
-    "hs_get_kernel_times", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
+    "hs_get_kernel_times", "hs_device_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
 HS_OK, HS_E_INVAL, HS_E_NOMEM, HS_E_OVERSUBSCRIBED = 0, -1, -2, -3
@@ -116,6 +116,7 @@ def load() -> C.CDLL:
         "hs_set_kernel_timing": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_get_kernel_times": (C.c_int, [C.c_void_p, P(hs_kernel_time), C.c_int, P(C.c_int)]),
+        "hs_device_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
         "hs_last_error": (C.c_char_p, []),
         "hs_version": (C.c_char_p, []),
     }
@@ -296,6 +297,10 @@ def hs_latency_metrics_compute(latencies, trim: bool = True) -> dict:
     _check(load().hs_latency_metrics_compute(x.ctypes.data, x.size, 1 if trim else 0,
                                              C.byref(m)))
     return {k: getattr(m, k) for k, _ in hs_latency_metrics._fields_}
+
+
+def hs_device_copy(ctx: int, d_dst: int, d_src: int, nbytes: int) -> None:
+    _check(load().hs_device_copy(ctx, d_dst, d_src, nbytes))
 
 
 def hs_set_launch_mode(app: int, mode: int) -> None:

@@ -125,5 +125,6 @@ KernelDesc describe(const OverlayParams& p);
 
 // ---- helpers ------------------------------------------------------------------------------
 void launch_fill_zero(void* d, size_t bytes, hipStream_t s);   // bytes multiple of 16
+void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);   // bytes multiple of 16
 
 }  // namespace hs

@@ -335,9 +335,11 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
 // of Cin the patch goes to LDS once and serves all nine taps; only the weight tile (64 x 64
 // halves per tap) is streamed per tap.  Global traffic per tap drops from 16 KB to
 // 8 KB + patch/9 -- these layers are bound by bytes fetched per workgroup, not by MFMA rate.
-// Pipeline: three weight stages in registers (9 taps = 3 x 3, so the stage of a tap is a
-// literal), the next chunk's patch is prefetched during the first taps of the current one;
-// the nine steps of a chunk are written out, loads are unconditional and branch-free.
+// Pipeline: nine weight stages in registers, one per tap (the stage of a tap is a literal):
+// while tap t of chunk cc is computed, the weights of tap t of chunk cc+1 are already being
+// fetched, i.e. a whole chunk of weights is in flight; the next chunk's patch is prefetched
+// during the first taps of the current one.  The nine steps of a chunk are written out,
+// loads are unconditional and branch-free.
 // Wavefront (wm, wn): pixel rows 4*wm .. 4*wm+3 (MT groups of 4 x 8 pixels), channels
 // 32*wn .. +31.  chunks_per_split / nchunks count Cin chunks here (split-K over Cin).
 // =============================================================================================
@@ -345,10 +347,15 @@ template <int MT>
 __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   constexpr int KC = 64, TH = 8, TW = 8 * MT, PH = TH + 2, PW = TW + 2, NPIX = PH * PW;
   constexpr int PITCH = KC + 8;
+  // Patch rows are padded so that consecutive rows start 128 bytes apart modulo 256: the 16
+  // lanes of one ds_read_b128 pass (two rows of 8 pixels, 144-byte pixel pitch) then fall into
+  // 16 different 16-byte bank groups.
+  constexpr int RP = PW * PITCH + (MT == 1 ? 112 : 48);   // halves per patch row
+  static_assert((RP * 2) % 256 == 128, "patch row pitch must be 128 mod 256 bytes");
   constexpr int PV = NPIX * 8;               // 16-byte vectors in a patch
   constexpr int PL = (PV + 255) / 256;       // patch vectors per thread (4 or 6)
   static_assert(PL <= 9, "patch prefetch is spread over the nine taps");
-  __shared__ __align__(16) f16 s_patch[2][NPIX * PITCH];
+  __shared__ __align__(16) f16 s_patch[2][PH * RP];
   __shared__ __align__(16) f16 s_w[2][64 * PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
@@ -386,7 +393,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     l_pinb[i] = l_pact[i] && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
     l_pbase[i] = l_pinb[i] ? p.in + (((long)img * p.hin + iy) * p.win + ix) * p.cin_pitch + kv * 8
                            : p.in;
-    l_plds[i] = pix * PITCH + kv * 8;
+    l_plds[i] = py * RP + px * PITCH + kv * 8;
   }
 
   floatx16 acc[MT];
@@ -398,9 +405,9 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   const int wm = wave & 1, wn = wave >> 1;
   // fragment bases: weights row (32*wn + r); pixel (4*wm + r/8, r%8) of column group g
   const int fw_off = (wn * 32 + r) * PITCH + h * 8;
-  const int fp_off = ((4 * wm + (r >> 3)) * PW + (r & 7)) * PITCH + h * 8;
+  const int fp_off = (4 * wm + (r >> 3)) * RP + (r & 7) * PITCH + h * 8;
 
-  u32x4 st_w[3][2];
+  u32x4 st_w[9][2];
   u32x4 st_p[PL];
 #define HS_LOAD_W(S_, CC_, TAP_)                                                               \
   {                                                                                            \
@@ -415,8 +422,8 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   // refill decision is resolved at compile time.
 #define HS_TAP(TAP_, LAST_)                                                                    \
   {                                                                                            \
-    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[0]]) = st_w[(TAP_) % 3][0];                     \
-    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[1]]) = st_w[(TAP_) % 3][1];                     \
+    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[0]]) = st_w[TAP_][0];                           \
+    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[1]]) = st_w[TAP_][1];                           \
     if ((TAP_) == 0) {                                                                         \
       const u32x4 zero_ = {0u, 0u, 0u, 0u};                                                    \
       _Pragma("unroll") for (int i = 0; i < PL; ++i)                                           \
@@ -424,11 +431,10 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
           *reinterpret_cast<u32x4*>(&s_patch[pb][l_plds[i]]) = l_pinb[i] ? st_p[i] : zero_;    \
     }                                                                                          \
     __syncthreads();                                                                           \
-    if ((TAP_) + 3 < 9) HS_LOAD_W((TAP_) % 3, cc, (TAP_) + 3)                                  \
-    else if (!(LAST_)) HS_LOAD_W((TAP_) % 3, cc + 1, (TAP_) + 3 - 9)                           \
+    if (!(LAST_)) HS_LOAD_W(TAP_, cc + 1, TAP_)                                                \
     if (!(LAST_) && (TAP_) < PL) { HS_LOAD_P((TAP_) < PL ? (TAP_) : 0, cc + 1) }               \
     const f16* fw_ = &s_w[buf][fw_off];                                                        \
-    const f16* fp_ = &s_patch[pb][fp_off + (((TAP_) / 3) * PW + ((TAP_) % 3)) * PITCH];        \
+    const f16* fp_ = &s_patch[pb][fp_off + ((TAP_) / 3) * RP + ((TAP_) % 3) * PITCH];          \
     _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                   \
       const half8 a_ = *reinterpret_cast<const half8*>(fw_ + ks * 16);                         \
       _Pragma("unroll") for (int g = 0; g < MT; ++g) {                                         \
@@ -446,9 +452,9 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   int cc = cc_begin;
 #pragma unroll
   for (int i = 0; i < PL; ++i) HS_LOAD_P(i, cc)
-  HS_LOAD_W(0, cc, 0)
-  HS_LOAD_W(1, cc, 1)
-  HS_LOAD_W(2, cc, 2)
+  HS_LOAD_W(0, cc, 0) HS_LOAD_W(1, cc, 1) HS_LOAD_W(2, cc, 2)
+  HS_LOAD_W(3, cc, 3) HS_LOAD_W(4, cc, 4) HS_LOAD_W(5, cc, 5)
+  HS_LOAD_W(6, cc, 6) HS_LOAD_W(7, cc, 7) HS_LOAD_W(8, cc, 8)
   for (; cc + 1 < cc_end; ++cc) {
     HS_CHUNK(false)
     pb ^= 1;
@@ -740,6 +746,22 @@ __global__ __launch_bounds__(256) void k_fill_zero(uint4* d, size_t n) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
     d[i] = make_uint4(0, 0, 0, 0);
+}
+
+// Plain streaming copy (16-byte vectors, grid-stride): the known-size kernel that hardware
+// byte counters are calibrated against.
+__global__ __launch_bounds__(256) void k_copy(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                              size_t n) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 16;
+  if (n == 0) return;
+  const unsigned blocks = (unsigned)min((size_t)8192, (n + 255) / 256);
+  hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
+                     reinterpret_cast<uint4*>(dst), n);
 }
 
 void launch_fill_zero(void* d, size_t bytes, hipStream_t s) {

@@ -869,6 +869,18 @@ hs_status hs_device_cus(hs_ctx* ctx, int* n_cus) {
   return HS_OK;
 }
 
+hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes) {
+  if (!ctx || !d_dst || !d_src || bytes % 16 != 0 || ((uintptr_t)d_dst & 15) || ((uintptr_t)d_src & 15)) {
+    set_error("hs_device_copy: NULL, misaligned pointer or size not a multiple of 16");
+    return HS_E_INVAL;
+  }
+  HS_HIP(hipSetDevice(ctx->device));
+  launch_copy(d_dst, d_src, bytes, nullptr);
+  HS_HIP(hipGetLastError());
+  HS_HIP(hipStreamSynchronize(nullptr));
+  return HS_OK;
+}
+
 hs_status hs_query_workspace(const hs_app_desc* desc, size_t* bytes) {
   if (!bytes) { set_error("hs_query_workspace: NULL bytes"); return HS_E_INVAL; }
   hs_status st = validate_desc(desc);
