@@ -55,9 +55,11 @@ struct ConvParams {
   int kc;               // 16, 32 or 64
   int depth;            // prefetch depth in chunks: 4, or 8 (kc == 64 only)
   int variant;          // 0: generic tile of 64 consecutive pixels (k_conv_mfma)
-                        // 1, 2: 3x3/1 layers, spatial tile 8 x 8 / 8 x 16 with a shared input
-                        //       patch (k_conv3x3_halo<1|2>); needs cin % 64 == 0
-  int tiles_x;          // variant 1, 2: spatial tiles per output row
+                        // 1, 2, 3: 3x3/1 layers with a shared input patch (k_conv3x3_halo),
+                        //    needs cin % 64 == 0; spatial tile 8 x 8 (1) or 8 x 16 (2, 3);
+                        //    3 keeps one patch buffer and three weight stages, so that three
+                        //    workgroups fit a CU (grids well beyond two workgroups per CU)
+  int tiles_x;          // variant 1, 2, 3: spatial tiles per output row
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;
   // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)
@@ -94,9 +96,20 @@ struct LstmEpilogueParams {
 };
 KernelDesc describe(const LstmEpilogueParams& p);
 
-// 3x3 stride-2 pad-1 max-pool on pixel-major fp16, c multiple of 8.
-struct MaxPoolParams { const f16* in; f16* out; int hin, win, hout, wout, c, batch; };
-KernelDesc describe(const MaxPoolParams& p);
+// Stem of the ResNet-style backbone: 7x7 stride-2 pad-3 convolution 3 -> 64, ReLU, 3x3 stride-2
+// pad-1 max-pool, fused.  in: padded 4-channel fp16 images (pad 3 on the top and left, zeros),
+// hin x win pixels each with win even; wt: [64][224] halves, k = (ky*8 + px)*4 + ch, zero where
+// px == 7 or ch == 3; out: pooled pixel-major [batch][hp][wp][64].
+struct StemPoolParams {
+  const f16* in; const f16* wt; f16* out;
+  int hin, win;          // padded image
+  int hc, wc;            // convolution output
+  int hp, wp;            // pooled output
+  int batch;
+  int tiles_x, tiles_y;  // tiles of 8 x 15 pooled pixels
+  int tiles_per_xcd;     // ceil(batch * tiles_y * tiles_x / 8)
+};
+KernelDesc describe(const StemPoolParams& p);
 
 // ---- stage 3: postprocess -----------------------------------------------------------------
 struct PostRecord {           // written by the kernel into pinned host memory

@@ -335,28 +335,33 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
 // of Cin the patch goes to LDS once and serves all nine taps; only the weight tile (64 x 64
 // halves per tap) is streamed per tap.  Global traffic per tap drops from 16 KB to
 // 8 KB + patch/9 -- these layers are bound by bytes fetched per workgroup, not by MFMA rate.
-// Pipeline: nine weight stages in registers, one per tap (the stage of a tap is a literal):
-// while tap t of chunk cc is computed, the weights of tap t of chunk cc+1 are already being
-// fetched, i.e. a whole chunk of weights is in flight; the next chunk's patch is prefetched
-// during the first taps of the current one.  The nine steps of a chunk are written out,
-// loads are unconditional and branch-free.
+// Pipeline: WS weight stages in registers (stage = tap % WS, a literal): while a tap is
+// computed, the weights of the step WS taps ahead are being fetched -- with WS == 9 a whole
+// chunk of weights is in flight, which suits grids of at most two workgroups per CU; the next
+// chunk's patch is prefetched during the first taps of the current one and, with a single patch
+// buffer (PB == 1), handed to LDS behind one extra barrier per chunk.  PB == 1 with WS == 3 is
+// the lean form: 45 KB of LDS and under 170 registers, three workgroups per CU.  The nine steps
+// of a chunk are written out, loads are unconditional and branch-free.
 // Wavefront (wm, wn): pixel rows 4*wm .. 4*wm+3 (MT groups of 4 x 8 pixels), channels
 // 32*wn .. +31.  chunks_per_split / nchunks count Cin chunks here (split-K over Cin).
 // =============================================================================================
-template <int MT>
+template <int MT, int PB, int WS>
 __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   constexpr int KC = 64, TH = 8, TW = 8 * MT, PH = TH + 2, PW = TW + 2, NPIX = PH * PW;
   constexpr int PITCH = KC + 8;
+  constexpr int BN = 64;                     // output channels per workgroup
+  constexpr int WL = BN / 32;                // weight vectors per thread and tap
   // Patch rows are padded so that consecutive rows start 128 bytes apart modulo 256: the 16
   // lanes of one ds_read_b128 pass (two rows of 8 pixels, 144-byte pixel pitch) then fall into
   // 16 different 16-byte bank groups.
-  constexpr int RP = PW * PITCH + (MT == 1 ? 112 : 48);   // halves per patch row
+  constexpr int RP = PW * PITCH + (TW == 8 ? 112 : 48);   // halves per patch row
   static_assert((RP * 2) % 256 == 128, "patch row pitch must be 128 mod 256 bytes");
   constexpr int PV = NPIX * 8;               // 16-byte vectors in a patch
   constexpr int PL = (PV + 255) / 256;       // patch vectors per thread (4 or 6)
   static_assert(PL <= 9, "patch prefetch is spread over the nine taps");
-  __shared__ __align__(16) f16 s_patch[2][PH * RP];
-  __shared__ __align__(16) f16 s_w[2][64 * PITCH];
+  static_assert(WS == 9 || WS == 3, "weight stages: a divisor of nine");
+  __shared__ __align__(16) f16 s_patch[PB][PH * RP];
+  __shared__ __align__(16) f16 s_w[2][BN * PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
   const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
@@ -367,15 +372,15 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   const int tiles_img = p.tiles_m / p.batch;            // spatial tiles per image
   const int img = tile_m / tiles_img, tile_s = tile_m - img * tiles_img;
   const int ty = tile_s / p.tiles_x, tx = tile_s - ty * p.tiles_x;
-  const int y0 = ty * TH, x0 = tx * TW, n0 = tile_n * 64;
+  const int y0 = ty * TH, x0 = tx * TW, n0 = tile_n * BN;
   const int cc_begin = split * p.chunks_per_split;
   const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
 
   // loop-invariant loader state
-  const f16* l_wbase[2];
-  int l_wlds[2];
+  const f16* l_wbase[WL];
+  int l_wlds[WL];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < WL; ++i) {
     const int v = tid + 256 * i, row = v >> 3, kv = v & 7;
     l_wbase[i] = p.wt + (size_t)(n0 + row) * p.ktot + kv * 8;
     l_wlds[i] = row * PITCH + kv * 8;
@@ -407,31 +412,34 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   const int fw_off = (wn * 32 + r) * PITCH + h * 8;
   const int fp_off = (4 * wm + (r >> 3)) * RP + (r & 7) * PITCH + h * 8;
 
-  u32x4 st_w[9][2];
+  u32x4 st_w[WS][WL];
   u32x4 st_p[PL];
 #define HS_LOAD_W(S_, CC_, TAP_)                                                               \
   {                                                                                            \
     const long off_ = ((long)(TAP_) * p.chunks_per_tap + (CC_)) * KC;                          \
-    st_w[S_][0] = *reinterpret_cast<const u32x4*>(l_wbase[0] + off_);                          \
-    st_w[S_][1] = *reinterpret_cast<const u32x4*>(l_wbase[1] + off_);                          \
+    _Pragma("unroll") for (int i = 0; i < WL; ++i)                                             \
+      st_w[S_][i] = *reinterpret_cast<const u32x4*>(l_wbase[i] + off_);                        \
   }
 #define HS_LOAD_P(I_, CC_)                                                                     \
   st_p[I_] = *reinterpret_cast<const u32x4*>(l_pinb[I_] ? l_pbase[I_] + (long)(CC_) * KC : p.in);
 
   // One tap of chunk cc.  TAP_ and LAST_ are literals: every register index and every
-  // refill decision is resolved at compile time.
+  // refill decision is resolved at compile time.  Weight stage TAP_ % WS is handed to LDS and
+  // refilled with the weights of the step WS taps ahead.
 #define HS_TAP(TAP_, LAST_)                                                                    \
   {                                                                                            \
-    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[0]]) = st_w[TAP_][0];                           \
-    *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[1]]) = st_w[TAP_][1];                           \
+    _Pragma("unroll") for (int i = 0; i < WL; ++i)                                             \
+      *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[i]]) = st_w[(TAP_) % WS][i];                  \
     if ((TAP_) == 0) {                                                                         \
+      if (PB == 1) __syncthreads(); /* every wave is done with the previous chunk's patch */   \
       const u32x4 zero_ = {0u, 0u, 0u, 0u};                                                    \
       _Pragma("unroll") for (int i = 0; i < PL; ++i)                                           \
         if (l_pact[i])                                                                         \
           *reinterpret_cast<u32x4*>(&s_patch[pb][l_plds[i]]) = l_pinb[i] ? st_p[i] : zero_;    \
     }                                                                                          \
     __syncthreads();                                                                           \
-    if (!(LAST_)) HS_LOAD_W(TAP_, cc + 1, TAP_)                                                \
+    if (!(LAST_) || (TAP_) + WS < 9)                                                           \
+      HS_LOAD_W((TAP_) % WS, cc + ((TAP_) + WS) / 9, ((TAP_) + WS) % 9)                        \
     if (!(LAST_) && (TAP_) < PL) { HS_LOAD_P((TAP_) < PL ? (TAP_) : 0, cc + 1) }               \
     const f16* fw_ = &s_w[buf][fw_off];                                                        \
     const f16* fp_ = &s_patch[pb][fp_off + ((TAP_) / 3) * RP + ((TAP_) % 3) * PITCH];          \
@@ -453,11 +461,13 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
 #pragma unroll
   for (int i = 0; i < PL; ++i) HS_LOAD_P(i, cc)
   HS_LOAD_W(0, cc, 0) HS_LOAD_W(1, cc, 1) HS_LOAD_W(2, cc, 2)
-  HS_LOAD_W(3, cc, 3) HS_LOAD_W(4, cc, 4) HS_LOAD_W(5, cc, 5)
-  HS_LOAD_W(6, cc, 6) HS_LOAD_W(7, cc, 7) HS_LOAD_W(8, cc, 8)
+  if (WS == 9) {
+    HS_LOAD_W(3 % WS, cc, 3) HS_LOAD_W(4 % WS, cc, 4) HS_LOAD_W(5 % WS, cc, 5)
+    HS_LOAD_W(6 % WS, cc, 6) HS_LOAD_W(7 % WS, cc, 7) HS_LOAD_W(8 % WS, cc, 8)
+  }
   for (; cc + 1 < cc_end; ++cc) {
     HS_CHUNK(false)
-    pb ^= 1;
+    if (PB == 2) pb ^= 1;
   }
   HS_CHUNK(true)
 #undef HS_CHUNK
@@ -494,8 +504,9 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
   const dim3 grid(8u * (unsigned)p.tiles_per_xcd);
-  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1>, grid, dim3(256), 0};
-  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2>, grid, dim3(256), 0};
+  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9>, grid, dim3(256), 0};
+  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9>, grid, dim3(256), 0};
+  if (p.variant == 3) return KernelDesc{(const void*)k_conv3x3_halo<2, 1, 3>, grid, dim3(256), 0};
   const void* f = p.kc == 16   ? (const void*)k_conv_mfma<16, 4>
                   : p.kc == 32 ? (const void*)k_conv_mfma<32, 4>
                   : p.depth == 8 ? (const void*)k_conv_mfma<64, 8>
@@ -592,41 +603,148 @@ KernelDesc describe(const LstmEpilogueParams& p) {
   return KernelDesc{(const void*)k_lstm_epilogue, dim3((unsigned)p.m), dim3(256), 0};
 }
 
-// ---------------------------------------------------------------------------------------------
-// Max-pool 3x3 / 2, pad 1: one thread per (output pixel, 8 channels).
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_maxpool(MaxPoolParams p) {
-  const int cv = p.c >> 3;
-  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)p.batch * p.hout * p.wout * cv) return;
-  const int v = (int)(t % cv);
-  const int pix = (int)(t / cv);                     // output pixel over the whole batch
-  const int img = pix / (p.hout * p.wout), pl = pix - img * (p.hout * p.wout);
-  const int oy = pl / p.wout, ox = pl - oy * p.wout;
-  const f16* in = p.in + (size_t)img * p.hin * p.win * p.c;
-  half8 best;
-  bool first = true;
-  for (int ky = 0; ky < 3; ++ky) {
-    const int iy = 2 * oy + ky - 1;
-    if (iy < 0 || iy >= p.hin) continue;
-    for (int kx = 0; kx < 3; ++kx) {
-      const int ix = 2 * ox + kx - 1;
-      if (ix < 0 || ix >= p.win) continue;
-      const half8 x =
-          *reinterpret_cast<const half8*>(in + ((size_t)iy * p.win + ix) * p.c + v * 8);
-      if (first) { best = x; first = false; }
-      else {
+// =============================================================================================
+// Stem: 7x7 stride-2 convolution (3 -> 64 channels) + ReLU + 3x3 stride-2 max-pool in one
+// kernel; the 64-channel convolution output (the largest tensor of the network) never reaches
+// memory.
+//
+// A workgroup produces 8 x 15 pooled pixels, i.e. the 17 x 31 convolution outputs under them
+// (one row/column of overlap with the neighbouring tiles), as 17 row fragments of 32 pixels.
+// The whole input patch (39 rows x 70 padded 4-channel pixels) and the whole weight matrix
+// (64 x 224 halves, k = (ky*8 + px)*4 + ch) sit in LDS.  Because the image is stored with 4
+// channels per pixel, the 32 K-values of kernel row ky for convolution pixel cx are the 64
+// contiguous bytes starting at input pixel 2*cx of row 2*cy + ky: MFMA pixel operands are read
+// straight from the patch, no im2col copy.
+// Wavefront (wm, wn): convolution rows 8*wm .. 8*wm+8 (row 8 is computed by both halves, it
+// feeds pooled rows 3 and 4), channels 32*wn .. +31: nine accumulators.  Pooling: ReLU, zero outside the convolution output (every pooling
+// window holds a real pixel and ReLU outputs are >= 0, so zero stands for "absent"), maximum
+// over three accumulators (rows), then over lanes r, r+1, r+2 (columns, two DPP wavefront
+// shifts); even lanes store.
+// Rounding to fp16 after the maximum equals the maximum of the rounded values.
+// =============================================================================================
+// value of lane + 1 (DPP whole-wavefront shift; lane 63 keeps its own)
+__device__ __forceinline__ float lane_plus_1(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x130,
+                                                    0xf, 0xf, false));
+}
+
+__global__ __launch_bounds__(256, 2) void k_stem_pool(StemPoolParams p) {
+  constexpr int PROWS = 39, PVEC = 35, PROW_H = PVEC * 8;      // patch rows, vectors, halves per row
+  constexpr int WPITCH = 224 + 8;                              // halves per weight row in LDS
+  constexpr int NPV = PROWS * PVEC, NPL = (NPV + 255) / 256;   // patch vectors, per thread
+  constexpr int NWL = 64 * 28 / 256;                           // weight vectors per thread
+  __shared__ __align__(16) f16 s_patch[PROWS * PROW_H];
+  __shared__ __align__(16) f16 s_w[64 * WPITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if (tile >= p.batch * p.tiles_y * p.tiles_x) return;
+  const int tx = tile % p.tiles_x, ty = (tile / p.tiles_x) % p.tiles_y;
+  const int img = tile / (p.tiles_x * p.tiles_y);
+  const int p0 = 8 * ty, q0 = 15 * tx;              // first pooled pixel
+  const int cy0 = 2 * p0 - 1, cx0 = 2 * q0 - 1;     // first convolution pixel
+  const int iy0 = 2 * cy0, ix0 = 2 * cx0;           // first pixel of the padded image (may be < 0)
+
+  // ---- fill LDS: unconditional loads from clamped addresses, zeros where out of the image
+  u32x4 st_p[NPL], st_w[NWL];
+  bool inb[NPL];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) best[j] = x[j] > best[j] ? x[j] : best[j];
+  for (int i = 0; i < NPL; ++i) {
+    const int v = min(tid + 256 * i, NPV - 1);
+    const int ly = v / PVEC, lv = v - ly * PVEC;
+    const int y = iy0 + ly, x = ix0 + 2 * lv;
+    inb[i] = y >= 0 && y < p.hin && x >= 0 && x < p.win;
+    const f16* src = inb[i] ? p.in + (((size_t)img * p.hin + y) * p.win + x) * 4 : p.in;
+    st_p[i] = *reinterpret_cast<const u32x4*>(src);
+  }
+#pragma unroll
+  for (int i = 0; i < NWL; ++i) {
+    const int v = tid + 256 * i;
+    st_w[i] = *reinterpret_cast<const u32x4*>(p.wt + (size_t)v * 8);   // rows are 28 vectors, dense
+  }
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    const int v = tid + 256 * i;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    if (v < NPV) *reinterpret_cast<u32x4*>(&s_patch[v * 8]) = inb[i] ? st_p[i] : zero;
+  }
+#pragma unroll
+  for (int i = 0; i < NWL; ++i) {
+    const int v = tid + 256 * i, row = v / 28, kv = v - row * 28;
+    *reinterpret_cast<u32x4*>(&s_w[row * WPITCH + kv * 8]) = st_w[i];
+  }
+  __syncthreads();
+
+  // ---- 14 K-steps of 16 (two per kernel row), nine row fragments each
+  const int wm = wave & 1, wn = wave >> 1;
+  floatx16 acc[9];
+#pragma unroll
+  for (int j = 0; j < 9; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.0f;
+  const f16* fw = &s_w[(32 * wn + r) * WPITCH + h * 8];
+  const f16* fp = &s_patch[(16 * wm) * PROW_H + r * 8 + h * 8];   // patch row 2*(8*wm + j) + ky
+  // The wavefront's 14 weight fragments stay in registers.  Patch row rho serves every
+  // (convolution row j, kernel row ky) with 2*j + ky == rho, so each patch fragment is read
+  // once: 46 LDS reads feed the 126 MFMAs.  Per accumulator the K order stays ky = 0..6.
+  half8 a[7][2];
+#pragma unroll
+  for (int ky = 0; ky < 7; ++ky)
+#pragma unroll
+    for (int s = 0; s < 2; ++s) a[ky][s] = *reinterpret_cast<const half8*>(fw + ky * 32 + s * 16);
+#pragma unroll
+  for (int rho = 0; rho < 23; ++rho) {
+    if (rho % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // bounds how far reads are hoisted
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const half8 b = *reinterpret_cast<const half8*>(fp + rho * PROW_H + s * 16);
+#pragma unroll
+      for (int j = 0; j < 9; ++j) {
+        const int ky = rho - 2 * j;
+        if (ky >= 0 && ky <= 6)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ky < 0 ? 0 : ky > 6 ? 6 : ky][s], b,
+                                                         acc[j], 0, 0, 0);
       }
     }
   }
-  *reinterpret_cast<half8*>(p.out + (size_t)pix * p.c + v * 8) = best;
+
+  // ---- ReLU, zero outside the convolution output, pool
+  const int cx = cx0 + r;
+  const bool col_ok = cx >= 0 && cx < p.wc;
+#pragma unroll
+  for (int j = 0; j < 9; ++j) {
+    const int cy = cy0 + 8 * wm + j;
+    const bool ok = col_ok && cy >= 0 && cy < p.hc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = ok ? fmaxf(acc[j][i], 0.0f) : 0.0f;
+  }
+  const int q = q0 + (r >> 1);
+  const bool writer = (r & 1) == 0 && r <= 28 && q < p.wp;
+#pragma unroll
+  for (int pl = 0; pl < 4; ++pl) {
+    const int py = p0 + 4 * wm + pl;
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float m = fmaxf(fmaxf(acc[2 * pl][i], acc[2 * pl + 1][i]), acc[2 * pl + 2][i]);
+      const float m2 = fmaxf(m, lane_plus_1(m));     // columns r, r+1
+      v[i] = fmaxf(m2, lane_plus_1(m2));             // columns r .. r+2
+    }
+    if (writer && py < p.hp) {
+      f16* dst = p.out + (((size_t)img * p.hp + py) * p.wp + q) * 64 + 32 * wn + 4 * h;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        half4 o;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = (f16)v[4 * i + c];
+        *reinterpret_cast<half4*>(dst + 8 * i) = o;
+      }
+    }
+  }
 }
 
-KernelDesc describe(const MaxPoolParams& p) {
-  const size_t n = (size_t)p.batch * p.hout * p.wout * (p.c >> 3);
-  return KernelDesc{(const void*)k_maxpool, dim3((unsigned)((n + 255) / 256)), dim3(256), 0};
+KernelDesc describe(const StemPoolParams& p) {
+  return KernelDesc{(const void*)k_stem_pool, dim3(8u * (unsigned)p.tiles_per_xcd), dim3(256), 0};
 }
 
 // =============================================================================================

@@ -38,9 +38,9 @@ static inline uint64_t now_ns() {
   } while (0)
 
 // ---- kernel families (for timing) ----------------------------------------------------------
-enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_MAXPOOL, F_POST, F_OVERLAY, F_COUNT };
+enum Family { F_RESIZE, F_CONV, F_SPLITK, F_LSTM, F_STEM, F_POST, F_OVERLAY, F_COUNT };
 static const char* kFamilyName[F_COUNT] = {"resize_norm", "conv_mfma", "splitk_epilogue",
-                                           "lstm_head", "maxpool", "postprocess", "overlay"};
+                                           "lstm_head", "stem_pool_mfma", "postprocess", "overlay"};
 
 struct Op {
   Family fam;
@@ -49,7 +49,7 @@ struct Op {
   ConvParams conv;
   SplitKEpilogueParams splitk;
   LstmEpilogueParams lstm;
-  MaxPoolParams pool;
+  StemPoolParams stem;
   PostParams post;
   OverlayParams overlay;
 };
@@ -60,7 +60,7 @@ static KernelDesc op_desc(const Op& op) {
     case F_CONV: return describe(op.conv);
     case F_SPLITK: return describe(op.splitk);
     case F_LSTM: return describe(op.lstm);
-    case F_MAXPOOL: return describe(op.pool);
+    case F_STEM: return describe(op.stem);
     case F_POST: return describe(op.post);
     default: return describe(op.overlay);
   }
@@ -72,7 +72,7 @@ static void* op_params(Op& op) {
     case F_CONV: return &op.conv;
     case F_SPLITK: return &op.splitk;
     case F_LSTM: return &op.lstm;
-    case F_MAXPOOL: return &op.pool;
+    case F_STEM: return &op.stem;
     case F_POST: return &op.post;
     default: return &op.overlay;
   }
@@ -248,11 +248,12 @@ struct Builder {
   static void choose_split(ConvParams& c) {
     const bool halo = c.ntaps == 9 && c.kw == 3 && c.stride == 1 && c.pad == 1 && c.kc == 64;
     if (halo) {
-      // spatial tiles of 8 x 16 pixels when that still yields enough workgroups, else 8 x 8
+      // spatial tiles of 8 x 16 pixels when that still yields enough workgroups, else 8 x 8;
+      // grids of more than two workgroups per CU take the leaner 8 x 16 kernel (three per CU)
       const int ty = (c.hout + 7) / 8;
       const int wide = c.batch * ty * ((c.wout + 15) / 16) * (c.cout_pad / 64);
-      c.variant = wide >= 192 ? 2 : 1;
-      const int tw = c.variant == 2 ? 16 : 8;
+      c.variant = wide > 512 ? 3 : wide >= 192 ? 2 : 1;
+      const int tw = c.variant == 1 ? 8 : 16;
       c.tiles_x = (c.wout + tw - 1) / tw;
       c.tiles_m = c.batch * ty * c.tiles_x;
       c.tiles_n = c.cout_pad / 64;
@@ -388,23 +389,33 @@ struct Builder {
     for (int i = 0; i < 3; ++i) { hf = conv_out(hf, 3, 2, 1); wf = conv_out(wf, 3, 2, 1); }
     const size_t nb = (size_t)d.batch;
     const int mf = (int)nb * hf * wf;                    // feature-map pixels over the batch
-    Tensor stem;
-    stem.p = acts<f16>(nb * hs_ * ws_ * 64); stem.pitch = 64;
     Tensor buf[4];
     for (int i = 0; i < 4; ++i) buf[i].p = acts<f16>(nb * hp * wp * 64);
     f16* concat = acts<f16>((size_t)mf * 768);
     float* cstate = acts<float>((size_t)mf * 256);
 
     size_t at = 0;
-    first_layer(at, ph, pw, 64, 7, &stem);
-    at += 64 * 3 * 49;
     {
+      // stem convolution and max-pool in one kernel; weights packed as row taps of 8 pixels
+      const size_t w_off = reserve_w((size_t)64 * 224);
+      if (pack) pack_rowtap(blob + at, 64, 7, 8, 64, host_w.data() + w_off);
       Op op;
-      op.fam = F_MAXPOOL;
-      op.pool = MaxPoolParams{stem.p, buf[0].p, hs_, ws_, hp, wp, 64, d.batch};
-      op.bytes = nb * ((double)hs_ * ws_ + (double)hp * wp) * 64 * 2;
+      op.fam = F_STEM;
+      StemPoolParams& sp = op.stem;
+      std::memset(&sp, 0, sizeof(sp));
+      sp.in = nullptr;   // per slot
+      sp.wt = d_w ? d_w + w_off : nullptr;
+      sp.out = buf[0].p;
+      sp.hin = ph; sp.win = pw; sp.hc = hs_; sp.wc = ws_; sp.hp = hp; sp.wp = wp;
+      sp.batch = d.batch;
+      sp.tiles_x = (wp + 14) / 15; sp.tiles_y = (hp + 7) / 8;
+      sp.tiles_per_xcd = (sp.batch * sp.tiles_x * sp.tiles_y + 7) / 8;
+      op.flops = 2.0 * nb * hs_ * ws_ * 64.0 * 3 * 49;
+      op.bytes = nb * ((double)d.net_h * d.net_w * 8 + (double)hp * wp * 64 * 2);
       ops.push_back(op);
+      first_conv_op = (int)ops.size() - 1;
     }
+    at += 64 * 3 * 49;
     int cur = 0;
     buf[0].h = hp; buf[0].w = wp; buf[0].c = 64; buf[0].pitch = 64;
     const int widths[4] = {64, 128, 256, 512};
@@ -635,7 +646,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       s.pre.push_back(r);
     }
     s.infer = b.ops;
-    s.infer[b.first_conv_op].conv.in = s.d_netin;
+    if (s.infer[b.first_conv_op].fam == F_STEM) s.infer[b.first_conv_op].stem.in = s.d_netin;
+    else s.infer[b.first_conv_op].conv.in = s.d_netin;
     Op& lo = s.infer[b.logits_op];
     if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits;
     else if (lo.fam == F_SPLITK) lo.splitk.out_f32 = s.d_logits;
