@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--fps", type=float, default=60.0, help="pacing of the latency run")
     ap.add_argument("--partition", choices=["none", "equal"], default="none",
                     help="equal: disjoint CU-masked partitions, inference/overlay split")
+    ap.add_argument("--hog", type=int, default=0, metavar="K",
+                    help="K extra applications that submit frames back to back during the paced "
+                         "latency run (saturating neighbours, not counted in the latency figures); "
+                         "with --partition equal they get partitions of their own")
     ap.add_argument("--paced-frames", type=int, default=60)
     ap.add_argument("--distinct-frames", type=int, default=8)
     ap.add_argument("--queue-depth", type=int, default=4)
@@ -111,8 +115,16 @@ def main():
         # frames[i][k] = what is submitted as frame k of application i (one tensor per stream)
         frames.append([[per_stream[j][k] for j in range(args.batch)]
                        for k in range(args.distinct_frames)])
+    hogs, hog_frames, hog_outs = [], [], []
+    for i in range(args.hog):
+        s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW,
+                      net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
+                      queue_depth=args.queue_depth, batch=1)
+        hogs.append(s)
+        hog_frames.append([s.upload_frame(f) for f in si.tool_scene_frames(2, FH, FW, 100 + i)])
+        hog_outs.append([s.new_output() for _ in range(args.queue_depth)])
     if args.partition == "equal":
-        for s, (ci, co) in zip(streams, equal_partitions(n_cus, args.streams)):
+        for s, (ci, co) in zip(streams + hogs, equal_partitions(n_cus, args.streams + args.hog)):
             hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
     outs = [[[s.new_output() for _ in range(args.batch)] for _ in range(args.queue_depth)]
             for s in streams]
@@ -151,7 +163,31 @@ def main():
         hs.hs_reset_state(s.app)
     paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
              for f in frames]
+    hog_stop = threading.Event()
+    hog_count = [0] * len(hogs)
+
+    def hog_worker(i):
+        s, k, inflight = hogs[i], 0, 0
+        while not hog_stop.is_set():
+            if s.submit(hog_frames[i][k % 2], hog_outs[i][k % args.queue_depth], k) == hs.HS_OK:
+                k += 1
+                inflight += 1
+            else:
+                s.wait()
+                inflight -= 1
+                hog_count[i] += 1
+        for _ in range(inflight):
+            s.wait()
+
+    hog_threads = [threading.Thread(target=hog_worker, args=(i,)) for i in range(len(hogs))]
+    for t in hog_threads:
+        t.start()
+    t_hog = time.perf_counter()
     results, dropped = run_paced(streams, paced, args.fps, outs)
+    hog_stop.set()
+    for t in hog_threads:
+        t.join()
+    t_hog = time.perf_counter() - t_hog
     lat_ms = []
     for rs in results:
         for j in range(args.batch):
@@ -159,6 +195,11 @@ def main():
             t = min(10, len(per) // 6)
             lat_ms.extend(per[t:len(per) - t])   # trim each stream's warm-up / cool-down
     m = hs.hs_latency_metrics_compute(lat_ms, trim=False)
+    per_stream_p50 = []
+    for rs in results:
+        for j in range(args.batch):
+            per = [(r[j].t_overlay_done_ns - r[j].t_submit_ns) / 1e6 for r in rs]
+            per_stream_p50.append(round(float(np.median(per)), 4))
     stage_ms = {}
     for name, a, b in (("pre", "t_submit_ns", "t_pre_done_ns"),
                        ("infer", "t_pre_done_ns", "t_infer_done_ns"),
@@ -210,7 +251,7 @@ def main():
             d["GB/s"] = round(e["bytes"] / (e["total_ms"] * 1e-3) / 1e9, 1)
         kernels[e["name"]] = d
 
-    for s in streams:
+    for s in streams + hogs:
         s.close()
     hs.hs_shutdown(ctx)
 
@@ -246,13 +287,14 @@ def main():
                                "argmax, alpha-blend overlay on the 1080p frame",
                    "streams": args.streams, "batch": args.batch, "partition": args.partition,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
-                   "device_cus": n_cus},
+                   "hog_apps": args.hog, "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),
                        "std": round(m["std"], 4), "tail": round(m["tail"], 4),
                        "flatness": round(m["flatness"], 4), "dropped": int(sum(dropped)),
-                       "stage_median_ms": stage_ms},
+                       "stage_median_ms": stage_ms, "per_stream_p50": per_stream_p50,
+                       "hog_frames_per_s": round(sum(hog_count) / t_hog, 1) if hogs else None},
         "roofline": roof,
         "kernels": kernels,
         "cpu_baseline": cpu,
