@@ -34,7 +34,8 @@ struct ResizeParams {
   float* dst_f32;       // optional planar fp32 [3][ho][wo]
   const float* lut32;   // 256 entries
   const f16* lut16;     // 256 entries
-  float rcp_dx, rcp_dy, rcp_d;  // 1/(2*wo), 1/(2*ho), 1/(4*wo*ho): division estimates
+  float rcp_dx, rcp_dy;         // 1/(2*wo), 1/(2*ho): division estimates
+  uint32_t d_magic, d_shift;    // floor(n / (4*wo*ho)) = mulhi(n, d_magic) >> d_shift for n < 2^31
 };
 KernelDesc describe(const ResizeParams& p);
 
@@ -123,6 +124,7 @@ struct PostParams {
   float* heat; uint8_t* mask;    // [8][n]
   PostRecord* rec;               // host-visible
   int batch;                     // images: logits/heat/mask are [batch][8][n], rec[batch]
+  uint8_t* kmap;                 // [batch][n]: lowest channel with mask set, 0xff if none
 };
 KernelDesc describe(const PostParams& p);
 
@@ -130,7 +132,9 @@ KernelDesc describe(const PostParams& p);
 struct OverlayParams {
   const uint8_t* src[kMaxBatch]; uint8_t* dst[kMaxBatch];   // per stream
   int batch; size_t pitch; int wf, hf;
-  const uint8_t* mask; int wm, hm;   // [batch][8][hm][wm]
+  const uint8_t* kmap; int wm, hm;   // [batch][hm][wm]: lowest set mask channel or 0xff
+  float rcp_gpr, rcp_hf, rcp_wf, rcp_wm;   // 1/ceil(wf/16), 1/hf, 1/wf, 1/wm: division estimates
+                                     // (needs wf*wm, hf*hm and ceil(wf/16)*hf below 2^31)
   int a;                             // Q8 alpha, 0..256
   uint32_t pal[8];                   // R | G<<8 | B<<16
 };

@@ -51,8 +51,8 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
   s_lut16[tid] = p.lut16[tid];
   __syncthreads();
 
-  const uint8_t* p0 = lds;
-  const uint8_t* p1 = lds + (size_t)row_vecs * 16;
+  const uint32_t* p0 = reinterpret_cast<const uint32_t*>(lds);
+  const uint32_t* p1 = reinterpret_cast<const uint32_t*>(lds + (size_t)row_vecs * 16);
   const uint32_t d = dx * dy;
   const uint32_t wy1 = fy, wy0 = dy - fy;
   for (int X = tid; X < p.wo; X += 256) {
@@ -60,15 +60,25 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
     nx = max(0, min(nx, (p.wi - 1) * (int)dx));
     const uint32_t x0 = udiv_est((uint32_t)nx, dx, p.rcp_dx);
     const uint32_t fx = (uint32_t)nx - x0 * dx;
-    const uint32_t x1 = min(x0 + 1u, (uint32_t)(p.wi - 1));
     const uint32_t wx1 = fx, wx0 = dx - fx;
+    // The two source pixels x0, x0+1 are 6 consecutive bytes inside three aligned words: fetch
+    // the words from each row and funnel-shift the bytes into place (v_alignbyte).  At the
+    // right edge x0 + 1 is past the row, its weight fx is 0 there and the bytes read are the
+    // next row or the padding behind the rows.
+    const uint32_t b0 = 3u * x0, wi0 = b0 >> 2, sh = b0 & 3u;
+    const uint32_t a0 = __builtin_amdgcn_alignbyte(p0[wi0 + 1], p0[wi0], sh);      // bytes 0..3
+    const uint32_t a1 = __builtin_amdgcn_alignbyte(p0[wi0 + 2], p0[wi0 + 1], sh);  // bytes 4..7
+    const uint32_t c0 = __builtin_amdgcn_alignbyte(p1[wi0 + 1], p1[wi0], sh);
+    const uint32_t c1 = __builtin_amdgcn_alignbyte(p1[wi0 + 2], p1[wi0 + 1], sh);
+    const uint64_t r0 = (uint64_t)a1 << 32 | a0, r1 = (uint64_t)c1 << 32 | c0;
     uint32_t q[3];
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
-      const uint32_t p00 = p0[3 * x0 + c], p01 = p0[3 * x1 + c];
-      const uint32_t p10 = p1[3 * x0 + c], p11 = p1[3 * x1 + c];
+      const uint32_t p00 = (uint32_t)(r0 >> (8 * c)) & 0xffu, p01 = (uint32_t)(r0 >> (8 * c + 24)) & 0xffu;
+      const uint32_t p10 = (uint32_t)(r1 >> (8 * c)) & 0xffu, p11 = (uint32_t)(r1 >> (8 * c + 24)) & 0xffu;
       const uint32_t acc = wy0 * (wx0 * p00 + wx1 * p01) + wy1 * (wx0 * p10 + wx1 * p11);
-      q[c] = udiv_est(acc + (d >> 1), d, p.rcp_d);
+      // floor((acc + d/2) / d) by multiplication: exact for numerators below 2^31
+      q[c] = __umulhi(acc + (d >> 1), p.d_magic) >> p.d_shift;
     }
     half4 px;
     px[0] = s_lut16[q[0]];
@@ -87,7 +97,7 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
 }
 
 KernelDesc describe(const ResizeParams& p) {
-  const unsigned lds = (unsigned)((3 * p.wi + 15) >> 4) * 16 * 2;
+  const unsigned lds = (unsigned)((3 * p.wi + 15) >> 4) * 16 * 2 + 16;   // + padding read at the edge
   return KernelDesc{(const void*)k_resize_norm, dim3(p.ho, p.batch), dim3(256), lds};
 }
 
@@ -748,7 +758,7 @@ KernelDesc describe(const StemPoolParams& p) {
 }
 
 // =============================================================================================
-// Stage 3: one workgroup per tool channel.  Every lane keeps (best value, lowest index);
+// Stage 3: one workgroup per tool channel (plus one for the overlay's channel map).  Every lane keeps (best value, lowest index);
 // wavefront butterfly reduction, then one more across the 4 wavefronts through LDS.
 // The integer outputs are decided on the logits with exact comparisons.
 // =============================================================================================
@@ -761,6 +771,18 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
   __shared__ int s_i[4];
   const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const size_t img_off = (size_t)blockIdx.y * 8 * p.n;   // image blockIdx.y of the batch
+  if (k == 8) {
+    // ninth workgroup: per cell the lowest channel whose mask is set (what the overlay draws),
+    // decided on the logits with the same comparison as the masks
+    for (int i = tid; i < p.n; i += 256) {
+      uint8_t lowest = 0xff;
+#pragma unroll
+      for (int c = 7; c >= 0; --c)
+        if (p.logits[img_off + (size_t)c * p.n + i] > p.theta) lowest = (uint8_t)c;
+      p.kmap[(size_t)blockIdx.y * p.n + i] = lowest;
+    }
+    return;
+  }
   float* const heat = p.heat + img_off;
   uint8_t* const mask = p.mask + img_off;
   PostRecord* const rec = p.rec + blockIdx.y;
@@ -791,72 +813,166 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
 }
 
 KernelDesc describe(const PostParams& p) {
-  return KernelDesc{(const void*)k_postprocess, dim3(8, p.batch), dim3(256), 0};
+  return KernelDesc{(const void*)k_postprocess, dim3(9, p.batch), dim3(256), 0};
 }
 
 // =============================================================================================
-// Stage 4: one workgroup per frame row.  The row's mask cells are reduced to "lowest set
-// channel" once in LDS; each thread then streams 16 pixels (48 bytes) with 16-byte accesses.
+// Stage 4: pure streaming.  A thread owns one group of 16 pixels (48 bytes, three 16-byte
+// accesses) of one frame row; groups are numbered row-major over the frame, 256 per workgroup,
+// so there is no per-row prologue and no barrier.  A group spans at most two cells of the
+// channel map when a cell is at least 16 pixels wide: both are fetched up front together with
+// the pixels (a third cell, on tiny frames, is fetched on demand).  Where the frame rows are
+// contiguous, a wavefront moves its 3072 bytes as fully coalesced 16-byte vectors and regroups
+// them through LDS, instead of every lane touching its own 48-byte span.
 // =============================================================================================
-__global__ __launch_bounds__(128) void k_overlay(OverlayParams p) {
-  extern __shared__ uint8_t s_k[];        // wm entries: lowest set channel or 0xff
-  const int Y = blockIdx.x, tid = threadIdx.x;
-  const int my = (int)(((long long)Y * p.hm) / p.hf);
-  for (int x = tid; x < p.wm; x += 128) {
-    uint8_t k = 0xff;
-    for (int c = 7; c >= 0; --c)
-      if (p.mask[(((size_t)blockIdx.y * 8 + c) * p.hm + my) * p.wm + x]) k = (uint8_t)c;
-    s_k[x] = k;
-  }
-  __syncthreads();
+__global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
+  __shared__ u32x4 s_x[4][192];
+  const int gpr = (p.wf + 15) >> 4;                              // groups per row
+  const int g = (int)blockIdx.x * 256 + (int)threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g_wave = g - lane;                                   // first group of the wavefront
+  // rows of whole groups butt against each other and the wavefront is full (uniform per wavefront)
+  const bool coalesced =
+      (p.wf & 15) == 0 && p.pitch == (size_t)48 * gpr && g_wave + 64 <= gpr * p.hf;
+  if (g >= gpr * p.hf) return;
+  // all quotients by float estimate + exact fix-up (operands < 2^31, quotients < 2^22)
+  const int Y = (int)udiv_est((uint32_t)g, (uint32_t)gpr, p.rcp_gpr), X0 = (g - Y * gpr) * 16;
+  const int my = (int)udiv_est((uint32_t)(Y * p.hm), (uint32_t)p.hf, p.rcp_hf);
+  const uint8_t* krow = p.kmap + ((size_t)blockIdx.y * p.hm + my) * p.wm;
   const uint8_t* srow = p.src[blockIdx.y] + (size_t)Y * p.pitch;
   uint8_t* drow = p.dst[blockIdx.y] + (size_t)Y * p.pitch;
   const int ia = 256 - p.a;
-  for (int X0 = tid * 16; X0 < p.wf; X0 += 128 * 16) {
-    const int npx = min(16, p.wf - X0);
-    int mx = (int)(((long long)X0 * p.wm) / p.wf);
-    int rem = (int)(((long long)X0 * p.wm) - (long long)mx * p.wf);
-    if (npx == 16) {
-      uint4 v[3];
-      const uint4* s4 = reinterpret_cast<const uint4*>(srow + (size_t)X0 * 3);
+  const int npx = min(16, p.wf - X0);
+  const int mx0 = (int)udiv_est((uint32_t)(X0 * p.wm), (uint32_t)p.wf, p.rcp_wf);
+  int mx = mx0;
+  int rem = X0 * p.wm - mx * p.wf;
+  if (npx == 16) {
+    u32x4 v[3];
+    if (coalesced) {
+      // the wavefront's 64 groups are 3072 contiguous bytes: fetch them as 3 x 64 consecutive
+      // 16-byte vectors and regroup through LDS (own region per wavefront, no workgroup barrier)
+      const u32x4* s4 = reinterpret_cast<const u32x4*>(p.src[blockIdx.y] + (size_t)g_wave * 48);
+      const u32x4 t0 = s4[lane], t1 = s4[64 + lane], t2 = s4[128 + lane];
+      s_x[wave][lane] = t0; s_x[wave][64 + lane] = t1; s_x[wave][128 + lane] = t2;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      v[0] = s_x[wave][3 * lane]; v[1] = s_x[wave][3 * lane + 1]; v[2] = s_x[wave][3 * lane + 2];
+    } else {
+      const u32x4* s4 = reinterpret_cast<const u32x4*>(srow + (size_t)X0 * 3);
       v[0] = s4[0]; v[1] = s4[1]; v[2] = s4[2];
-      uint8_t* b = reinterpret_cast<uint8_t*>(v);
+    }
+    const uint8_t k0 = krow[mx0], k1 = krow[min(mx0 + 1, p.wm - 1)];
+    uint32_t w[12];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) w[i] = v[i >> 2][i & 3];
+    // Most groups see one channel for all 16 pixels: nothing to draw, or one colour.  Then the
+    // blend runs on two bytes per 32-bit operation: even and odd bytes of a word are 16-bit
+    // fields, (256 - a) * byte + (a * colour + 128) never exceeds 65408, so no field carries into
+    // its neighbour.  Word j of the group starts with channel j mod 3.
+    const int mx_last = (int)udiv_est((uint32_t)((X0 + 15) * p.wm), (uint32_t)p.wf, p.rcp_wf);
+    const bool one_cell = mx_last == mx0 || (mx_last == mx0 + 1 && k1 == k0);
+    if (one_cell) {
+      if (k0 != 0xff) {
+        const uint32_t col = p.pal[k0];
+        uint32_t t[3];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) t[c] = (uint32_t)p.a * ((col >> (8 * c)) & 0xffu) + 128u;
+#pragma unroll
+        for (int j = 0; j < 12; ++j) {
+          const uint32_t ce = t[j % 3] | (t[(j + 2) % 3] << 16);        // bytes 0 and 2
+          const uint32_t co = t[(j + 1) % 3] | (t[(j + 3) % 3] << 16);  // bytes 1 and 3
+          const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
+          w[j] = (((e * (uint32_t)ia + ce) >> 8) & 0x00ff00ffu) |
+                 ((o * (uint32_t)ia + co) & 0xff00ff00u);
+        }
+      }
+    } else if (mx_last == mx0 + 1) {
+      // two cells: pixels [0, s) see k0, [s, 16) see k1.  Same packed blend with the colour
+      // term chosen per byte (byte index < 3*s), then bytes of an undrawn cell are restored.
+      const int s3 = 3 * (int)udiv_est((uint32_t)(p.wf - rem + p.wm - 1), (uint32_t)p.wm, p.rcp_wm);
+      const uint32_t c0 = k0 != 0xff ? p.pal[k0 & 7] : 0u, c1 = k1 != 0xff ? p.pal[k1 & 7] : 0u;
+      const uint32_t d0 = k0 != 0xff ? 0xffffffffu : 0u, d1 = k1 != 0xff ? 0xffffffffu : 0u;
+      uint32_t t0[3], t1[3];
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        t0[c] = (uint32_t)p.a * ((c0 >> (8 * c)) & 0xffu) + 128u;
+        t1[c] = (uint32_t)p.a * ((c1 >> (8 * c)) & 0xffu) + 128u;
+      }
+#pragma unroll
+      for (int j = 0; j < 12; ++j) {
+        const uint32_t tb0 = 4 * j + 0 < s3 ? t0[j % 3] : t1[j % 3];
+        const uint32_t tb1 = 4 * j + 1 < s3 ? t0[(j + 1) % 3] : t1[(j + 1) % 3];
+        const uint32_t tb2 = 4 * j + 2 < s3 ? t0[(j + 2) % 3] : t1[(j + 2) % 3];
+        const uint32_t tb3 = 4 * j + 3 < s3 ? t0[(j + 3) % 3] : t1[(j + 3) % 3];
+        const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
+        const uint32_t blended = (((e * (uint32_t)ia + (tb0 | (tb2 << 16))) >> 8) & 0x00ff00ffu) |
+                                 ((o * (uint32_t)ia + (tb1 | (tb3 << 16))) & 0xff00ff00u);
+        const int nb = min(4, max(0, s3 - 4 * j));                    // leading bytes of cell 0
+        const uint32_t low = nb == 4 ? 0xffffffffu : ((1u << (8 * nb)) - 1u);
+        const uint32_t draw = (low & d0) | (~low & d1);
+        w[j] = (blended & draw) | (w[j] & ~draw);
+      }
+    } else {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const uint8_t k = s_k[mx];
+        const uint8_t k = mx == mx0 ? k0 : (mx == mx0 + 1 ? k1 : krow[mx]);
         if (k != 0xff) {
           const uint32_t col = p.pal[k];
 #pragma unroll
           for (int c = 0; c < 3; ++c) {
+            const int byte = 3 * i + c;                 // literal after unrolling
             const uint32_t pc = (col >> (8 * c)) & 0xffu;
-            b[3 * i + c] = (uint8_t)((p.a * pc + ia * (uint32_t)b[3 * i + c] + 128u) >> 8);
+            const uint32_t old = (w[byte >> 2] >> (8 * (byte & 3))) & 0xffu;
+            const uint32_t nw = (p.a * pc + ia * old + 128u) >> 8;
+            w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (nw << (8 * (byte & 3)));
           }
-        }
-        rem += p.wm;
-        while (rem >= p.wf) { rem -= p.wf; ++mx; }
-      }
-      uint4* d4 = reinterpret_cast<uint4*>(drow + (size_t)X0 * 3);
-      d4[0] = v[0]; d4[1] = v[1]; d4[2] = v[2];
-    } else {
-      for (int i = 0; i < npx; ++i) {
-        const uint8_t k = s_k[mx];
-        for (int c = 0; c < 3; ++c) {
-          uint32_t x = srow[(size_t)(X0 + i) * 3 + c];
-          if (k != 0xff) {
-            const uint32_t pc = (p.pal[k] >> (8 * c)) & 0xffu;
-            x = (p.a * pc + ia * x + 128u) >> 8;
-          }
-          drow[(size_t)(X0 + i) * 3 + c] = (uint8_t)x;
         }
         rem += p.wm;
         while (rem >= p.wf) { rem -= p.wf; ++mx; }
       }
     }
+    if (coalesced) {
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        u32x4 o = {w[4 * j], w[4 * j + 1], w[4 * j + 2], w[4 * j + 3]};
+        s_x[wave][3 * lane + j] = o;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      u32x4* d4 = reinterpret_cast<u32x4*>(p.dst[blockIdx.y] + (size_t)g_wave * 48);
+      d4[lane] = s_x[wave][lane];
+      d4[64 + lane] = s_x[wave][64 + lane];
+      d4[128 + lane] = s_x[wave][128 + lane];
+    } else {
+      u32x4* d4 = reinterpret_cast<u32x4*>(drow + (size_t)X0 * 3);
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        u32x4 o = {w[4 * j], w[4 * j + 1], w[4 * j + 2], w[4 * j + 3]};
+        d4[j] = o;
+      }
+    }
+  } else {
+    for (int i = 0; i < npx; ++i) {
+      const uint8_t k = krow[mx];
+      for (int c = 0; c < 3; ++c) {
+        uint32_t x = srow[(size_t)(X0 + i) * 3 + c];
+        if (k != 0xff) {
+          const uint32_t pc = (p.pal[k] >> (8 * c)) & 0xffu;
+          x = (p.a * pc + ia * x + 128u) >> 8;
+        }
+        drow[(size_t)(X0 + i) * 3 + c] = (uint8_t)x;
+      }
+      rem += p.wm;
+      while (rem >= p.wf) { rem -= p.wf; ++mx; }
+    }
   }
 }
 
 KernelDesc describe(const OverlayParams& p) {
-  return KernelDesc{(const void*)k_overlay, dim3(p.hf, p.batch), dim3(128), (unsigned)p.wm};
+  const unsigned groups = (unsigned)(((p.wf + 15) >> 4) * p.hf);
+  return KernelDesc{(const void*)k_overlay, dim3((groups + 255) / 256, p.batch), dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------

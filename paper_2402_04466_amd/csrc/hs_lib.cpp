@@ -572,7 +572,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   const int mh = b.map_h, mw = b.map_w;
   const size_t n_map = (size_t)mh * mw;
   const int B = d->batch;
-  struct SlotBuf { f16* netin; float* netin32; float* logits; float* heat; uint8_t* mask; };
+  struct SlotBuf { f16* netin; float* netin32; float* logits; float* heat; uint8_t* mask;
+                   uint8_t* kmap; };
   std::vector<SlotBuf> sb(depth);
   for (int i = 0; i < depth; ++i) {
     sb[i].netin = b.carve.take<f16>((size_t)B * ph * pw * 4);
@@ -581,6 +582,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     sb[i].logits = b.carve.take<float>(B * 8 * n_map);
     sb[i].heat = b.carve.take<float>(B * 8 * n_map);
     sb[i].mask = b.carve.take<uint8_t>(B * 8 * n_map);
+    sb[i].kmap = b.carve.take<uint8_t>(B * n_map);
   }
   const size_t total = round_up_sz(b.carve.off, 256);
   if (bytes_out) *bytes_out = total;
@@ -640,7 +642,16 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       rp.dst = s.d_netin; rp.dst_w = pw; rp.pad_l = pad; rp.pad_t = pad;
       rp.dst_f32 = s.d_netin_f32; rp.lut32 = d_lut32; rp.lut16 = d_lut16;
       rp.rcp_dx = 1.0f / (2.0f * d->net_w); rp.rcp_dy = 1.0f / (2.0f * d->net_h);
-      rp.rcp_d = 1.0f / (4.0f * (float)d->net_w * (float)d->net_h);
+      {
+        // D = 4*wo*ho; l = ceil(log2 D); magic = ceil(2^(31+l) / D) < 2^32.  The error term
+        // magic*D - 2^(31+l) is below D <= 2^l, so floor(n/D) = (n*magic) >> (31+l) for n < 2^31.
+        const uint64_t D = 4ull * (uint64_t)d->net_w * (uint64_t)d->net_h;
+        int l = 0;
+        while ((1ull << l) < D) ++l;
+        const unsigned __int128 num = (unsigned __int128)1 << (31 + l);
+        rp.d_magic = (uint32_t)((num + D - 1) / D);
+        rp.d_shift = (uint32_t)(l - 1);
+      }
       r.bytes = B * (3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
                      (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0));
       s.pre.push_back(r);
@@ -655,7 +666,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     {
       Op p;
       p.fam = F_POST;
-      p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec, B};
+      p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec, B,
+                          sb[i].kmap};
       p.bytes = B * 8.0 * n_map * (4 + 4 + 1);
       s.post.push_back(p);
     }
@@ -665,12 +677,15 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       OverlayParams& op = o.overlay;
       std::memset(&op, 0, sizeof(op));
       op.batch = B; op.pitch = d->frame_pitch;
-      op.wf = d->frame_w; op.hf = d->frame_h; op.mask = s.d_mask; op.wm = mw; op.hm = mh;
+      op.wf = d->frame_w; op.hf = d->frame_h; op.kmap = sb[i].kmap; op.wm = mw; op.hm = mh;
+      op.rcp_gpr = 1.0f / (float)((d->frame_w + 15) / 16);
+      op.rcp_hf = 1.0f / (float)d->frame_h; op.rcp_wf = 1.0f / (float)d->frame_w;
+      op.rcp_wm = 1.0f / (float)mw;
       op.a = a_q8;
       for (int k = 0; k < 8; ++k)
         op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
                     ((uint32_t)d->palette[k][2] << 16);
-      o.bytes = B * (6.0 * d->frame_w * d->frame_h + 8.0 * n_map);
+      o.bytes = B * (6.0 * d->frame_w * d->frame_h + 1.0 * n_map);
       s.overlay.push_back(o);
     }
     HS_HIP(hipEventCreate(&s.ev_pre));

@@ -192,6 +192,42 @@ def test_batched_streams_match_per_stream_oracles(hs, ctx, net, net_name, layers
         s.close()
 
 
+def test_config5_full_size_batch12_sampled_streams(hs, ctx):
+    """The saturation configuration as bench.py runs it: 12 streams of 1920x1080 frames batched
+    through one pass of the big network (854x480 input, HIP-graph launch, the large-grid kernel
+    variants), two frames with the state carried.  Streams 0, 7 and 11 are checked in full
+    against their own oracle streams; all twelve must show distinct, finite outputs."""
+    from paper_2402_04466_amd.harness import AppStream
+    B, T, sampled = 12, 2, (0, 7, 11)
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    frames = {j: list(si.tool_scene_frames(T, 1080, 1920, 13 + j)) for j in range(B)}
+    s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=1920, frame_h=1080, net_w=854,
+                  net_h=480, blob=blob, palette=PAL, queue_depth=2, batch=B)
+    hs.hs_set_launch_mode(s.app, hs.HS_LAUNCH_GRAPH)
+    oracles = {j: make_oracles("resnet18_convlstm", blob, 854, 480, True, PAL) for j in sampled}
+    try:
+        for t in range(T):
+            print(f"[config5] frame {t}", flush=True)
+            d_in = [s.upload_frame(frames[j][t]) for j in range(B)]
+            d_out = [s.new_output() for _ in range(B)]
+            assert s.submit_batch(d_in, d_out, t) == hs.HS_OK
+            rs = s.wait_batch()
+            assert len(rs) == B and all(r.frame_id == t for r in rs)
+            logits = [s.fetch(rs[j])["logits"] for j in range(B)]
+            assert all(np.isfinite(l).all() for l in logits)
+            for j in range(1, B):
+                assert not np.array_equal(logits[j], logits[0])       # streams are not mixed up
+            for j in sampled:
+                g = s.fetch(rs[j], d_out[j])
+                a, b = oracles[j][0].process(frames[j][t]), oracles[j][1].process(frames[j][t])
+                check_frame(g, frames[j][t], a, b, threshold=0.5, alpha=0.5, palette=PAL,
+                            fp32_input=False, tag=f"config5/stream{j}/frame{t}")
+                gh, gc = s.state(rs[j], stream=j)
+                assert rms_rel(gh, a["h"]) <= TOL_STATE_RMS and rms_rel(gc, a["c"]) <= TOL_STATE_RMS
+    finally:
+        s.close()
+
+
 def test_graph_and_kernel_by_kernel_launch_paths_agree(hs, ctx):
     """The pre-built HIP graph of stages 1-3 is replayed for several frames (with the host's
     own synchronisation and read-backs between replays) and must give, frame by frame and
