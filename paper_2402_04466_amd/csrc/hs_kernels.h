@@ -60,7 +60,10 @@ struct ConvParams {
                         //    needs cin % 64 == 0; spatial tile 8 x 8 (1) or 8 x 16 (2, 3);
                         //    3 keeps one patch buffer and three weight stages, so that three
                         //    workgroups fit a CU (grids well beyond two workgroups per CU)
-  int tiles_x;          // variant 1, 2, 3: spatial tiles per output row
+                        // 4: 3x3/2 pad-1 layers the same way (8 x 8 tile, patch stored as four
+                        //    parity planes), optionally with the block's 1x1/2 projection of
+                        //    the same input fused in (wt2 != NULL)
+  int tiles_x;          // variant 1..4: spatial tiles per output row
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;
   // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)
@@ -76,6 +79,10 @@ struct ConvParams {
   int res_pitch;
   int relu;
   float* out_f32;       // if set: planar fp32 out_f32[n*m_total + m] instead of `out`
+  // variant 4 only: fused 1x1 stride-2 projection of the same input (no residual, no ReLU)
+  const f16* wt2;       // packed [cout_pad][cin], or NULL
+  f16* out2; int out2_pitch;
+  float* partial2;      // [nsplit][m][cout_pad] fp32 when use_partial
 };
 KernelDesc describe(const ConvParams& p);
 
@@ -83,6 +90,8 @@ KernelDesc describe(const ConvParams& p);
 struct SplitKEpilogueParams {
   const float* partial; int nsplit; int m; int cout; int cout_pad;
   f16* out; int out_pitch; const f16* res; int res_pitch; int relu; float* out_f32; int img_m;
+  // optional second tensor reduced in the same launch (fused projection): plain fp16 store
+  const float* partial2; f16* out2; int out2_pitch;
 };
 KernelDesc describe(const SplitKEpilogueParams& p);
 

@@ -355,22 +355,28 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
 // Wavefront (wm, wn): pixel rows 4*wm .. 4*wm+3 (MT groups of 4 x 8 pixels), channels
 // 32*wn .. +31.  chunks_per_split / nchunks count Cin chunks here (split-K over Cin).
 // =============================================================================================
-template <int MT, int PB, int WS>
+template <int MT, int PB, int WS, int STRIDE>
 __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
-  constexpr int KC = 64, TH = 8, TW = 8 * MT, PH = TH + 2, PW = TW + 2, NPIX = PH * PW;
+  constexpr int KC = 64, TH = 8, TW = 8 * MT;
+  constexpr int IPH = STRIDE * TH + 3 - STRIDE, IPW = STRIDE * TW + 3 - STRIDE;   // input patch
+  constexpr int NPL = STRIDE * STRIDE;                 // parity planes the patch is stored as
+  constexpr int PLH = STRIDE == 1 ? IPH : TH + 1, PLW = STRIDE == 1 ? IPW : TW + 1;
+  constexpr int NPIX = IPH * IPW;
   constexpr int PITCH = KC + 8;
   constexpr int BN = 64;                     // output channels per workgroup
   constexpr int WL = BN / 32;                // weight vectors per thread and tap
-  // Patch rows are padded so that consecutive rows start 128 bytes apart modulo 256: the 16
+  // Plane rows are padded so that consecutive rows start 128 bytes apart modulo 256: the 16
   // lanes of one ds_read_b128 pass (two rows of 8 pixels, 144-byte pixel pitch) then fall into
   // 16 different 16-byte bank groups.
-  constexpr int RP = PW * PITCH + (TW == 8 ? 112 : 48);   // halves per patch row
-  static_assert((RP * 2) % 256 == 128, "patch row pitch must be 128 mod 256 bytes");
+  constexpr int RP = (PLW * PITCH * 2 + ((128 - (PLW * PITCH * 2) % 256 + 256) % 256)) / 2;
+  static_assert((RP * 2) % 256 == 128, "plane row pitch must be 128 mod 256 bytes");
   constexpr int PV = NPIX * 8;               // 16-byte vectors in a patch
-  constexpr int PL = (PV + 255) / 256;       // patch vectors per thread (4 or 6)
-  static_assert(PL <= 9, "patch prefetch is spread over the nine taps");
+  constexpr int PL = (PV + 255) / 256;       // patch vectors per thread (4, 6 or 10)
+  constexpr int PT = (PL + 8) / 9;           // of which fetched per tap
+  static_assert(PT <= 2, "patch prefetch is spread over the nine taps");
   static_assert(WS == 9 || WS == 3, "weight stages: a divisor of nine");
-  __shared__ __align__(16) f16 s_patch[PB][PH * RP];
+  static_assert(STRIDE == 1 || (MT == 1 && PB == 1), "stride 2: 8 x 8 tile, one patch buffer");
+  __shared__ __align__(16) f16 s_patch[PB][NPL * PLH * RP];
   __shared__ __align__(16) f16 s_w[2][BN * PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
@@ -385,14 +391,17 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   const int y0 = ty * TH, x0 = tx * TW, n0 = tile_n * BN;
   const int cc_begin = split * p.chunks_per_split;
   const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
+  const bool has_proj = STRIDE == 2 && p.wt2 != nullptr;
 
   // loop-invariant loader state
   const f16* l_wbase[WL];
+  const f16* l_w2base[WL];
   int l_wlds[WL];
 #pragma unroll
   for (int i = 0; i < WL; ++i) {
     const int v = tid + 256 * i, row = v >> 3, kv = v & 7;
     l_wbase[i] = p.wt + (size_t)(n0 + row) * p.ktot + kv * 8;
+    l_w2base[i] = has_proj ? p.wt2 + (size_t)(n0 + row) * (p.chunks_per_tap * KC) + kv * 8 : p.wt;
     l_wlds[i] = row * PITCH + kv * 8;
   }
   const f16* l_pbase[PL];
@@ -402,20 +411,26 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   for (int i = 0; i < PL; ++i) {
     const int v = tid + 256 * i;
     const int pix = min(v >> 3, NPIX - 1), kv = v & 7;
-    const int py = pix / PW, px = pix - py * PW;
-    const int iy = y0 + py - 1, ix = x0 + px - 1;
+    const int py = pix / IPW, px = pix - py * IPW;
+    const int iy = STRIDE * y0 + py - 1, ix = STRIDE * x0 + px - 1;
     l_pact[i] = v < PV;
     l_pinb[i] = l_pact[i] && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
     l_pbase[i] = l_pinb[i] ? p.in + (((long)img * p.hin + iy) * p.win + ix) * p.cin_pitch + kv * 8
                            : p.in;
-    l_plds[i] = py * RP + px * PITCH + kv * 8;
+    // stride 2: pixel (py, px) goes to parity plane (py & 1, px & 1) at (py / 2, px / 2), so
+    // that the lanes of a tap read neighbouring plane pixels, as for stride 1
+    l_plds[i] = STRIDE == 1 ? py * RP + px * PITCH + kv * 8
+                            : (((py & 1) * 2 + (px & 1)) * PLH + (py >> 1)) * RP +
+                                  (px >> 1) * PITCH + kv * 8;
   }
 
-  floatx16 acc[MT];
+  floatx16 acc[MT], acc2;
 #pragma unroll
   for (int g = 0; g < MT; ++g)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc2[i] = 0.0f;
 
   const int wm = wave & 1, wn = wave >> 1;
   // fragment bases: weights row (32*wn + r); pixel (4*wm + r/8, r%8) of column group g
@@ -423,6 +438,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   const int fp_off = (4 * wm + (r >> 3)) * RP + (r & 7) * PITCH + h * 8;
 
   u32x4 st_w[WS][WL];
+  u32x4 st_w2[WL];
   u32x4 st_p[PL];
 #define HS_LOAD_W(S_, CC_, TAP_)                                                               \
   {                                                                                            \
@@ -430,8 +446,15 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     _Pragma("unroll") for (int i = 0; i < WL; ++i)                                             \
       st_w[S_][i] = *reinterpret_cast<const u32x4*>(l_wbase[i] + off_);                        \
   }
+#define HS_LOAD_W2(CC_)                                                                        \
+  _Pragma("unroll") for (int i = 0; i < WL; ++i)                                               \
+    st_w2[i] = *reinterpret_cast<const u32x4*>(l_w2base[i] + (long)(CC_) * KC);
 #define HS_LOAD_P(I_, CC_)                                                                     \
   st_p[I_] = *reinterpret_cast<const u32x4*>(l_pinb[I_] ? l_pbase[I_] + (long)(CC_) * KC : p.in);
+  // offset of tap (ky, kx) inside the patch, relative to the wavefront's first pixel
+#define HS_TAP_OFF(KY_, KX_)                                                                   \
+  (STRIDE == 1 ? (KY_) * RP + (KX_) * PITCH                                                    \
+               : ((((KY_) & 1) * 2 + ((KX_) & 1)) * PLH + ((KY_) >> 1)) * RP + ((KX_) >> 1) * PITCH)
 
   // One tap of chunk cc.  TAP_ and LAST_ are literals: every register index and every
   // refill decision is resolved at compile time.  Weight stage TAP_ % WS is handed to LDS and
@@ -450,9 +473,12 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     __syncthreads();                                                                           \
     if (!(LAST_) || (TAP_) + WS < 9)                                                           \
       HS_LOAD_W((TAP_) % WS, cc + ((TAP_) + WS) / 9, ((TAP_) + WS) % 9)                        \
-    if (!(LAST_) && (TAP_) < PL) { HS_LOAD_P((TAP_) < PL ? (TAP_) : 0, cc + 1) }               \
+    if (!(LAST_)) {                                                                            \
+      _Pragma("unroll") for (int i = PT * (TAP_); i < PT * (TAP_) + PT; ++i)                   \
+        if (i < PL) { HS_LOAD_P(i < PL ? i : 0, cc + 1) }                                      \
+    }                                                                                          \
     const f16* fw_ = &s_w[buf][fw_off];                                                        \
-    const f16* fp_ = &s_patch[pb][fp_off + ((TAP_) / 3) * RP + ((TAP_) % 3) * PITCH];          \
+    const f16* fp_ = &s_patch[pb][fp_off + HS_TAP_OFF((TAP_) / 3, (TAP_) % 3)];                \
     _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                   \
       const half8 a_ = *reinterpret_cast<const half8*>(fw_ + ks * 16);                         \
       _Pragma("unroll") for (int g = 0; g < MT; ++g) {                                         \
@@ -462,9 +488,27 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     }                                                                                          \
     buf ^= 1;                                                                                  \
   }
+  // Tenth step of a stride-2 chunk: the 1x1 stride-2 projection of the same input reads exactly
+  // the centre tap's pixels, so it rides along with its own weights and accumulator.
+#define HS_PROJ(LAST_)                                                                         \
+  if (has_proj) {                                                                              \
+    _Pragma("unroll") for (int i = 0; i < WL; ++i)                                             \
+      *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[i]]) = st_w2[i];                              \
+    __syncthreads();                                                                           \
+    if (!(LAST_)) { HS_LOAD_W2(cc + 1) }                                                       \
+    const f16* fw_ = &s_w[buf][fw_off];                                                        \
+    const f16* fp_ = &s_patch[pb][fp_off + HS_TAP_OFF(1, 1)];                                  \
+    _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                   \
+      const half8 a_ = *reinterpret_cast<const half8*>(fw_ + ks * 16);                         \
+      const half8 b_ = *reinterpret_cast<const half8*>(fp_ + ks * 16);                         \
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_, b_, acc2, 0, 0, 0);                    \
+    }                                                                                          \
+    buf ^= 1;                                                                                  \
+  }
 #define HS_CHUNK(LAST_)                                                                        \
   HS_TAP(0, LAST_) HS_TAP(1, LAST_) HS_TAP(2, LAST_) HS_TAP(3, LAST_) HS_TAP(4, LAST_)         \
-  HS_TAP(5, LAST_) HS_TAP(6, LAST_) HS_TAP(7, LAST_) HS_TAP(8, LAST_)
+  HS_TAP(5, LAST_) HS_TAP(6, LAST_) HS_TAP(7, LAST_) HS_TAP(8, LAST_)                          \
+  if (STRIDE == 2) { HS_PROJ(LAST_) }
 
   int buf = 0, pb = 0;
   int cc = cc_begin;
@@ -475,14 +519,18 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     HS_LOAD_W(3 % WS, cc, 3) HS_LOAD_W(4 % WS, cc, 4) HS_LOAD_W(5 % WS, cc, 5)
     HS_LOAD_W(6 % WS, cc, 6) HS_LOAD_W(7 % WS, cc, 7) HS_LOAD_W(8 % WS, cc, 8)
   }
+  if (STRIDE == 2) { HS_LOAD_W2(cc) }
   for (; cc + 1 < cc_end; ++cc) {
     HS_CHUNK(false)
     if (PB == 2) pb ^= 1;
   }
   HS_CHUNK(true)
 #undef HS_CHUNK
+#undef HS_PROJ
 #undef HS_TAP
+#undef HS_TAP_OFF
 #undef HS_LOAD_P
+#undef HS_LOAD_W2
 #undef HS_LOAD_W
 
   // accumulator quad i of group g: channels n_base + 8*i .. +3 of pixel (oy, ox_g)
@@ -509,14 +557,39 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
       }
     }
   }
+  if (has_proj) {
+    // projection output: no residual, no ReLU
+    const int ox = x0 + (r & 7);
+    if (oy < p.hout && ox < p.wout) {
+      const int m = img * p.img_m + oy * p.wout + ox;
+      if (p.use_partial) {
+        float* dst = p.partial2 + ((size_t)split * p.m + m) * p.cout_pad + n_base;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<float4*>(dst + 8 * i) =
+              make_float4(acc2[4 * i], acc2[4 * i + 1], acc2[4 * i + 2], acc2[4 * i + 3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int n = n_base + 8 * i;
+          if (n >= p.cout) continue;
+          half4 o;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[j] = (f16)acc2[4 * i + j];
+          *reinterpret_cast<half4*>(p.out2 + (size_t)m * p.out2_pitch + n) = o;
+        }
+      }
+    }
+  }
 }
 
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
   const dim3 grid(8u * (unsigned)p.tiles_per_xcd);
-  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9>, grid, dim3(256), 0};
-  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9>, grid, dim3(256), 0};
-  if (p.variant == 3) return KernelDesc{(const void*)k_conv3x3_halo<2, 1, 3>, grid, dim3(256), 0};
+  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1>, grid, dim3(256), 0};
+  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1>, grid, dim3(256), 0};
+  if (p.variant == 3) return KernelDesc{(const void*)k_conv3x3_halo<2, 1, 3, 1>, grid, dim3(256), 0};
+  if (p.variant == 4) return KernelDesc{(const void*)k_conv3x3_halo<1, 1, 3, 2>, grid, dim3(256), 0};
   const void* f = p.kc == 16   ? (const void*)k_conv_mfma<16, 4>
                   : p.kc == 32 ? (const void*)k_conv_mfma<32, 4>
                   : p.depth == 8 ? (const void*)k_conv_mfma<64, 8>
@@ -557,6 +630,17 @@ __global__ __launch_bounds__(256) void k_splitk_epilogue(SplitKEpilogueParams p)
 #pragma unroll
     for (int j = 0; j < 4; ++j) o[j] = (f16)v[j];
     *reinterpret_cast<half4*>(p.out + (size_t)m * p.out_pitch + n) = o;
+  }
+  if (p.partial2) {
+    float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sidx = 0; sidx < p.nsplit; ++sidx) {
+      const float4 v2 = *reinterpret_cast<const float4*>(
+          p.partial2 + ((size_t)sidx * p.m + m) * p.cout_pad + n);
+      b.x += v2.x; b.y += v2.y; b.z += v2.z; b.w += v2.w;
+    }
+    half4 o2;
+    o2[0] = (f16)b.x; o2[1] = (f16)b.y; o2[2] = (f16)b.z; o2[3] = (f16)b.w;
+    *reinterpret_cast<half4*>(p.out2 + (size_t)m * p.out2_pitch + n) = o2;
   }
 }
 

@@ -247,7 +247,19 @@ struct Builder {
   // Picks the kernel variant, the tile grid and the split along K.
   static void choose_split(ConvParams& c) {
     const bool halo = c.ntaps == 9 && c.kw == 3 && c.stride == 1 && c.pad == 1 && c.kc == 64;
-    if (halo) {
+    const bool halo2 = c.ntaps == 9 && c.kw == 3 && c.stride == 2 && c.pad == 1 && c.kc == 64;
+    if (halo2) {
+      c.variant = 4;
+      c.tiles_x = (c.wout + 7) / 8;
+      c.tiles_m = c.batch * ((c.hout + 7) / 8) * c.tiles_x;
+      c.tiles_n = c.cout_pad / 64;
+      const int tiles = c.tiles_m * c.tiles_n;
+      const int units = c.chunks_per_tap;
+      int ns = 1;
+      if (tiles < 192) ns = std::max(1, std::min((256 + tiles - 1) / tiles, units));
+      c.chunks_per_split = (units + ns - 1) / ns;
+      c.nsplit = (units + c.chunks_per_split - 1) / c.chunks_per_split;
+    } else if (halo) {
       // spatial tiles of 8 x 16 pixels when that still yields enough workgroups, else 8 x 8;
       // grids of more than two workgroups per CU take the leaner 8 x 16 kernel (three per CU)
       const int ty = (c.hout + 7) / 8;
@@ -281,8 +293,11 @@ struct Builder {
   // Appends the convolution and, when it is split along K, its reduction kernel.
   // keep_partial: leave the partial sums in the scratch buffer for a later kernel (ConvLSTM).
   // Returns the index of the convolution op.
+  // w2_off / out2: packed weights and output of a 1x1 stride-2 projection fused into a 3x3
+  // stride-2 layer (out2 == NULL: none).
   int add_conv(ConvParams c, size_t w_off, const Tensor* res, const Tensor* out, bool relu,
-               bool want_f32, bool keep_partial, double flops) {
+               bool want_f32, bool keep_partial, double flops, size_t w2_off = 0,
+               const Tensor* out2 = nullptr) {
     Op op;
     op.fam = F_CONV;
     op.flops = flops;
@@ -293,8 +308,15 @@ struct Builder {
     c.partial = nullptr;   // patched when the scratch buffer is carved
     c.out = nullptr; c.out_pitch = 0; c.res = nullptr; c.res_pitch = 0; c.relu = 0;
     c.out_f32 = nullptr;
+    c.wt2 = nullptr; c.out2 = nullptr; c.out2_pitch = 0; c.partial2 = nullptr;
+    const bool fused = out2 != nullptr && c.variant == 4;
+    if (fused) {
+      c.wt2 = d_w ? d_w + w2_off : nullptr;
+      if (!partial) { c.out2 = out2->p; c.out2_pitch = out2->pitch; }
+    }
     if (partial) {
-      partial_floats = std::max(partial_floats, (size_t)c.nsplit * c.m * c.cout_pad);
+      partial_floats =
+          std::max(partial_floats, (size_t)(fused ? 2 : 1) * c.nsplit * c.m * c.cout_pad);
     } else {
       if (out) { c.out = out->p; c.out_pitch = out->pitch; }
       if (res) { c.res = res->p; c.res_pitch = res->pitch; }
@@ -316,6 +338,11 @@ struct Builder {
       s.relu = relu ? 1 : 0;
       s.out_f32 = nullptr;
       s.img_m = c.img_m;
+      s.partial2 = nullptr; s.out2 = nullptr; s.out2_pitch = 0;
+      if (fused) {
+        s.out2 = out2->p; s.out2_pitch = out2->pitch;   // partial2 patched with the scratch
+        e.bytes *= 2.0;
+      }
       ops.push_back(e);
       if (want_f32) logits_op = (int)ops.size() - 1;
     }
@@ -324,8 +351,11 @@ struct Builder {
 
   // Generic convolution on a pixel-major tensor; weights are the next cout*cin*k*k floats of the
   // blob starting at blob_at. Fills out->h/w/c.
+  // proj_at / proj_out: blob offset and output of the block's 1x1 stride-2 projection, fused into
+  // this 3x3 stride-2 layer when the layer qualifies (returns through *proj_fused whether it was).
   int conv_layer(const Tensor& in, size_t blob_at, int cout, int k, int stride, int pad, bool relu,
-                 const Tensor* res, Tensor* out, bool want_f32, bool keep_partial) {
+                 const Tensor* res, Tensor* out, bool want_f32, bool keep_partial,
+                 size_t proj_at = 0, Tensor* proj_out = nullptr, bool* proj_fused = nullptr) {
     const int cin = in.c;
     ConvParams g;
     std::memset(&g, 0, sizeof(g));
@@ -340,8 +370,16 @@ struct Builder {
     const size_t w_off = reserve_w((size_t)g.cout_pad * g.ktot);
     if (pack) pack_generic(blob + blob_at, cout, cin, k, g.cout_pad, host_w.data() + w_off);
     out->h = g.hout; out->w = g.wout; out->c = cout;
+    const bool fuse = proj_out && k == 3 && stride == 2 && pad == 1 && g.kc == 64;
+    if (proj_fused) *proj_fused = fuse;
+    if (!fuse)
+      return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
+                      2.0 * g.m * (double)cout * cin * k * k);
+    const size_t w2_off = reserve_w((size_t)g.cout_pad * cin);
+    if (pack) pack_generic(blob + proj_at, cout, cin, 1, g.cout_pad, host_w.data() + w2_off);
+    proj_out->h = g.hout; proj_out->w = g.wout; proj_out->c = cout;
     return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
-                    2.0 * g.m * (double)cout * cin * k * k);
+                    2.0 * g.m * (double)cout * cin * (k * k + 1), w2_off, proj_out);
   }
 
   // First layer: 3 input channels on the padded 4-channel image, k x k, stride 2, ReLU.
@@ -434,12 +472,16 @@ struct Builder {
                      at_p = at_b + (size_t)width * width * 9;
         at = at_p + (proj ? (size_t)width * bc_in : 0);
         t.pitch = width;
-        conv_layer(a, at_a, width, 3, proj ? 2 : 1, 1, true, nullptr, &t, false, false);
         const Tensor* shortcut = &a;
         if (proj) {
+          // the projection reads the centre-tap pixels of conv a: one kernel computes both
           sc.pitch = width;
-          conv_layer(a, at_p, width, 1, 2, 0, false, nullptr, &sc, false, false);
+          bool fused = false;
+          conv_layer(a, at_a, width, 3, 2, 1, true, nullptr, &t, false, false, at_p, &sc, &fused);
+          if (!fused) conv_layer(a, at_p, width, 1, 2, 0, false, nullptr, &sc, false, false);
           shortcut = &sc;
+        } else {
+          conv_layer(a, at_a, width, 3, 1, 1, true, nullptr, &t, false, false);
         }
         const bool last = s == 3 && blk == 1;
         if (last) { o.p = concat; o.pitch = 768; } else { o.pitch = width; }
@@ -563,8 +605,15 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   b.walk(ph, pw);
   float* d_partial = b.carve.take<float>(b.partial_floats);
   for (Op& op : b.ops) {
-    if (op.fam == F_CONV && op.conv.use_partial) op.conv.partial = d_partial;
-    if (op.fam == F_SPLITK) op.splitk.partial = d_partial;
+    if (op.fam == F_CONV && op.conv.use_partial) {
+      op.conv.partial = d_partial;
+      if (op.conv.wt2) op.conv.partial2 = d_partial + (size_t)op.conv.nsplit * op.conv.m * op.conv.cout_pad;
+    }
+    if (op.fam == F_SPLITK) {
+      op.splitk.partial = d_partial;
+      if (op.splitk.out2)
+        op.splitk.partial2 = d_partial + (size_t)op.splitk.nsplit * op.splitk.m * op.splitk.cout_pad;
+    }
     if (op.fam == F_LSTM) op.lstm.partial = d_partial;
   }
   float* d_lut32 = b.carve.take<float>(256);
