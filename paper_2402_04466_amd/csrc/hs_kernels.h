@@ -69,7 +69,9 @@ struct ConvParams {
   // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)
   int nsplit, chunks_per_split;
   int tiles_m, tiles_n; // 64x64 output tiles; the grid is 8 * tiles_per_xcd workgroups
-  int tiles_per_xcd;    // ceil(tiles_m * tiles_n * nsplit / 8)
+  int tiles_per_wg;     // variant 1..4: consecutive spatial tiles one workgroup walks (>= 1);
+                        // workgroups = ceil(tiles_m / tiles_per_wg) * tiles_n * nsplit
+  int tiles_per_xcd;    // ceil(workgroups / 8)
   int use_partial;      // 1: store fp32 partial sums for a reduction kernel, no epilogue here
   float* partial;       // [nsplit][m][cout_pad] fp32
   // fused epilogue (use_partial == 0)

@@ -355,8 +355,8 @@ __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
 // Wavefront (wm, wn): pixel rows 4*wm .. 4*wm+3 (MT groups of 4 x 8 pixels), channels
 // 32*wn .. +31.  chunks_per_split / nchunks count Cin chunks here (split-K over Cin).
 // =============================================================================================
-template <int MT, int PB, int WS, int STRIDE>
-__global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
+template <int MT, int PB, int WS, int STRIDE, bool PERSIST, int OCC>
+__global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
   constexpr int KC = 64, TH = 8, TW = 8 * MT;
   constexpr int IPH = STRIDE * TH + 3 - STRIDE, IPW = STRIDE * TW + 3 - STRIDE;   // input patch
   constexpr int NPL = STRIDE * STRIDE;                 // parity planes the patch is stored as
@@ -381,14 +381,17 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
   const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
-  if (tile >= p.tiles_m * p.tiles_n * p.nsplit) return;
-  const int tile_m = tile % p.tiles_m;
-  const int tile_n = (tile / p.tiles_m) % p.tiles_n;
-  const int split = tile / (p.tiles_m * p.tiles_n);
+  // A workgroup owns tiles_per_wg consecutive spatial tiles of one channel tile (and K split)
+  // and walks them in one software pipeline: the next tile's patch is prefetched during the
+  // last chunk of the current one, so the cold start is paid once per workgroup.
+  const int groups_m = (p.tiles_m + p.tiles_per_wg - 1) / p.tiles_per_wg;
+  if (tile >= groups_m * p.tiles_n * p.nsplit) return;
+  const int tm_begin = (tile % groups_m) * p.tiles_per_wg;
+  const int tm_end = PERSIST ? min(p.tiles_m, tm_begin + p.tiles_per_wg) : tm_begin + 1;
+  const int tile_n = (tile / groups_m) % p.tiles_n;
+  const int split = tile / (groups_m * p.tiles_n);
   const int tiles_img = p.tiles_m / p.batch;            // spatial tiles per image
-  const int img = tile_m / tiles_img, tile_s = tile_m - img * tiles_img;
-  const int ty = tile_s / p.tiles_x, tx = tile_s - ty * p.tiles_x;
-  const int y0 = ty * TH, x0 = tx * TW, n0 = tile_n * BN;
+  const int n0 = tile_n * BN;
   const int cc_begin = split * p.chunks_per_split;
   const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
   const bool has_proj = STRIDE == 2 && p.wt2 != nullptr;
@@ -404,33 +407,46 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     l_w2base[i] = has_proj ? p.wt2 + (size_t)(n0 + row) * (p.chunks_per_tap * KC) + kv * 8 : p.wt;
     l_wlds[i] = row * PITCH + kv * 8;
   }
-  const f16* l_pbase[PL];
-  int l_plds[PL];
-  bool l_pact[PL], l_pinb[PL];
+  // patch loader: the LDS slot of every vector is fixed, its source depends on the tile.
+  // l_pyx packs the vector's pixel inside the patch; a source is kept as an offset in halves
+  // from p.in (below 2^31 by construction of the plan), negative when the pixel is padding.
+  int l_plds[PL], l_pyx[PL];
 #pragma unroll
   for (int i = 0; i < PL; ++i) {
     const int v = tid + 256 * i;
     const int pix = min(v >> 3, NPIX - 1), kv = v & 7;
     const int py = pix / IPW, px = pix - py * IPW;
-    const int iy = STRIDE * y0 + py - 1, ix = STRIDE * x0 + px - 1;
-    l_pact[i] = v < PV;
-    l_pinb[i] = l_pact[i] && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
-    l_pbase[i] = l_pinb[i] ? p.in + (((long)img * p.hin + iy) * p.win + ix) * p.cin_pitch + kv * 8
-                           : p.in;
+    l_pyx[i] = py | (px << 8);
     // stride 2: pixel (py, px) goes to parity plane (py & 1, px & 1) at (py / 2, px / 2), so
-    // that the lanes of a tap read neighbouring plane pixels, as for stride 1
-    l_plds[i] = STRIDE == 1 ? py * RP + px * PITCH + kv * 8
-                            : (((py & 1) * 2 + (px & 1)) * PLH + (py >> 1)) * RP +
-                                  (px >> 1) * PITCH + kv * 8;
+    // that the lanes of a tap read neighbouring plane pixels, as for stride 1.  -1: no such vector
+    l_plds[i] = v >= PV ? -1
+                : STRIDE == 1 ? py * RP + px * PITCH + kv * 8
+                              : (((py & 1) * 2 + (px & 1)) * PLH + (py >> 1)) * RP +
+                                    (px >> 1) * PITCH + kv * 8;
   }
+  // source offsets of spatial tile TM_ (also its image and origin)
+#define HS_TILE_SETUP(TM_, POFF_, IMG_, Y0_, X0_)                                              \
+  {                                                                                            \
+    IMG_ = (TM_) / tiles_img;                                                                  \
+    const int ts_ = (TM_) - IMG_ * tiles_img;                                                  \
+    const int ty_ = ts_ / p.tiles_x;                                                           \
+    Y0_ = ty_ * TH;                                                                            \
+    X0_ = (ts_ - ty_ * p.tiles_x) * TW;                                                        \
+    _Pragma("unroll") for (int i = 0; i < PL; ++i) {                                           \
+      const int iy_ = STRIDE * Y0_ + (l_pyx[i] & 0xff) - 1;                                    \
+      const int ix_ = STRIDE * X0_ + (l_pyx[i] >> 8) - 1;                                      \
+      const bool inb_ = l_plds[i] >= 0 && iy_ >= 0 && iy_ < p.hin && ix_ >= 0 && ix_ < p.win;  \
+      POFF_[i] = inb_ ? ((IMG_ * p.hin + iy_) * p.win + ix_) * p.cin_pitch + (tid & 7) * 8 : -1; \
+    }                                                                                          \
+  }
+  int l_poff[PL], l_poff_n[PL];
+  int img, y0, x0, img_n, y0_n, x0_n;
+  HS_TILE_SETUP(tm_begin, l_poff, img, y0, x0)
 
-  floatx16 acc[MT], acc2;
+  const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  floatx16 acc[MT], acc2 = zero16;
 #pragma unroll
-  for (int g = 0; g < MT; ++g)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) acc2[i] = 0.0f;
+  for (int g = 0; g < MT; ++g) acc[g] = zero16;
 
   const int wm = wave & 1, wn = wave >> 1;
   // fragment bases: weights row (32*wn + r); pixel (4*wm + r/8, r%8) of column group g
@@ -449,17 +465,18 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
 #define HS_LOAD_W2(CC_)                                                                        \
   _Pragma("unroll") for (int i = 0; i < WL; ++i)                                               \
     st_w2[i] = *reinterpret_cast<const u32x4*>(l_w2base[i] + (long)(CC_) * KC);
-#define HS_LOAD_P(I_, CC_)                                                                     \
-  st_p[I_] = *reinterpret_cast<const u32x4*>(l_pinb[I_] ? l_pbase[I_] + (long)(CC_) * KC : p.in);
+#define HS_LOAD_P(I_, CC_, POFF_)                                                              \
+  st_p[I_] = *reinterpret_cast<const u32x4*>(p.in + (POFF_[I_] >= 0 ? POFF_[I_] + (CC_) * KC : 0));
   // offset of tap (ky, kx) inside the patch, relative to the wavefront's first pixel
 #define HS_TAP_OFF(KY_, KX_)                                                                   \
   (STRIDE == 1 ? (KY_) * RP + (KX_) * PITCH                                                    \
                : ((((KY_) & 1) * 2 + ((KX_) & 1)) * PLH + ((KY_) >> 1)) * RP + ((KX_) >> 1) * PITCH)
 
-  // One tap of chunk cc.  TAP_ and LAST_ are literals: every register index and every
-  // refill decision is resolved at compile time.  Weight stage TAP_ % WS is handed to LDS and
-  // refilled with the weights of the step WS taps ahead.
-#define HS_TAP(TAP_, LAST_)                                                                    \
+  // One tap of chunk cc of the current tile.  TAP_ and LAST_ are literals: every register index
+  // and every refill decision is resolved at compile time.  Weight stage TAP_ % WS is handed to
+  // LDS and refilled with the weights of the step WS taps ahead; CCN_, PBASE_N_, PINB_N_ name
+  // the item after this chunk (next chunk of this tile, or first chunk of the next tile).
+#define HS_TAP(TAP_, LAST_, CCN_, POFF_N_)                                                     \
   {                                                                                            \
     _Pragma("unroll") for (int i = 0; i < WL; ++i)                                             \
       *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[i]]) = st_w[(TAP_) % WS][i];                  \
@@ -467,15 +484,15 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
       if (PB == 1) __syncthreads(); /* every wave is done with the previous chunk's patch */   \
       const u32x4 zero_ = {0u, 0u, 0u, 0u};                                                    \
       _Pragma("unroll") for (int i = 0; i < PL; ++i)                                           \
-        if (l_pact[i])                                                                         \
-          *reinterpret_cast<u32x4*>(&s_patch[pb][l_plds[i]]) = l_pinb[i] ? st_p[i] : zero_;    \
+        if (l_plds[i] >= 0)                                                                    \
+          *reinterpret_cast<u32x4*>(&s_patch[pb][l_plds[i]]) = l_poff[i] >= 0 ? st_p[i] : zero_; \
     }                                                                                          \
     __syncthreads();                                                                           \
     if (!(LAST_) || (TAP_) + WS < 9)                                                           \
-      HS_LOAD_W((TAP_) % WS, cc + ((TAP_) + WS) / 9, ((TAP_) + WS) % 9)                        \
+      HS_LOAD_W((TAP_) % WS, ((TAP_) + WS >= 9 ? (CCN_) : cc), ((TAP_) + WS) % 9)              \
     if (!(LAST_)) {                                                                            \
       _Pragma("unroll") for (int i = PT * (TAP_); i < PT * (TAP_) + PT; ++i)                   \
-        if (i < PL) { HS_LOAD_P(i < PL ? i : 0, cc + 1) }                                      \
+        if (i < PL) { HS_LOAD_P(i < PL ? i : 0, CCN_, POFF_N_) }                               \
     }                                                                                          \
     const f16* fw_ = &s_w[buf][fw_off];                                                        \
     const f16* fp_ = &s_patch[pb][fp_off + HS_TAP_OFF((TAP_) / 3, (TAP_) % 3)];                \
@@ -490,12 +507,12 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
   }
   // Tenth step of a stride-2 chunk: the 1x1 stride-2 projection of the same input reads exactly
   // the centre tap's pixels, so it rides along with its own weights and accumulator.
-#define HS_PROJ(LAST_)                                                                         \
+#define HS_PROJ(LAST_, CCN_)                                                                   \
   if (has_proj) {                                                                              \
     _Pragma("unroll") for (int i = 0; i < WL; ++i)                                             \
       *reinterpret_cast<u32x4*>(&s_w[buf][l_wlds[i]]) = st_w2[i];                              \
     __syncthreads();                                                                           \
-    if (!(LAST_)) { HS_LOAD_W2(cc + 1) }                                                       \
+    if (!(LAST_)) { HS_LOAD_W2(CCN_) }                                                         \
     const f16* fw_ = &s_w[buf][fw_off];                                                        \
     const f16* fp_ = &s_patch[pb][fp_off + HS_TAP_OFF(1, 1)];                                  \
     _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                   \
@@ -505,26 +522,99 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
     }                                                                                          \
     buf ^= 1;                                                                                  \
   }
-#define HS_CHUNK(LAST_)                                                                        \
-  HS_TAP(0, LAST_) HS_TAP(1, LAST_) HS_TAP(2, LAST_) HS_TAP(3, LAST_) HS_TAP(4, LAST_)         \
-  HS_TAP(5, LAST_) HS_TAP(6, LAST_) HS_TAP(7, LAST_) HS_TAP(8, LAST_)                          \
-  if (STRIDE == 2) { HS_PROJ(LAST_) }
+#define HS_CHUNK(LAST_, CCN_, PO_N_)                                                           \
+  HS_TAP(0, LAST_, CCN_, PO_N_) HS_TAP(1, LAST_, CCN_, PO_N_) HS_TAP(2, LAST_, CCN_, PO_N_)    \
+  HS_TAP(3, LAST_, CCN_, PO_N_) HS_TAP(4, LAST_, CCN_, PO_N_) HS_TAP(5, LAST_, CCN_, PO_N_)    \
+  HS_TAP(6, LAST_, CCN_, PO_N_) HS_TAP(7, LAST_, CCN_, PO_N_) HS_TAP(8, LAST_, CCN_, PO_N_)    \
+  if (STRIDE == 2) { HS_PROJ(LAST_, CCN_) }
+
+  const int wm_rows = 4 * wm + (r >> 3);
+  const int n_base = n0 + wn * 32 + h * 4;
+  // Stores the finished tile (image img, origin y0, x0) and clears the accumulators.
+  // Accumulator quad i of group g: channels n_base + 8*i .. +3 of pixel (oy, ox_g).
+#define HS_STORE_TILE()                                                                        \
+  {                                                                                            \
+    const int oy = y0 + wm_rows;                                                               \
+    _Pragma("unroll") for (int g = 0; g < MT; ++g) {                                           \
+      const int ox = x0 + 8 * g + (r & 7);                                                     \
+      if (oy < p.hout && ox < p.wout) {                                                        \
+        const int m = img * p.img_m + oy * p.wout + ox;                                        \
+        if (p.use_partial) {                                                                   \
+          float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;            \
+          _Pragma("unroll") for (int i = 0; i < 4; ++i)                                        \
+            *reinterpret_cast<float4*>(dst + 8 * i) = make_float4(                             \
+                acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]);       \
+        } else {                                                                               \
+          _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
+            const int n = n_base + 8 * i;                                                      \
+            if (n < p.cout) {                                                                  \
+              float v[4] = {acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2],               \
+                            acc[g][4 * i + 3]};                                                \
+              store_quad(p, m, n, v);                                                          \
+            }                                                                                  \
+          }                                                                                    \
+        }                                                                                      \
+      }                                                                                        \
+      acc[g] = zero16;                                                                         \
+    }                                                                                          \
+    if (has_proj) { /* projection output: no residual, no ReLU */                              \
+      const int ox = x0 + (r & 7);                                                             \
+      if (oy < p.hout && ox < p.wout) {                                                        \
+        const int m = img * p.img_m + oy * p.wout + ox;                                        \
+        if (p.use_partial) {                                                                   \
+          float* dst = p.partial2 + ((size_t)split * p.m + m) * p.cout_pad + n_base;           \
+          _Pragma("unroll") for (int i = 0; i < 4; ++i)                                        \
+            *reinterpret_cast<float4*>(dst + 8 * i) = make_float4(                             \
+                acc2[4 * i], acc2[4 * i + 1], acc2[4 * i + 2], acc2[4 * i + 3]);               \
+        } else {                                                                               \
+          _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
+            const int n = n_base + 8 * i;                                                      \
+            if (n < p.cout) {                                                                  \
+              half4 o;                                                                         \
+              _Pragma("unroll") for (int j = 0; j < 4; ++j) o[j] = (f16)acc2[4 * i + j];       \
+              *reinterpret_cast<half4*>(p.out2 + (size_t)m * p.out2_pitch + n) = o;            \
+            }                                                                                  \
+          }                                                                                    \
+        }                                                                                      \
+      }                                                                                        \
+      acc2 = zero16;                                                                           \
+    }                                                                                          \
+  }
 
   int buf = 0, pb = 0;
   int cc = cc_begin;
 #pragma unroll
-  for (int i = 0; i < PL; ++i) HS_LOAD_P(i, cc)
+  for (int i = 0; i < PL; ++i) HS_LOAD_P(i, cc, l_poff)
   HS_LOAD_W(0, cc, 0) HS_LOAD_W(1, cc, 1) HS_LOAD_W(2, cc, 2)
   if (WS == 9) {
     HS_LOAD_W(3 % WS, cc, 3) HS_LOAD_W(4 % WS, cc, 4) HS_LOAD_W(5 % WS, cc, 5)
     HS_LOAD_W(6 % WS, cc, 6) HS_LOAD_W(7 % WS, cc, 7) HS_LOAD_W(8 % WS, cc, 8)
   }
   if (STRIDE == 2) { HS_LOAD_W2(cc) }
-  for (; cc + 1 < cc_end; ++cc) {
-    HS_CHUNK(false)
+  // Items = (tile, chunk) pairs in order; `_n` state describes the item after the current one.
+  const int n_items = (tm_end - tm_begin) * (cc_end - cc_begin);
+  int tm = tm_begin;
+#pragma unroll
+  for (int i = 0; i < PL; ++i) l_poff_n[i] = l_poff[i];
+  img_n = img; y0_n = y0; x0_n = x0;
+  for (int item = 0; item + 1 < n_items; ++item) {
+    const bool cross = PERSIST && cc + 1 == cc_end;    // the next item starts a new tile
+    const int cc_nx = cross ? cc_begin : cc + 1;
+    if (cross) { HS_TILE_SETUP(tm + 1, l_poff_n, img_n, y0_n, x0_n) }
+    HS_CHUNK(false, cc_nx, l_poff_n)
     if (PB == 2) pb ^= 1;
+    if (cross) {
+      HS_STORE_TILE()
+#pragma unroll
+      for (int i = 0; i < PL; ++i) l_poff[i] = l_poff_n[i];
+      img = img_n; y0 = y0_n; x0 = x0_n;
+      ++tm;
+    }
+    cc = cc_nx;
   }
-  HS_CHUNK(true)
+  HS_CHUNK(true, cc, l_poff)
+  HS_STORE_TILE()
+#undef HS_STORE_TILE
 #undef HS_CHUNK
 #undef HS_PROJ
 #undef HS_TAP
@@ -532,64 +622,22 @@ __global__ __launch_bounds__(256) void k_conv3x3_halo(ConvParams p) {
 #undef HS_LOAD_P
 #undef HS_LOAD_W2
 #undef HS_LOAD_W
-
-  // accumulator quad i of group g: channels n_base + 8*i .. +3 of pixel (oy, ox_g)
-  const int oy = y0 + 4 * wm + (r >> 3);
-  const int n_base = n0 + wn * 32 + h * 4;
-#pragma unroll
-  for (int g = 0; g < MT; ++g) {
-    const int ox = x0 + 8 * g + (r & 7);
-    if (oy >= p.hout || ox >= p.wout) continue;
-    const int m = img * p.img_m + oy * p.wout + ox;
-    if (p.use_partial) {
-      float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<float4*>(dst + 8 * i) = make_float4(
-            acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int n = n_base + 8 * i;
-        if (n >= p.cout) continue;
-        float v[4] = {acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]};
-        store_quad(p, m, n, v);
-      }
-    }
-  }
-  if (has_proj) {
-    // projection output: no residual, no ReLU
-    const int ox = x0 + (r & 7);
-    if (oy < p.hout && ox < p.wout) {
-      const int m = img * p.img_m + oy * p.wout + ox;
-      if (p.use_partial) {
-        float* dst = p.partial2 + ((size_t)split * p.m + m) * p.cout_pad + n_base;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          *reinterpret_cast<float4*>(dst + 8 * i) =
-              make_float4(acc2[4 * i], acc2[4 * i + 1], acc2[4 * i + 2], acc2[4 * i + 3]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int n = n_base + 8 * i;
-          if (n >= p.cout) continue;
-          half4 o;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) o[j] = (f16)acc2[4 * i + j];
-          *reinterpret_cast<half4*>(p.out2 + (size_t)m * p.out2_pitch + n) = o;
-        }
-      }
-    }
-  }
+#undef HS_TILE_SETUP
 }
 
+constexpr int OCC3 = 2, OCC4 = 2;   // waves per SIMD the tile-walking instantiations are built for
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
   const dim3 grid(8u * (unsigned)p.tiles_per_xcd);
-  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1>, grid, dim3(256), 0};
-  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1>, grid, dim3(256), 0};
-  if (p.variant == 3) return KernelDesc{(const void*)k_conv3x3_halo<2, 1, 3, 1>, grid, dim3(256), 0};
-  if (p.variant == 4) return KernelDesc{(const void*)k_conv3x3_halo<1, 1, 3, 2>, grid, dim3(256), 0};
+  const bool walk = p.tiles_per_wg > 1;
+  if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1, false, 1>, grid, dim3(256), 0};
+  if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1, false, 1>, grid, dim3(256), 0};
+  if (p.variant == 3)
+    return KernelDesc{walk ? (const void*)k_conv3x3_halo<2, 1, 3, 1, true, OCC3>
+                           : (const void*)k_conv3x3_halo<2, 1, 3, 1, false, 1>, grid, dim3(256), 0};
+  if (p.variant == 4)
+    return KernelDesc{walk ? (const void*)k_conv3x3_halo<1, 1, 3, 2, true, OCC4>
+                           : (const void*)k_conv3x3_halo<1, 1, 3, 2, false, 1>, grid, dim3(256), 0};
   const void* f = p.kc == 16   ? (const void*)k_conv_mfma<16, 4>
                   : p.kc == 32 ? (const void*)k_conv_mfma<32, 4>
                   : p.depth == 8 ? (const void*)k_conv_mfma<64, 8>

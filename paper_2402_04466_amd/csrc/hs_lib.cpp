@@ -246,8 +246,10 @@ struct Builder {
 
   // Picks the kernel variant, the tile grid and the split along K.
   static void choose_split(ConvParams& c) {
-    const bool halo = c.ntaps == 9 && c.kw == 3 && c.stride == 1 && c.pad == 1 && c.kc == 64;
-    const bool halo2 = c.ntaps == 9 && c.kw == 3 && c.stride == 2 && c.pad == 1 && c.kc == 64;
+    // the shared-patch kernels address the input with 32-bit offsets (in halves)
+    const bool fits32 = (double)c.batch * c.hin * c.win * c.cin_pitch < 2147483648.0;
+    const bool halo = c.ntaps == 9 && c.kw == 3 && c.stride == 1 && c.pad == 1 && c.kc == 64 && fits32;
+    const bool halo2 = c.ntaps == 9 && c.kw == 3 && c.stride == 2 && c.pad == 1 && c.kc == 64 && fits32;
     if (halo2) {
       c.variant = 4;
       c.tiles_x = (c.wout + 7) / 8;
@@ -287,7 +289,15 @@ struct Builder {
       c.nsplit = (c.nchunks + c.chunks_per_split - 1) / c.chunks_per_split;
     }
     c.depth = (c.kc == 64 && c.chunks_per_split >= 12) ? 8 : 4;
-    c.tiles_per_xcd = (c.tiles_m * c.tiles_n * c.nsplit + 7) / 8;
+    // grids several times what the device holds at once (768 workgroups): each workgroup walks
+    // consecutive spatial tiles, sized so that the whole grid is resident at two per CU
+    c.tiles_per_wg = 1;
+    if (c.variant == 3 || c.variant == 4) {
+      const int wgs = c.tiles_m * c.tiles_n * c.nsplit;
+      if (wgs > 1536) c.tiles_per_wg = (wgs + 511) / 512;
+    }
+    const int groups_m = (c.tiles_m + c.tiles_per_wg - 1) / c.tiles_per_wg;
+    c.tiles_per_xcd = (groups_m * c.tiles_n * c.nsplit + 7) / 8;
   }
 
   // Appends the convolution and, when it is split along K, its reduction kernel.
@@ -370,7 +380,8 @@ struct Builder {
     const size_t w_off = reserve_w((size_t)g.cout_pad * g.ktot);
     if (pack) pack_generic(blob + blob_at, cout, cin, k, g.cout_pad, host_w.data() + w_off);
     out->h = g.hout; out->w = g.wout; out->c = cout;
-    const bool fuse = proj_out && k == 3 && stride == 2 && pad == 1 && g.kc == 64;
+    const bool fuse = proj_out && k == 3 && stride == 2 && pad == 1 && g.kc == 64 &&
+                      (double)g.batch * g.hin * g.win * g.cin_pitch < 2147483648.0;
     if (proj_fused) *proj_fused = fuse;
     if (!fuse)
       return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
