@@ -21,10 +21,11 @@ from .convnet import (conv2d, maxpool2d, relu, sigmoid, Tiny4Net, ResNet18ConvLS
                       convlstm_step, split_blob, basic_block)
 from .postprocess import postprocess, logit_threshold
 from .overlay import overlay, alpha_q8
+from .annotate import annotate, anchor
 from .metrics import determinism_metrics, trim_count
 from .pipeline import OracleApp
 
 __all__ = ["resize_bilinear_u8", "normalize_lut", "preprocess", "conv2d", "maxpool2d",
            "relu", "sigmoid", "Tiny4Net", "ResNet18ConvLSTMNet", "convlstm_step",
-           "split_blob", "basic_block", "postprocess", "logit_threshold", "overlay", "alpha_q8",
+           "split_blob", "basic_block", "postprocess", "logit_threshold", "overlay", "alpha_q8", "annotate", "anchor",
            "determinism_metrics", "trim_count", "OracleApp"]

@@ -9,17 +9,22 @@ from .resize import preprocess
 from .convnet import Tiny4Net, ResNet18ConvLSTMNet
 from .postprocess import postprocess
 from .overlay import overlay
+from .annotate import annotate
 
 
 class OracleApp:
     def __init__(self, net: str, blob: np.ndarray, net_w: int, net_h: int, fp16_input: bool,
                  palette: np.ndarray, mean: float = 0.5, std: float = 0.25,
-                 threshold: float = 0.5, alpha: float = 0.5, storage: str = "fp32"):
+                 threshold: float = 0.5, alpha: float = 0.5, storage: str = "fp32",
+                 glyphs=None, marker_arm: int = 12, marker_half: int = 1, glyph_scale: int = 2):
         self.net = {"tiny4": Tiny4Net, "resnet18_convlstm": ResNet18ConvLSTMNet}[net](
             blob, storage)
         self.net_w, self.net_h, self.fp16_input = net_w, net_h, fp16_input
         self.mean, self.std, self.threshold, self.alpha = mean, std, threshold, alpha
         self.palette = np.asarray(palette, dtype=np.uint8)
+        # annotation layer (markers + labels) only when a glyph table is given
+        self.glyphs = None if glyphs is None else np.asarray(glyphs, dtype=np.uint8)
+        self.marker = (marker_arm, marker_half, glyph_scale)
 
     def reset(self):
         self.net.reset()
@@ -30,6 +35,9 @@ class OracleApp:
         logits = self.net.forward(net_in)
         post = postprocess(logits, self.threshold)
         out = overlay(frame, post["mask"], self.palette, self.alpha)
+        if self.glyphs is not None:
+            out = annotate(out, post["argmax_idx"], post["present"], logits.shape[2],
+                           logits.shape[1], self.palette, self.glyphs, *self.marker)
         res = {"resized": resized, "net_input": net_in, "logits": logits, "overlay": out}
         res.update(post)
         if hasattr(self.net, "h") and self.net.h is not None:

@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
+import oracle
 from oracle import (postprocess, logit_threshold, overlay, alpha_q8, determinism_metrics,
                     trim_count, OracleApp)
 
@@ -189,3 +190,82 @@ def test_pipeline_stage_order_and_shapes():
     untouched = ~r["mask"].any(axis=0)[cell_y][:, cell_x]
     assert np.array_equal(r["overlay"][untouched], frames[0][untouched])
     assert (r["overlay"][~untouched] != frames[0][~untouched]).any()
+
+
+# ---- annotation layer (markers + labels): Section III-A, "segmented tools and their text labels" --
+def _annotate_witness(img, argmax_idx, present, wm, hm, palette, glyphs, arm, half, scale, pad=64):
+    """Independent construction: whole-array masks (|dx|, |dy| tests by broadcasting, glyphs by
+    np.kron) on a canvas padded by `pad` on every side, cropped at the end (clipping for free)."""
+    hf, wf, _ = img.shape
+    canvas = np.zeros((hf + 2 * pad, wf + 2 * pad, 3), np.uint8)
+    canvas[pad:pad + hf, pad:pad + wf] = img
+    ys = np.arange(-pad, hf + pad)[:, None]
+    xs = np.arange(-pad, wf + pad)[None, :]
+    for k in range(8):
+        if not present[k]:
+            continue
+        ay, ax = divmod(int(argmax_idx[k]), wm)
+        cx = int(np.floor((ax + 0.5) * wf / wm + 1e-9))
+        cy = int(np.floor((ay + 0.5) * hf / hm + 1e-9))
+        dx, dy = np.abs(xs - cx), np.abs(ys - cy)
+        cross = ((dx <= arm) & (dy <= half)) | ((dy <= arm) & (dx <= half))
+        canvas[cross] = palette[k]
+        for gi, g in enumerate((0, 1 + k)):
+            bits = np.array([[(int(glyphs[g, r]) >> (4 - c)) & 1 for c in range(5)] for r in range(7)])
+            big = np.kron(bits, np.ones((scale, scale), dtype=int)).astype(bool)
+            oy = cy - 7 * scale - 2 + pad
+            ox = cx + arm + 2 + gi * 6 * scale + pad
+            region = canvas[oy:oy + 7 * scale, ox:ox + 5 * scale]
+            region[big] = palette[k]
+    return canvas[pad:pad + hf, pad:pad + wf]
+
+
+def test_annotate_nothing_present_is_identity():
+    rng = np.random.default_rng(0)
+    img = rng.integers(0, 256, (40, 60, 3), dtype=np.uint8)
+    out = oracle.annotate(img, [3] * 8, [0] * 8, 6, 4, si.DEFAULT_PALETTE, si.DEFAULT_GLYPHS)
+    assert np.array_equal(out, img)
+
+
+def test_annotate_anchor_closed_form_and_cross_pixel_count():
+    # frame an integer multiple s of the map: anchor = cell origin + s // 2
+    assert oracle.anchor(2 * 27 + 5, 27, 15, 27 * 70, 15 * 70) == (5 * 70 + 35, 2 * 70 + 35)
+    assert oracle.anchor(0, 27, 15, 1920, 1080) == (1920 // 54, 1080 // 30)
+    img = np.zeros((200, 200, 3), np.uint8)
+    no_glyphs = np.zeros((9, 7), np.uint8)
+    for arm, half in ((12, 1), (5, 0), (20, 3)):
+        out = oracle.annotate(img, [55] + [0] * 7, [1] + [0] * 7, 10, 10, si.DEFAULT_PALETTE,
+                              no_glyphs, arm, half, 2)
+        painted = int((out != 0).any(axis=2).sum())
+        assert painted == 2 * (2 * arm + 1) * (2 * half + 1) - (2 * half + 1) ** 2
+        assert (out[(out != 0).any(axis=2)] == si.DEFAULT_PALETTE[0]).all()
+
+
+@pytest.mark.parametrize("wf,hf,wm,hm,scale,arm,half", [
+    (320, 240, 32, 32, 2, 12, 1),      # config-1 geometry
+    (1920, 1080, 27, 15, 2, 12, 1),    # config-2 geometry
+    (97, 61, 5, 3, 3, 7, 2),           # odd sizes, everything near the borders
+])
+def test_annotate_matches_whole_array_witness_with_clipping_and_order(wf, hf, wm, hm, scale, arm,
+                                                                      half):
+    rng = np.random.default_rng(wf)
+    img = rng.integers(0, 256, (hf, wf, 3), dtype=np.uint8)
+    n = wm * hm
+    # corners (clipping on every side), two tools on the same cell (order), random others
+    argmax_idx = [0, wm - 1, n - wm, n - 1, n // 2, n // 2, int(rng.integers(n)), int(rng.integers(n))]
+    present = [1, 1, 1, 1, 1, 1, 0, 1]
+    out = oracle.annotate(img, argmax_idx, present, wm, hm, si.DEFAULT_PALETTE, si.DEFAULT_GLYPHS,
+                          arm, half, scale)
+    want = _annotate_witness(img, argmax_idx, present, wm, hm, si.DEFAULT_PALETTE,
+                             si.DEFAULT_GLYPHS, arm, half, scale)
+    assert np.array_equal(out, want)
+    cx, cy = oracle.anchor(n // 2, wm, hm, wf, hf)
+    assert tuple(out[cy, cx]) == tuple(si.DEFAULT_PALETTE[5])     # tool 5 painted over tool 4
+    assert np.array_equal(img, np.asarray(img))                   # input untouched
+
+
+def test_glyph_table_shape_and_t_glyph():
+    g = si.DEFAULT_GLYPHS
+    assert g.shape == (9, 7) and g.dtype == np.uint8 and int(g.max()) < 32
+    assert g[0, 0] == 0b11111 and all(int(v) == 0b00100 for v in g[0, 1:])   # 'T'
+    assert len({tuple(r) for r in g}) == 9                                    # all glyphs differ
