@@ -45,6 +45,9 @@ def parse():
                     help="K extra applications that submit frames back to back during the paced "
                          "latency run (saturating neighbours, not counted in the latency figures); "
                          "with --partition equal they get partitions of their own")
+    ap.add_argument("--annotate", action="store_true",
+                    help="overlay also draws argmax markers and tool labels (off in the headline "
+                         "workload)")
     ap.add_argument("--paced-frames", type=int, default=60)
     ap.add_argument("--distinct-frames", type=int, default=8)
     ap.add_argument("--queue-depth", type=int, default=4)
@@ -103,7 +106,8 @@ def main():
     for i in range(args.streams):
         s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW,
                       net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
-                      queue_depth=args.queue_depth, batch=args.batch)
+                      queue_depth=args.queue_depth, batch=args.batch,
+                      glyphs=si.DEFAULT_GLYPHS if args.annotate else None)
         hs.hs_set_launch_mode(s.app, hs.HS_LAUNCH_GRAPH if args.launch_mode == "graph"
                               else hs.HS_LAUNCH_EAGER)
         streams.append(s)
@@ -287,7 +291,7 @@ def main():
                                "argmax, alpha-blend overlay on the 1080p frame",
                    "streams": args.streams, "batch": args.batch, "partition": args.partition,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
-                   "hog_apps": args.hog, "device_cus": n_cus},
+                   "hog_apps": args.hog, "annotate": bool(args.annotate), "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),

@@ -89,6 +89,18 @@ typedef struct {
                             /* one frame of each stream; stages 1, 3, 4 run per stream,   */
                             /* the network runs once over the whole batch (ConvLSTM state */
                             /* per stream). Use hs_submit_batch / hs_poll_batch then.     */
+  /* Annotation layer of stage 4 (paper Section III-A: the visualisation draws the segmented
+   * tools and their text labels).  With annotate != 0, for every tool k whose present flag
+   * is set, in increasing k and opaque in palette[k], on top of the blended masks:
+   * a cross-hair centred on the argmax cell's footprint, cx = ((2*ax+1)*frame_w)/(2*map_w),
+   * cy likewise (arms marker_arm pixels long, 2*marker_half+1 thick), and the label 'T'<k>
+   * (glyphs of 5 x 7 cells, glyph_scale pixels per cell, second glyph 6*glyph_scale to the
+   * right, label origin (cx + marker_arm + 2, cy - 7*glyph_scale - 2)); clipped to the frame. */
+  int annotate;             /* 0: masks only                                             */
+  int marker_arm;           /* 0..64                                                     */
+  int marker_half;          /* 0..8                                                      */
+  int glyph_scale;          /* 1..8                                                      */
+  uint8_t glyphs[9][7];     /* 'T','0'..'7': 7 rows of 5-bit masks, bit 4 = left column  */
   void* d_workspace;        /* DEVICE memory owned by the caller, 256-byte aligned       */
   size_t workspace_bytes;   /* >= hs_query_workspace(); plays the role of the per-client  */
                             /* device-memory limit of the paper's partitions              */

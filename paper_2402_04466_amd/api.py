@@ -46,6 +46,8 @@ class hs_app_desc(C.Structure):
         ("mean", C.c_float), ("std", C.c_float), ("threshold", C.c_float), ("alpha", C.c_float),
         ("net", C.c_int), ("weights", C.c_void_p), ("weight_floats", C.c_size_t),
         ("palette", (C.c_uint8 * 3) * HS_NUM_TOOLS), ("queue_depth", C.c_int), ("batch", C.c_int),
+        ("annotate", C.c_int), ("marker_arm", C.c_int), ("marker_half", C.c_int),
+        ("glyph_scale", C.c_int), ("glyphs", (C.c_uint8 * 7) * 9),
         ("d_workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -143,9 +145,11 @@ def _check(status: int, soft=()) -> int:
 
 def make_desc(*, frame_w, frame_h, net_w, net_h, net, weights, palette, d_workspace=0,
               workspace_bytes=0, frame_pitch=None, net_fp32_input=0, mean=0.5, std=0.25,
-              threshold=0.5, alpha=0.5, queue_depth=2, batch=1) -> hs_app_desc:
+              threshold=0.5, alpha=0.5, queue_depth=2, batch=1, glyphs=None, marker_arm=12,
+              marker_half=1, glyph_scale=2) -> hs_app_desc:
     """Fill an hs_app_desc.  ``weights`` is a contiguous float32 NumPy array (kept alive by
-    the returned object); ``palette`` an (8, 3) uint8 array."""
+    the returned object); ``palette`` an (8, 3) uint8 array; ``glyphs`` a (9, 7) uint8 table of
+    row masks, which switches the annotation layer (markers + labels) on."""
     d = hs_app_desc()
     d.frame_w, d.frame_h = int(frame_w), int(frame_h)
     d.frame_pitch = int(frame_pitch if frame_pitch is not None else 3 * frame_w)
@@ -162,6 +166,13 @@ def make_desc(*, frame_w, frame_h, net_w, net_h, net, weights, palette, d_worksp
             d.palette[k][c] = int(pal[k, c])
     d.queue_depth = int(queue_depth)
     d.batch = int(batch)
+    d.annotate = 0 if glyphs is None else 1
+    d.marker_arm, d.marker_half, d.glyph_scale = int(marker_arm), int(marker_half), int(glyph_scale)
+    if glyphs is not None:
+        gl = np.asarray(glyphs, dtype=np.uint8).reshape(9, 7)
+        for g in range(9):
+            for r in range(7):
+                d.glyphs[g][r] = int(gl[g, r])
     d.d_workspace = int(d_workspace)
     d.workspace_bytes = int(workspace_bytes)
     return d

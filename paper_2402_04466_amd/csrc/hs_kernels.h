@@ -136,6 +136,10 @@ struct PostParams {
   PostRecord* rec;               // host-visible
   int batch;                     // images: logits/heat/mask are [batch][8][n], rec[batch]
   uint8_t* kmap;                 // [batch][n]: lowest channel with mask set, 0xff if none
+  // anchors of the annotation layer: marks[(image*8 + k)*2 + {0,1}] = frame position (cx, cy) of
+  // the centre of tool k's argmax cell, cx = -1 when the tool is absent; NULL: not wanted
+  int* marks;
+  int wm, hm, wf, hf;            // map (n == wm*hm) and frame size, for the anchors
 };
 KernelDesc describe(const PostParams& p);
 
@@ -148,6 +152,11 @@ struct OverlayParams {
                                      // (needs wf*wm, hf*hm and ceil(wf/16)*hf below 2^31)
   int a;                             // Q8 alpha, 0..256
   uint32_t pal[8];                   // R | G<<8 | B<<16
+  // annotation layer: cross-hair and 'T'<k> label per present tool, opaque, in tool order
+  const int* marks;                  // anchors written by the postprocess kernel, NULL: none
+  int arm, half, scale;              // marker arm / half thickness, pixels per glyph cell
+  float rcp_scale;                   // 1/scale
+  uint64_t glyph[9];                 // bit (5*row + col) of glyph g, col 0 = leftmost
 };
 KernelDesc describe(const OverlayParams& p);
 

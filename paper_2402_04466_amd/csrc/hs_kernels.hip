@@ -941,6 +941,18 @@ __global__ __launch_bounds__(256) void k_postprocess(PostParams p) {
     rec->argmax_idx[k] = bi;
     rec->peak[k] = 1.0f / (1.0f + expf(-bv));
     rec->present[k] = bv > p.theta ? 1 : 0;
+    if (p.marks) {
+      // anchor of the annotation layer: centre of the argmax cell's footprint in the frame
+      int* mk = p.marks + ((size_t)blockIdx.y * 8 + k) * 2;
+      if (bv > p.theta) {
+        const int ay = bi / p.wm, ax = bi - ay * p.wm;
+        mk[0] = ((2 * ax + 1) * p.wf) / (2 * p.wm);
+        mk[1] = ((2 * ay + 1) * p.hf) / (2 * p.hm);
+      } else {
+        mk[0] = -1;
+        mk[1] = -1;
+      }
+    }
   }
 }
 
@@ -1064,6 +1076,52 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
         while (rem >= p.wf) { rem -= p.wf; ++mx; }
       }
     }
+    if (p.marks) {
+      // annotation layer: a tool's drawing lies in one box; only groups that meet a box look
+      // closer, pixel by pixel, tools in increasing order (later tools paint over earlier ones)
+      const int* mk = p.marks + (size_t)blockIdx.y * 16;
+      const int lab_w = 11 * p.scale, lab_h = 7 * p.scale;
+#pragma unroll 1
+      for (int k = 0; k < 8; ++k) {
+        const int cx = mk[2 * k], cy = mk[2 * k + 1];
+        if (cx < 0) continue;
+        const int ox = cx + p.arm + 2, oy = cy - lab_h - 2;          // label origin
+        if (Y < min(cy - p.arm, oy) || Y > cy + p.arm || X0 + 15 < cx - p.arm ||
+            X0 >= ox + lab_w)
+          continue;
+        const uint32_t col = p.pal[k];
+        // what this row paints, as pixel intervals around cx and a bit per label pixel
+        const int dy = abs(Y - cy);
+        const int reach = dy <= p.half ? p.arm : (dy <= p.arm ? p.half : -1);   // |X - cx| <= reach
+        uint64_t lab_lo = 0, lab_hi = 0;       // label pixels lx = 0..63 and 64..87 of this row
+        if (Y >= oy && Y < oy + lab_h) {
+          const int gy = (int)udiv_est((uint32_t)(Y - oy), (uint32_t)p.scale, p.rcp_scale);
+          const uint32_t cells = (uint32_t)((p.glyph[0] >> (5 * gy)) & 31ull) |
+                                 ((uint32_t)((p.glyph[1 + k] >> (5 * gy)) & 31ull) << 6);
+          const uint64_t run = (1ull << p.scale) - 1ull;               // scale <= 8 pixels per cell
+          for (int cell = 0; cell < 11; ++cell) {
+            if (!((cells >> cell) & 1u)) continue;
+            const int at = cell * p.scale;
+            if (at < 64) lab_lo |= run << at;
+            if (at + p.scale > 64) lab_hi |= at >= 64 ? run << (at - 64) : run >> (64 - at);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int X = X0 + i, lx = X - ox;
+          bool hit = abs(X - cx) <= reach;
+          if (lx >= 0 && lx < lab_w) hit = hit || (((lx < 64 ? lab_lo >> lx : lab_hi >> (lx - 64)) & 1ull) != 0);
+          if (hit) {
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+              const int byte = 3 * i + c;               // literal after unrolling
+              const uint32_t pc = (col >> (8 * c)) & 0xffu;
+              w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (pc << (8 * (byte & 3)));
+            }
+          }
+        }
+      }
+    }
     if (coalesced) {
 #pragma unroll
       for (int j = 0; j < 3; ++j) {
@@ -1088,13 +1146,32 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
   } else {
     for (int i = 0; i < npx; ++i) {
       const uint8_t k = krow[mx];
+      const int X = X0 + i;
+      int paint = -1;                          // tool whose marker or label covers this pixel
+      if (p.marks) {
+        const int* mk = p.marks + (size_t)blockIdx.y * 16;
+        for (int t = 0; t < 8; ++t) {
+          const int cx = mk[2 * t], cy = mk[2 * t + 1];
+          if (cx < 0) continue;
+          const int dx = abs(X - cx), dy = abs(Y - cy);
+          bool hit = (dx <= p.arm && dy <= p.half) || (dy <= p.arm && dx <= p.half);
+          const int lx = X - (cx + p.arm + 2), ly = Y - (cy - 7 * p.scale - 2);
+          if (lx >= 0 && lx < 11 * p.scale && ly >= 0 && ly < 7 * p.scale) {
+            const int cell = lx / p.scale, gy = ly / p.scale;
+            const int gi = cell >= 6 ? 1 : 0, gx = cell - 6 * gi;
+            if (gx < 5) hit = hit || ((p.glyph[gi ? 1 + t : 0] >> (5 * gy + gx)) & 1ull);
+          }
+          if (hit) paint = t;
+        }
+      }
       for (int c = 0; c < 3; ++c) {
-        uint32_t x = srow[(size_t)(X0 + i) * 3 + c];
+        uint32_t x = srow[(size_t)X * 3 + c];
         if (k != 0xff) {
           const uint32_t pc = (p.pal[k] >> (8 * c)) & 0xffu;
           x = (p.a * pc + ia * x + 128u) >> 8;
         }
-        drow[(size_t)(X0 + i) * 3 + c] = (uint8_t)x;
+        if (paint >= 0) x = (p.pal[paint] >> (8 * c)) & 0xffu;
+        drow[(size_t)X * 3 + c] = (uint8_t)x;
       }
       rem += p.wm;
       while (rem >= p.wf) { rem -= p.wf; ++mx; }

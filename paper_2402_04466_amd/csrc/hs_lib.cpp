@@ -582,6 +582,11 @@ static hs_status validate_desc(const hs_app_desc* d) {
     set_error("std must be > 0, threshold in (0,1), alpha in [0,1]");
     return HS_E_INVAL;
   }
+  if (d->annotate && (d->marker_arm < 0 || d->marker_arm > 64 || d->marker_half < 0 ||
+                      d->marker_half > 8 || d->glyph_scale < 1 || d->glyph_scale > 8)) {
+    set_error("annotation: marker_arm 0..64, marker_half 0..8, glyph_scale 1..8");
+    return HS_E_INVAL;
+  }
   if (d->batch < 1 || d->batch > 16) {
     set_error("batch must be 1..16");
     return HS_E_INVAL;
@@ -633,7 +638,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   const size_t n_map = (size_t)mh * mw;
   const int B = d->batch;
   struct SlotBuf { f16* netin; float* netin32; float* logits; float* heat; uint8_t* mask;
-                   uint8_t* kmap; };
+                   uint8_t* kmap; int* marks; };
   std::vector<SlotBuf> sb(depth);
   for (int i = 0; i < depth; ++i) {
     sb[i].netin = b.carve.take<f16>((size_t)B * ph * pw * 4);
@@ -643,6 +648,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     sb[i].heat = b.carve.take<float>(B * 8 * n_map);
     sb[i].mask = b.carve.take<uint8_t>(B * 8 * n_map);
     sb[i].kmap = b.carve.take<uint8_t>(B * n_map);
+    sb[i].marks = d->annotate ? b.carve.take<int>((size_t)B * 16) : nullptr;
   }
   const size_t total = round_up_sz(b.carve.off, 256);
   if (bytes_out) *bytes_out = total;
@@ -727,7 +733,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       Op p;
       p.fam = F_POST;
       p.post = PostParams{s.d_logits, (int)n_map, (float)theta_d, s.d_heat, s.d_mask, s.rec, B,
-                          sb[i].kmap};
+                          sb[i].kmap, sb[i].marks, mw, mh, d->frame_w, d->frame_h};
       p.bytes = B * 8.0 * n_map * (4 + 4 + 1);
       s.post.push_back(p);
     }
@@ -742,6 +748,16 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       op.rcp_hf = 1.0f / (float)d->frame_h; op.rcp_wf = 1.0f / (float)d->frame_w;
       op.rcp_wm = 1.0f / (float)mw;
       op.a = a_q8;
+      op.marks = sb[i].marks;
+      op.arm = d->marker_arm; op.half = d->marker_half; op.scale = d->glyph_scale;
+      op.rcp_scale = 1.0f / (float)std::max(1, d->glyph_scale);
+      for (int g = 0; g < 9; ++g) {
+        uint64_t bits = 0;
+        for (int r = 0; r < 7; ++r)
+          for (int c = 0; c < 5; ++c)
+            if ((d->glyphs[g][r] >> (4 - c)) & 1) bits |= 1ull << (5 * r + c);
+        op.glyph[g] = bits;
+      }
       for (int k = 0; k < 8; ++k)
         op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
                     ((uint32_t)d->palette[k][2] << 16);

@@ -21,6 +21,7 @@ class AppStream:
                  blob: np.ndarray, palette: np.ndarray, queue_depth: int = 2,
                  net_fp32_input: bool = False, frame_pitch: int | None = None, mean: float = 0.5,
                  std: float = 0.25, threshold: float = 0.5, alpha: float = 0.5, batch: int = 1,
+                 glyphs=None, marker_arm: int = 12, marker_half: int = 1, glyph_scale: int = 2,
                  device: str = "cuda:0"):
         self.ctx = ctx
         self.frame_w, self.frame_h = frame_w, frame_h
@@ -30,7 +31,8 @@ class AppStream:
         kw = dict(frame_w=frame_w, frame_h=frame_h, net_w=net_w, net_h=net_h, net=net,
                   weights=blob, palette=palette, frame_pitch=self.frame_pitch,
                   net_fp32_input=int(net_fp32_input), mean=mean, std=std, threshold=threshold,
-                  alpha=alpha, queue_depth=queue_depth, batch=batch)
+                  alpha=alpha, queue_depth=queue_depth, batch=batch, glyphs=glyphs,
+                  marker_arm=marker_arm, marker_half=marker_half, glyph_scale=glyph_scale)
         self.batch = batch
         need = api.hs_query_workspace(api.make_desc(**kw))
         self.workspace = torch.empty(need + 256, dtype=torch.uint8, device=self.device)

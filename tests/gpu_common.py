@@ -27,7 +27,7 @@ def rel_err(a, ref):
 
 
 def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, threshold, alpha,
-                palette, fp32_input, mean=0.5, std=0.25, tag=""):
+                palette, fp32_input, mean=0.5, std=0.25, tag="", glyphs=None, marker=(12, 1, 2)):
     """g: GPU outputs of one frame; o32 / o16: oracle outputs (fp32 storage / fp16 emulation)."""
     # ---- stage 1: bit-exact -------------------------------------------------------------
     lut16 = oracle.normalize_lut(mean, std, fp16=True)
@@ -65,6 +65,9 @@ def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, thre
     # ---- stage 4, stage-isolated: the oracle's overlay with the GPU's own mask --------------
     if "overlay" in g:
         want_ov = oracle.overlay(frame, g["mask"], palette, alpha)
+        if glyphs is not None:   # annotation layer from the GPU's own argmax / present
+            want_ov = oracle.annotate(want_ov, g["argmax_idx"], g["present"], g["mask"].shape[2],
+                                      g["mask"].shape[1], palette, glyphs, *marker)
         assert np.array_equal(g["overlay"], want_ov), f"{tag}: overlay differs"
     return e32
 

@@ -23,12 +23,14 @@ def ctx(hs):
 
 
 def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_input, depth=2,
-                threshold=0.5, alpha=0.5, check_state=False, tag=""):
+                threshold=0.5, alpha=0.5, check_state=False, tag="", glyphs=None,
+                marker=(12, 1, 2)):
     from paper_2402_04466_amd.harness import AppStream
     fh, fw, _ = frames[0].shape
     s = AppStream(ctx, net=net, frame_w=fw, frame_h=fh, net_w=net_w, net_h=net_h, blob=blob,
                   palette=PAL, queue_depth=depth, net_fp32_input=fp32_input, threshold=threshold,
-                  alpha=alpha)
+                  alpha=alpha, glyphs=glyphs, marker_arm=marker[0], marker_half=marker[1],
+                  glyph_scale=marker[2])
     o32, o16 = make_oracles(net_name, blob, net_w, net_h, not fp32_input, PAL,
                             threshold=threshold, alpha=alpha)
     errs = []
@@ -49,7 +51,8 @@ def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_inpu
             g = s.fetch(r, d_out)
             a, b = o32.process(f), o16.process(f)
             errs.append(check_frame(g, f, a, b, threshold=threshold, alpha=alpha, palette=PAL,
-                                    fp32_input=fp32_input, tag=f"{tag}/frame{i}"))
+                                    fp32_input=fp32_input, tag=f"{tag}/frame{i}", glyphs=glyphs,
+                                    marker=marker))
             if check_state:
                 gh, gc = s.state(r)
                 gx = s.features(r)
@@ -118,6 +121,24 @@ def test_tiny_net_edge_shapes(hs, ctx, fw, fh, nw, nh, thr, alpha):
                 tag=f"edge-{fw}x{fh}-{nw}x{nh}")
     if alpha == 0.0:
         pass  # check_frame already compared against the oracle overlay (== input for alpha 0)
+
+
+@pytest.mark.parametrize("fw,fh,nw,nh,net_name,marker", [
+    (320, 240, 128, 128, "tiny4", (12, 1, 2)),       # 10-pixel cells, markers of all 8 tools crowd
+    (322, 241, 96, 72, "tiny4", (7, 0, 1)),          # ragged rows: byte path of the overlay
+    (1920, 1080, 854, 480, "resnet18_convlstm", (12, 1, 2)),   # full size, coalesced path
+    (640, 360, 288, 160, "resnet18_convlstm", (20, 3, 3)),     # thick marker, big labels, clipping
+])
+def test_annotation_layer_markers_and_labels(hs, ctx, fw, fh, nw, nh, net_name, marker):
+    """Overlay with the annotation layer on: the frame must equal, bit for bit, the oracle's
+    mask blend + markers + 'T<k>' labels drawn from the GPU's own argmax / present record."""
+    tiny = net_name == "tiny4"
+    frames = list(si.uniform_frames(2, fh, fw, 9)) if tiny else \
+        list(si.tool_scene_frames(2, fh, fw, 9))
+    blob = si.he_normal_blob(si.TINY4_LAYERS if tiny else si.RESNET18_CONVLSTM_LAYERS, 4)
+    _run_stream(hs, ctx, net=hs.HS_NET_TINY4 if tiny else hs.HS_NET_RESNET18_CONVLSTM,
+                net_name=net_name, frames=frames, net_w=nw, net_h=nh, blob=blob, fp32_input=tiny,
+                glyphs=si.DEFAULT_GLYPHS, marker=marker, tag=f"annot-{fw}x{fh}")
 
 
 def test_reset_state_and_queue_semantics(hs, ctx):
