@@ -39,8 +39,13 @@ def parse():
                     help="streams per application, batched through the network together "
                          "(--streams counts applications; 12 with --fps 30 is the saturation case)")
     ap.add_argument("--fps", type=float, default=60.0, help="pacing of the latency run")
-    ap.add_argument("--partition", choices=["none", "equal"], default="none",
-                    help="equal: disjoint CU-masked partitions, inference/overlay split")
+    ap.add_argument("--partition", choices=["none", "equal", "equal-shared"], default="none",
+                    help="equal: disjoint CU-masked partitions, inference and overlay on separate "
+                         "CU sets and queues; equal-shared: one CU set and one queue per "
+                         "application for all four stages")
+    ap.add_argument("--partition-groups", type=int, default=0, metavar="G",
+                    help="with --partition equal: CU groups (8 CUs, one per XCD) per application "
+                         "instead of an equal share of the device; the last group serves the overlay")
     ap.add_argument("--hog", type=int, default=0, metavar="K",
                     help="K extra applications that submit frames back to back during the paced "
                          "latency run (saturating neighbours, not counted in the latency figures); "
@@ -62,13 +67,15 @@ def parse():
 
 
 def equal_partitions(n_cus: int, n_streams: int, overlay_groups: int = 1, spare_groups: int = 2,
-                     n_xcd: int = 8):
+                     n_xcd: int = 8, groups_per_app: int = 0):
     """n_streams disjoint CU sets of equal size, built from groups of n_xcd consecutive CUs
     (CU i sits on XCD i mod n_xcd and a mask needs a CU on every XCD).  Inside each set the
     last overlay_groups groups serve the overlay stream, the rest the inference stream;
     spare_groups groups stay unclaimed (the paper's appendix recommends leaving headroom)."""
     groups = n_cus // n_xcd - spare_groups
-    per = groups // n_streams
+    per = groups_per_app if groups_per_app else groups // n_streams
+    if per < 2 or per * n_streams > n_cus // n_xcd:
+        raise SystemExit(f"{n_streams} partitions of {per} CU groups do not fit {n_cus} CUs")
     parts = []
     for i in range(n_streams):
         cus = list(range(i * per * n_xcd, (i + 1) * per * n_xcd))
@@ -127,8 +134,12 @@ def main():
         hogs.append(s)
         hog_frames.append([s.upload_frame(f) for f in si.tool_scene_frames(2, FH, FW, 100 + i)])
         hog_outs.append([s.new_output() for _ in range(args.queue_depth)])
-    if args.partition == "equal":
-        for s, (ci, co) in zip(streams + hogs, equal_partitions(n_cus, args.streams + args.hog)):
+    if args.partition != "none":
+        for s, (ci, co) in zip(streams + hogs,
+                               equal_partitions(n_cus, args.streams + args.hog,
+                                                groups_per_app=args.partition_groups)):
+            if args.partition == "equal-shared":
+                ci = co = ci + co
             hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
     outs = [[[s.new_output() for _ in range(args.batch)] for _ in range(args.queue_depth)]
             for s in streams]
@@ -290,6 +301,7 @@ def main():
                                "ResNet-18-style + ConvLSTM(256) + 8-ch head, sigmoid/threshold/"
                                "argmax, alpha-blend overlay on the 1080p frame",
                    "streams": args.streams, "batch": args.batch, "partition": args.partition,
+                   "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
                    "hog_apps": args.hog, "annotate": bool(args.annotate), "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),

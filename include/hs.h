@@ -203,7 +203,10 @@ hs_status hs_get_features(hs_app* app, int stream, float* x_out);
 
 /* Bind the application's inference stream (stages 1-3) and overlay stream (stage 4) to
  * CU sets. Masks are bit sets, bit i of word i/32 = CU i, n_words <= HS_MAX_CU_WORDS.
- * The two masks may be equal or disjoint (compute / visualisation isolation).
+ * The two masks may be disjoint (compute / visualisation isolation: two streams, i.e. two
+ * hardware queues) or equal (one stream carries all four stages).  The device executes at
+ * most four hardware queues truly concurrently; queues beyond that share a pipe and their
+ * frames serialise, so more than two partitioned applications should use equal masks.
  * Admission control: refused with HS_E_OVERSUBSCRIBED, changing nothing, if a mask is
  * empty, names a CU the device does not have, or intersects CUs claimed by another
  * application of the context. On MI355X CU i belongs to XCD i mod 8 and every mask must

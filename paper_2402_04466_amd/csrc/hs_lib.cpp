@@ -816,7 +816,11 @@ static void completer_main(hs_app* app) {
 
 static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* mo, int n_words) {
   hipStream_t si = nullptr, so = nullptr;
-  if (mi) {
+  if (mi && std::memcmp(mi, mo, sizeof(uint32_t) * (size_t)n_words) == 0) {
+    // equal masks: one stream, i.e. one hardware queue, carries all four stages
+    HS_HIP(hipExtStreamCreateWithCUMask(&si, (uint32_t)n_words, mi));
+    so = si;
+  } else if (mi) {
     HS_HIP(hipExtStreamCreateWithCUMask(&si, (uint32_t)n_words, mi));
     hipError_t e = hipExtStreamCreateWithCUMask(&so, (uint32_t)n_words, mo);
     if (e != hipSuccess) {
@@ -833,8 +837,8 @@ static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* m
       return HS_E_DEVICE;
     }
   }
+  if (app->s_overlay && app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
   if (app->s_infer) (void)hipStreamDestroy(app->s_infer);
-  if (app->s_overlay) (void)hipStreamDestroy(app->s_overlay);
   app->s_infer = si;
   app->s_overlay = so;
   return HS_OK;
@@ -1057,8 +1061,8 @@ hs_status hs_destroy_app(hs_app* app) {
     (void)hipEventDestroy(s.ev_post);
     (void)hipEventDestroy(s.ev_overlay);
   }
+  if (app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
   (void)hipStreamDestroy(app->s_infer);
-  (void)hipStreamDestroy(app->s_overlay);
   if (app->pinned) (void)hipHostFree(app->pinned);
   {
     std::lock_guard<std::mutex> lk(app->ctx->mu);
