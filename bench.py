@@ -50,6 +50,18 @@ def parse():
                     help="K extra applications that submit frames back to back during the paced "
                          "latency run (saturating neighbours, not counted in the latency figures); "
                          "with --partition equal they get partitions of their own")
+    ap.add_argument("--tiny-apps", type=int, default=0, metavar="K",
+                    help="K applications of the small network (320x240 frames -> 128x128, 4 conv "
+                         "layers) paced beside the others during the latency run: heterogeneous "
+                         "applications sharing the GPU; their latencies are reported separately")
+    ap.add_argument("--pin-cpus", action="store_true",
+                    help="pin every application's submitting thread and completion thread to cores "
+                         "of their own (cores 2i and 2i+1 of this process's CPU set)")
+    ap.add_argument("--save-latencies", metavar="FILE",
+                    help="write the trimmed per-frame latencies (ms) of the paced run as JSON")
+    ap.add_argument("--compare-latencies", metavar="FILE",
+                    help="Mann-Whitney U of this run's latencies against a file written by "
+                         "--save-latencies (|z| > 1.96: the distributions differ)")
     ap.add_argument("--annotate", action="store_true",
                     help="overlay also draws argmax markers and tool labels (off in the headline "
                          "workload)")
@@ -134,9 +146,19 @@ def main():
         hogs.append(s)
         hog_frames.append([s.upload_frame(f) for f in si.tool_scene_frames(2, FH, FW, 100 + i)])
         hog_outs.append([s.new_output() for _ in range(args.queue_depth)])
+    tiny, tiny_frames, tiny_outs = [], [], []
+    if args.tiny_apps:
+        tiny_blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+        for i in range(args.tiny_apps):
+            s = AppStream(ctx, net=hs.HS_NET_TINY4, frame_w=320, frame_h=240, net_w=128, net_h=128,
+                          blob=tiny_blob, palette=si.DEFAULT_PALETTE, queue_depth=args.queue_depth,
+                          net_fp32_input=True)
+            tiny.append(s)
+            tiny_frames.append([[s.upload_frame(f)] for f in si.uniform_frames(8, 240, 320, 50 + i)])
+            tiny_outs.append([[s.new_output()] for _ in range(args.queue_depth)])
     if args.partition != "none":
-        for s, (ci, co) in zip(streams + hogs,
-                               equal_partitions(n_cus, args.streams + args.hog,
+        for s, (ci, co) in zip(streams + tiny + hogs,
+                               equal_partitions(n_cus, args.streams + args.tiny_apps + args.hog,
                                                 groups_per_app=args.partition_groups)):
             if args.partition == "equal-shared":
                 ci = co = ci + co
@@ -198,7 +220,26 @@ def main():
     for t in hog_threads:
         t.start()
     t_hog = time.perf_counter()
-    results, dropped = run_paced(streams, paced, args.fps, outs)
+    pins = None
+    if args.pin_cpus:
+        cores = sorted(os.sched_getaffinity(0))
+        pins = [cores[(2 * i) % len(cores)] for i in range(len(streams) + len(tiny))]
+        for i, s in enumerate(streams + tiny):
+            hs.hs_set_cpu_affinity(s.app, cores[(2 * i + 1) % len(cores)])
+    tiny_paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
+                  for f in tiny_frames]
+    results, dropped = run_paced(streams + tiny, paced + tiny_paced, args.fps, outs + tiny_outs,
+                                 pin_cpus=pins)
+    tiny_results, results = results[len(streams):], results[:len(streams)]
+    tiny_m = None
+    if tiny:
+        tl = []
+        for rs in tiny_results:
+            per = [(r[0].t_overlay_done_ns - r[0].t_submit_ns) / 1e6 for r in rs]
+            t = min(10, len(per) // 6)
+            tl.extend(per[t:len(per) - t])
+        tm = hs.hs_latency_metrics_compute(tl, trim=False)
+        tiny_m = {k: (int(v) if k == "n" else round(v, 4)) for k, v in tm.items()}
     hog_stop.set()
     for t in hog_threads:
         t.join()
@@ -210,6 +251,15 @@ def main():
             t = min(10, len(per) // 6)
             lat_ms.extend(per[t:len(per) - t])   # trim each stream's warm-up / cool-down
     m = hs.hs_latency_metrics_compute(lat_ms, trim=False)
+    mwu = None
+    if args.compare_latencies:
+        with open(args.compare_latencies) as fh:
+            other = json.load(fh)
+        mwu = hs.hs_mann_whitney_u(lat_ms, other["latency_ms"])
+        mwu["against"] = other.get("label", args.compare_latencies)
+    if args.save_latencies:
+        with open(args.save_latencies, "w") as fh:
+            json.dump({"label": " ".join(sys.argv[1:]), "latency_ms": lat_ms}, fh)
     per_stream_p50 = []
     for rs in results:
         for j in range(args.batch):
@@ -266,7 +316,7 @@ def main():
             d["GB/s"] = round(e["bytes"] / (e["total_ms"] * 1e-3) / 1e9, 1)
         kernels[e["name"]] = d
 
-    for s in streams + hogs:
+    for s in streams + tiny + hogs:
         s.close()
     hs.hs_shutdown(ctx)
 
@@ -303,13 +353,15 @@ def main():
                    "streams": args.streams, "batch": args.batch, "partition": args.partition,
                    "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
-                   "hog_apps": args.hog, "annotate": bool(args.annotate), "device_cus": n_cus},
+                   "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "annotate": bool(args.annotate), "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),
                        "std": round(m["std"], 4), "tail": round(m["tail"], 4),
                        "flatness": round(m["flatness"], 4), "dropped": int(sum(dropped)),
                        "stage_median_ms": stage_ms, "per_stream_p50": per_stream_p50,
+                       "mann_whitney": mwu, "pinned_cpus": bool(args.pin_cpus),
+                       "tiny_apps": tiny_m,
                        "hog_frames_per_s": round(sum(hog_count) / t_hog, 1) if hogs else None},
         "roofline": roof,
         "kernels": kernels,

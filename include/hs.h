@@ -267,6 +267,24 @@ hs_status hs_set_launch_mode(hs_app* app, int mode);
  * closest ranks. HS_E_INVAL if nothing is left. Pure host computation. */
 hs_status hs_latency_metrics_compute(const double* latencies, size_t n, int trim,
                                      hs_latency_metrics* out);
+/* Two-sided Mann-Whitney U comparison of two latency samples (paper, appendix "Additional
+ * Evaluation": two configurations differ when |Z| > 1.96 at significance level 0.05).
+ * u = number of pairs (a_i, b_j) with a_i > b_j plus half the ties; z = normal approximation
+ * with tie-corrected variance and 0.5 continuity correction, 0 when the variance vanishes.
+ * Pure host computation on HOST arrays; HS_E_INVAL if an array is NULL or empty. */
+typedef struct {
+  double u;          /* U statistic of sample a                                           */
+  double z;          /* > 0: a tends to be larger than b                                  */
+  int significant;   /* |z| > 1.96                                                        */
+} hs_mwu;
+hs_status hs_mann_whitney_u(const double* a, size_t na, const double* b, size_t nb, hs_mwu* out);
+
+/* Pin the application's completion thread (the one that observes the end of a frame and
+ * stamps its departure) to one CPU core, cpu = -1 lifts the pin (paper Section IV-C, CPU
+ * affinity). The caller pins its own submitting thread with sched_setaffinity.
+ * HS_E_INVAL if the core does not exist or the operating system refuses. */
+hs_status hs_set_cpu_affinity(hs_app* app, int cpu);
+
 /* enable != 0: bracket every kernel launch of this application with HIP events on the
  * launching stream and accumulate elapsed time per kernel family (adds event overhead;
  * meant for roofline measurements, off by default). Switching resets the accumulators.

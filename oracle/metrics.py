@@ -38,3 +38,33 @@ def determinism_metrics(latencies, trim: bool = True) -> dict:
     return {"n": int(len(s)), "mean": mean, "max": pct[100], "std": std,
             "p50": pct[50], "p99": pct[99], "tail": pct[100] - pct[95],
             "flatness": pct[90] - pct[10]}
+
+
+def mann_whitney_z(a, b) -> dict:
+    """Two-sided Mann-Whitney U comparison of two latency samples (paper, appendix "Additional
+    Evaluation": configurations are called different when |Z| > 1.96 at significance 0.05).
+
+    Straight from the definition: U_a = #{(i, j): a_i > b_j} + 0.5 * #{(i, j): a_i == b_j};
+    normal approximation with the tie-corrected variance and a 0.5 continuity correction
+    (the paper names neither; this is the common textbook form):
+    mu = n*m/2, sigma^2 = n*m/12 * ((N + 1) - sum(t^3 - t) / (N * (N - 1))), N = n + m,
+    t = sizes of the groups of equal values in the pooled sample,
+    z = (U_a - mu -/+ 0.5) / sigma (towards zero), z = 0 when U_a == mu or sigma == 0.
+    """
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    n, m = len(a), len(b)
+    u = 0.0
+    for x in a:                                  # pairwise, no ranking shortcut
+        u += float((x > b).sum()) + 0.5 * float((x == b).sum())
+    big_n = n + m
+    _, counts = np.unique(np.concatenate([a, b]), return_counts=True)
+    ties = float(((counts.astype(np.float64) ** 3) - counts).sum())
+    mu = n * m / 2.0
+    var = n * m / 12.0 * ((big_n + 1) - ties / (big_n * (big_n - 1))) if big_n > 1 else 0.0
+    d = u - mu
+    if var <= 0.0 or d == 0.0:
+        z = 0.0
+    else:
+        z = (d - 0.5 * np.sign(d)) / np.sqrt(var)
+    return {"u": u, "z": float(z), "significant": bool(abs(z) > 1.96)}

@@ -19,7 +19,7 @@ __all__ = [
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
-    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch", "hs_latency_metrics_compute", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
+    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
     "hs_get_kernel_times", "hs_device_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
@@ -72,6 +72,10 @@ class hs_latency_metrics(C.Structure):
                 ("flatness", C.c_double)]
 
 
+class hs_mwu(C.Structure):
+    _fields_ = [("u", C.c_double), ("z", C.c_double), ("significant", C.c_int)]
+
+
 class hs_kernel_time(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_uint64), ("total_ms", C.c_double),
                 ("flops", C.c_double), ("bytes", C.c_double)]
@@ -115,6 +119,8 @@ def load() -> C.CDLL:
         "hs_wait_result": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
         "hs_latency_metrics_compute": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int,
                                                  P(hs_latency_metrics)]),
+        "hs_mann_whitney_u": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, P(hs_mwu)]),
+        "hs_set_cpu_affinity": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_set_kernel_timing": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_get_kernel_times": (C.c_int, [C.c_void_p, P(hs_kernel_time), C.c_int, P(C.c_int)]),
@@ -308,6 +314,19 @@ def hs_latency_metrics_compute(latencies, trim: bool = True) -> dict:
     _check(load().hs_latency_metrics_compute(x.ctypes.data, x.size, 1 if trim else 0,
                                              C.byref(m)))
     return {k: getattr(m, k) for k, _ in hs_latency_metrics._fields_}
+
+
+def hs_mann_whitney_u(a, b) -> dict:
+    """Two-sided Mann-Whitney U of two latency samples: {"u", "z", "significant"}."""
+    x = np.ascontiguousarray(a, dtype=np.float64)
+    y = np.ascontiguousarray(b, dtype=np.float64)
+    r = hs_mwu()
+    _check(load().hs_mann_whitney_u(x.ctypes.data, x.size, y.ctypes.data, y.size, C.byref(r)))
+    return {"u": r.u, "z": r.z, "significant": bool(r.significant)}
+
+
+def hs_set_cpu_affinity(app: int, cpu: int) -> None:
+    _check(load().hs_set_cpu_affinity(app, int(cpu)))
 
 
 def hs_device_copy(ctx: int, d_dst: int, d_src: int, nbytes: int) -> None:

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <utility>
 #include <vector>
 
 #include "hs.h"
@@ -100,6 +101,43 @@ hs_status hs_latency_metrics_compute(const double* lat, size_t n, int trim,
   out->p99 = hs::percentile_sorted(s, 99.0);
   out->tail = s.back() - hs::percentile_sorted(s, 95.0);
   out->flatness = hs::percentile_sorted(s, 90.0) - hs::percentile_sorted(s, 10.0);
+  return HS_OK;
+}
+
+hs_status hs_mann_whitney_u(const double* a, size_t na, const double* b, size_t nb, hs_mwu* out) {
+  if (!a || !b || !out || na == 0 || nb == 0) {
+    hs::set_error("mann-whitney: NULL or empty sample");
+    return HS_E_INVAL;
+  }
+  // pooled mid-ranks: sort (value, sample) pairs, give every run of equal values its mean rank
+  std::vector<std::pair<double, int>> v;
+  v.reserve(na + nb);
+  for (size_t i = 0; i < na; ++i) v.emplace_back(a[i], 0);
+  for (size_t i = 0; i < nb; ++i) v.emplace_back(b[i], 1);
+  std::sort(v.begin(), v.end(),
+            [](const std::pair<double, int>& x, const std::pair<double, int>& y) { return x.first < y.first; });
+  const double N = (double)(na + nb);
+  double rank_sum_a = 0.0, ties = 0.0;
+  for (size_t i = 0; i < v.size();) {
+    size_t j = i;
+    while (j < v.size() && v[j].first == v[i].first) ++j;
+    const double t = (double)(j - i);
+    const double mid = 0.5 * ((double)(i + 1) + (double)j);     // ranks i+1 .. j
+    for (size_t k = i; k < j; ++k)
+      if (v[k].second == 0) rank_sum_a += mid;
+    ties += t * t * t - t;
+    i = j;
+  }
+  const double n = (double)na, m = (double)nb;
+  const double u = rank_sum_a - n * (n + 1.0) / 2.0;
+  const double mu = n * m / 2.0;
+  const double var = N > 1.0 ? n * m / 12.0 * ((N + 1.0) - ties / (N * (N - 1.0))) : 0.0;
+  const double d = u - mu;
+  double z = 0.0;
+  if (var > 0.0 && d != 0.0) z = (d - (d > 0.0 ? 0.5 : -0.5)) / std::sqrt(var);
+  out->u = u;
+  out->z = z;
+  out->significant = std::fabs(z) > 1.96 ? 1 : 0;
   return HS_OK;
 }
 

@@ -13,7 +13,10 @@
 #include <mutex>
 #include <string>
 #include <thread>
+#include <pthread.h>
+#include <sched.h>
 #include <time.h>
+#include <unistd.h>
 #include <vector>
 
 #include "hs.h"
@@ -1333,6 +1336,25 @@ hs_status hs_set_launch_mode(hs_app* app, int mode) {
   }
   if (frames_in_flight(app)) { set_error("hs_set_launch_mode: frames in flight"); return HS_E_STATE; }
   app->launch_mode = mode;
+  return HS_OK;
+}
+
+hs_status hs_set_cpu_affinity(hs_app* app, int cpu) {
+  if (!app) { set_error("hs_set_cpu_affinity: NULL"); return HS_E_INVAL; }
+  cpu_set_t set;
+  CPU_ZERO(&set);
+  if (cpu < 0) {
+    const long n = sysconf(_SC_NPROCESSORS_CONF);
+    for (long c = 0; c < n && c < CPU_SETSIZE; ++c) CPU_SET((int)c, &set);
+  } else {
+    if (cpu >= CPU_SETSIZE) { set_error("hs_set_cpu_affinity: no such core %d", cpu); return HS_E_INVAL; }
+    CPU_SET(cpu, &set);
+  }
+  const int rc = pthread_setaffinity_np(app->completer.native_handle(), sizeof(set), &set);
+  if (rc != 0) {
+    set_error("hs_set_cpu_affinity: core %d refused (%s)", cpu, strerror(rc));
+    return HS_E_INVAL;
+  }
   return HS_OK;
 }
 

@@ -7,6 +7,7 @@ paper runs one process per application instance (Section V-B).
 """
 from __future__ import annotations
 
+import os
 import threading
 import time
 
@@ -141,12 +142,13 @@ class AppStream:
             self._held.clear()
 
 
-def run_paced(streams, frames, fps: float, outputs):
+def run_paced(streams, frames, fps: float, outputs, pin_cpus=None):
     """Submit frame k of every application at t0 + k/fps from one thread per application and
     collect the per-frame results.  ``frames[i][k]`` / ``outputs[i][q]`` are lists with one
     device tensor per stream of application i (length ``batch``).  Returns, per application, the
     list of per-frame result lists (one hs_result per stream), plus the number of frames dropped
-    because the queue was full."""
+    because the queue was full.  ``pin_cpus[i]``: CPU core the submitting thread of application
+    i pins itself to."""
     n_streams = len(streams)
     results = [[] for _ in range(n_streams)]
     dropped = [0] * n_streams
@@ -157,6 +159,8 @@ def run_paced(streams, frames, fps: float, outputs):
     def worker(i):
         s = streams[i]
         fr = frames[i]
+        if pin_cpus is not None:      # paper Section IV-C: one core per application's submitter
+            os.sched_setaffinity(0, {pin_cpus[i]})
         for k in range(n):
             deadline = t0 + k * period
             while True:

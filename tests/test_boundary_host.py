@@ -130,3 +130,23 @@ def test_no_gpu_means_loud_failure_not_fallback():
     with pytest.raises(hs.HsError) as ei:
         hs.hs_init(0)
     assert ei.value.status == hs.HS_E_DEVICE
+
+
+def test_mann_whitney_matches_oracle_and_rejects_empty(hs):
+    """hs_mann_whitney_u (rank sums with mid-ranks) against the oracle's pairwise definition."""
+    import oracle
+    rng = np.random.default_rng(11)
+    for n, m, shift, quant in ((30, 45, 0.0, None), (200, 150, 0.2, None), (120, 120, 0.05, 0.02),
+                               (7, 5, 2.0, 0.5), (4, 4, 0.0, 1.0)):
+        a = rng.normal(1.0 + shift, 0.25, n)
+        b = rng.normal(1.0, 0.25, m)
+        if quant:
+            a, b = np.round(a / quant) * quant, np.round(b / quant) * quant
+        got, ref = hs.hs_mann_whitney_u(a, b), oracle.mann_whitney_z(a, b)
+        assert got["u"] == ref["u"]
+        assert abs(got["z"] - ref["z"]) <= 1e-12 * max(1.0, abs(ref["z"]))
+        assert got["significant"] == ref["significant"]
+    same = hs.hs_mann_whitney_u([3.0, 3.0, 3.0], [3.0, 3.0])
+    assert same["u"] == 3.0 and same["z"] == 0.0 and not same["significant"]
+    with pytest.raises(hs.HsError):
+        hs.hs_mann_whitney_u([], [1.0])

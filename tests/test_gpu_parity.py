@@ -149,6 +149,10 @@ def test_reset_state_and_queue_semantics(hs, ctx):
                   net_h=96, blob=blob, palette=PAL, queue_depth=2)
     try:
         assert s.poll() is None                                  # nothing submitted yet
+        import os
+        hs.hs_set_cpu_affinity(s.app, sorted(os.sched_getaffinity(0))[0])   # completion thread
+        with pytest.raises(hs.HsError):
+            hs.hs_set_cpu_affinity(s.app, 1 << 20)
         d_in = s.upload_frame(frames[0])
         outs = [s.new_output() for _ in range(3)]
 
@@ -167,6 +171,7 @@ def test_reset_state_and_queue_semantics(hs, ctx):
         assert s.submit(d_in, outs[2], 12) == hs.HS_E_QUEUE_FULL
         assert s.wait().frame_id == 10 and s.wait().frame_id == 11
         assert s.poll() is None
+        hs.hs_set_cpu_affinity(s.app, -1)
     finally:
         s.close()
 

@@ -269,3 +269,43 @@ def test_glyph_table_shape_and_t_glyph():
     assert g.shape == (9, 7) and g.dtype == np.uint8 and int(g.max()) < 32
     assert g[0, 0] == 0b11111 and all(int(v) == 0b00100 for v in g[0, 1:])   # 'T'
     assert len({tuple(r) for r in g}) == 9                                    # all glyphs differ
+
+
+# ---- Mann-Whitney U (appendix "Additional Evaluation": |Z| > 1.96, two-tailed, 0.05) -------------
+def test_mann_whitney_closed_forms():
+    # complete separation: U = n*m (or 0); symmetric samples: U = n*m/2, z = 0
+    r = oracle.mann_whitney_z([5, 6, 7, 8], [1, 2, 3])
+    assert r["u"] == 12.0
+    assert oracle.mann_whitney_z([1, 2, 3], [5, 6, 7, 8])["u"] == 0.0
+    r = oracle.mann_whitney_z([1, 4], [2, 3])
+    assert r["u"] == 2.0 and r["z"] == 0.0 and not r["significant"]
+    # all values equal: every pair is a tie, no evidence either way
+    r = oracle.mann_whitney_z([3, 3, 3], [3, 3])
+    assert r["u"] == 3.0 and r["z"] == 0.0
+    # hand-computed, no ties: a = {1, 3, 5}, b = {2, 4}: pairs a>b: (3,2), (5,2), (5,4) -> U = 3,
+    # mu = 3, z = 0;  a = {4, 5, 6}, b = {1, 2, 3}: U = 9, mu = 4.5, var = 9*7/12 = 5.25
+    assert oracle.mann_whitney_z([1, 3, 5], [2, 4])["u"] == 3.0
+    r = oracle.mann_whitney_z([4, 5, 6], [1, 2, 3])
+    assert r["u"] == 9.0 and abs(r["z"] - (9 - 4.5 - 0.5) / math.sqrt(5.25)) < 1e-12
+    # antisymmetry
+    a, b = [0.31, 0.35, 0.33, 0.40, 0.31], [0.30, 0.31, 0.29, 0.36]
+    assert abs(oracle.mann_whitney_z(a, b)["z"] + oracle.mann_whitney_z(b, a)["z"]) < 1e-12
+    assert oracle.mann_whitney_z(a, b)["u"] + oracle.mann_whitney_z(b, a)["u"] == len(a) * len(b)
+
+
+def test_mann_whitney_against_scipy_asymptotic():
+    from scipy import stats
+    rng = np.random.default_rng(5)
+    for n, m, shift, quant in ((40, 55, 0.0, None), (120, 80, 0.3, None), (200, 200, 0.1, 0.05),
+                               (15, 9, 1.0, 0.5)):
+        a = rng.normal(1.0 + shift, 0.2, n)
+        b = rng.normal(1.0, 0.3, m)
+        if quant:                                  # quantised latencies: many ties
+            a, b = np.round(a / quant) * quant, np.round(b / quant) * quant
+        got = oracle.mann_whitney_z(a, b)
+        ref = stats.mannwhitneyu(a, b, alternative="two-sided", method="asymptotic",
+                                 use_continuity=True)
+        assert abs(got["u"] - ref.statistic) < 1e-9
+        p = 2.0 * stats.norm.sf(abs(got["z"]))
+        assert abs(p - ref.pvalue) <= 1e-12 + 1e-9 * ref.pvalue
+        assert got["significant"] == (ref.pvalue < 2.0 * stats.norm.sf(1.96))
