@@ -114,6 +114,12 @@ struct Slot {
   std::vector<Op> post;    // stage 3
   std::vector<Op> overlay; // stage 4: one launch, blockIdx.y = stream of the batch
   hipEvent_t ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr, ev_overlay = nullptr;
+  // Consecutive frames alternate between two lanes (activation sets + streams) and overlap;
+  // the recurrent cell is the only thing that chains them: its gate convolution (op wait_idx)
+  // waits for the previous frame's state update, whose kernel (op record_idx) is followed by a
+  // record of ev_state.  -1: the network has no recurrent state.
+  int lane = 0, wait_idx = -1, record_idx = -1;
+  hipEvent_t ev_state = nullptr;
   // stages 1-3 as one HIP graph (kernel nodes chained in order, event-record nodes at the
   // stage boundaries); only the frame pointer of the first node changes from frame to frame
   hipGraph_t graph = nullptr;
@@ -155,10 +161,13 @@ struct hs_app {
   bool stateful = false;
   // recurrent state
   float* d_c = nullptr;
-  f16* d_concat = nullptr;
+  f16* d_concat = nullptr;        // lane 0: [x_t ; h_{t-1}] of the frames that run in lane 0
+  f16* d_concat1 = nullptr;       // lane 1 (NULL with a single lane)
   int concat_pitch = 0, hid = 0, x_ch = 0;
-  // streams / partition
-  hipStream_t s_infer = nullptr, s_overlay = nullptr;
+  int lanes = 1;
+  // streams / partition: s_infer2 carries lane 1 (equal to s_infer when partitioned, so that a
+  // partition keeps to one hardware queue)
+  hipStream_t s_infer = nullptr, s_infer2 = nullptr, s_overlay = nullptr;
   bool partitioned = false;
   uint32_t claim[HS_MAX_CU_WORDS] = {0};
   // ring
@@ -228,6 +237,7 @@ struct Builder {
   std::vector<Op> ops;            // stage-2 ops; slot-dependent pointers are patched per slot
   int first_conv_op = -1;         // op whose conv.in is the slot's padded net input
   int logits_op = -1;             // op that writes the slot's logits
+  int lstm_conv_op = -1;          // gate convolution of the recurrent cell (-1: none)
   int map_h = 0, map_w = 0;
   bool stateful = false;
   float* d_c = nullptr;
@@ -508,6 +518,7 @@ struct Builder {
     cat.p = concat; cat.h = hf; cat.w = wf; cat.c = 768; cat.pitch = 768;
     Tensor gates;
     const int lstm_conv = conv_layer(cat, at, 1024, 3, 1, 1, false, nullptr, &gates, false, true);
+    lstm_conv_op = lstm_conv;
     at += (size_t)1024 * 768 * 9;
     // head weights: 8 x 256 fp16, plain [k][c]; the head runs inside the ConvLSTM epilogue
     const size_t w_off = reserve_w(2048);
@@ -622,18 +633,42 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   Builder b(*d, create ? d->d_workspace : nullptr, create, true);
   b.d_w = b.carve.take<f16>(sizing.w_halves);
   b.walk(ph, pw);
-  float* d_partial = b.carve.take<float>(b.partial_floats);
-  for (Op& op : b.ops) {
-    if (op.fam == F_CONV && op.conv.use_partial) {
-      op.conv.partial = d_partial;
-      if (op.conv.wt2) op.conv.partial2 = d_partial + (size_t)op.conv.nsplit * op.conv.m * op.conv.cout_pad;
+  auto bind_partial = [](Builder& bb) {
+    float* d_partial = bb.carve.take<float>(bb.partial_floats);
+    for (Op& op : bb.ops) {
+      if (op.fam == F_CONV && op.conv.use_partial) {
+        op.conv.partial = d_partial;
+        if (op.conv.wt2)
+          op.conv.partial2 = d_partial + (size_t)op.conv.nsplit * op.conv.m * op.conv.cout_pad;
+      }
+      if (op.fam == F_SPLITK) {
+        op.splitk.partial = d_partial;
+        if (op.splitk.out2)
+          op.splitk.partial2 =
+              d_partial + (size_t)op.splitk.nsplit * op.splitk.m * op.splitk.cout_pad;
+      }
+      if (op.fam == F_LSTM) op.lstm.partial = d_partial;
     }
-    if (op.fam == F_SPLITK) {
-      op.splitk.partial = d_partial;
-      if (op.splitk.out2)
-        op.splitk.partial2 = d_partial + (size_t)op.splitk.nsplit * op.splitk.m * op.splitk.cout_pad;
+  };
+  bind_partial(b);
+  // Second lane: the same plan over its own activations and scratch (weights shared), so that
+  // consecutive frames can overlap.  Needs an even queue depth (slot i runs in lane i % 2 and
+  // frames must alternate strictly).  The cell state c is shared; every lane's state update
+  // writes h where the OTHER lane's gate convolution reads it.
+  const int lanes = depth % 2 == 0 ? 2 : 1;
+  Builder b1(*d, create ? d->d_workspace : nullptr, false, true);
+  if (lanes == 2) {
+    b1.carve.off = b.carve.off;
+    b1.d_w = b.d_w;
+    b1.walk(ph, pw);
+    bind_partial(b1);
+    b.carve.off = b1.carve.off;
+    if (b.stateful) {
+      LstmEpilogueParams& l0 = b.ops[b.logits_op].lstm;
+      LstmEpilogueParams& l1 = b1.ops[b1.logits_op].lstm;
+      l1.c = l0.c;
+      std::swap(l0.h_out, l1.h_out);
     }
-    if (op.fam == F_LSTM) op.lstm.partial = d_partial;
   }
   float* d_lut32 = b.carve.take<float>(256);
   f16* d_lut16 = b.carve.take<f16>(256);
@@ -663,6 +698,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   }
   app->map_h = mh; app->map_w = mw; app->stateful = b.stateful; app->batch = B;
   app->d_c = b.d_c; app->d_concat = b.d_concat; app->concat_pitch = 768; app->hid = 256;
+  app->d_concat1 = lanes == 2 ? b1.d_concat : nullptr;
+  app->lanes = lanes;
   app->x_ch = 512;
 
   // upload weights and tables, zero the recurrent state and the padded borders
@@ -682,6 +719,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   if (app->stateful) {
     HS_HIP(hipMemset(app->d_c, 0, B * n_map * 256 * sizeof(float)));
     HS_HIP(hipMemset(app->d_concat, 0, B * n_map * 768 * sizeof(f16)));
+    if (app->d_concat1) HS_HIP(hipMemset(app->d_concat1, 0, B * n_map * 768 * sizeof(f16)));
   }
   HS_HIP(hipDeviceSynchronize());
 
@@ -725,7 +763,9 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
                      (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0));
       s.pre.push_back(r);
     }
-    s.infer = b.ops;
+    s.lane = lanes == 2 ? i % 2 : 0;
+    s.infer = s.lane ? b1.ops : b.ops;
+    if (b.stateful) { s.wait_idx = b.lstm_conv_op; s.record_idx = b.logits_op; }
     if (s.infer[b.first_conv_op].fam == F_STEM) s.infer[b.first_conv_op].stem.in = s.d_netin;
     else s.infer[b.first_conv_op].conv.in = s.d_netin;
     Op& lo = s.infer[b.logits_op];
@@ -771,6 +811,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     HS_HIP(hipEventCreate(&s.ev_infer));
     HS_HIP(hipEventCreate(&s.ev_post));
     HS_HIP(hipEventCreate(&s.ev_overlay));
+    HS_HIP(hipEventCreate(&s.ev_state));
   }
   return HS_OK;
 }
@@ -818,7 +859,7 @@ static void completer_main(hs_app* app) {
 }
 
 static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* mo, int n_words) {
-  hipStream_t si = nullptr, so = nullptr;
+  hipStream_t si = nullptr, so = nullptr, si2 = nullptr;
   if (mi && std::memcmp(mi, mo, sizeof(uint32_t) * (size_t)n_words) == 0) {
     // equal masks: one stream, i.e. one hardware queue, carries all four stages
     HS_HIP(hipExtStreamCreateWithCUMask(&si, (uint32_t)n_words, mi));
@@ -834,15 +875,20 @@ static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* m
   } else {
     HS_HIP(hipStreamCreateWithFlags(&si, hipStreamNonBlocking));
     hipError_t e = hipStreamCreateWithFlags(&so, hipStreamNonBlocking);
+    if (e == hipSuccess && app->lanes == 2) e = hipStreamCreateWithFlags(&si2, hipStreamNonBlocking);
     if (e != hipSuccess) {
       (void)hipStreamDestroy(si);
+      if (so) (void)hipStreamDestroy(so);
       set_error("hipStreamCreateWithFlags failed: %s", hipGetErrorString(e));
       return HS_E_DEVICE;
     }
   }
+  if (!si2) si2 = si;   // partitioned, or a single lane: both lanes in one queue, in order
   if (app->s_overlay && app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
+  if (app->s_infer2 && app->s_infer2 != app->s_infer) (void)hipStreamDestroy(app->s_infer2);
   if (app->s_infer) (void)hipStreamDestroy(app->s_infer);
   app->s_infer = si;
+  app->s_infer2 = si2;
   app->s_overlay = so;
   return HS_OK;
 }
@@ -867,8 +913,10 @@ static void collect_timing(hs_app* app) {
   app->timed.clear();
 }
 
-static hs_status run_ops(hs_app* app, std::vector<Op>& ops, hipStream_t st) {
-  for (Op& op : ops) {
+static hs_status run_ops(hs_app* app, std::vector<Op>& ops, hipStream_t st, size_t first = 0,
+                         size_t last = (size_t)-1) {
+  for (size_t i = first; i < std::min(last, ops.size()); ++i) {
+    Op& op = ops[i];
     if (app->timing) {
       TimedLaunch t{op.fam, op.flops, op.bytes, nullptr, nullptr};
       HS_HIP(hipEventCreate(&t.e0));
@@ -902,7 +950,8 @@ static hipKernelNodeParams node_params(Op& op, void** args) {
 
 // Stages 1-3 of one queue slot as a linear HIP graph: resize, [event], network kernels,
 // [event], postprocess.  Built once; per frame only the resize node's source pointer changes.
-static hs_status build_slot_graph(Slot& s) {
+// wait_ev: the previous slot's ev_state (the frame before this slot's frame ran there).
+static hs_status build_slot_graph(Slot& s, hipEvent_t wait_ev) {
   HS_HIP(hipGraphCreate(&s.graph, 0));
   hipGraphNode_t prev = nullptr;
   auto add_kernel = [&](Op& op, hipGraphNode_t* out) -> hipError_t {
@@ -923,7 +972,15 @@ static hs_status build_slot_graph(Slot& s) {
   s.resize_nodes.resize(s.pre.size());
   for (size_t j = 0; j < s.pre.size(); ++j) HS_HIP(add_kernel(s.pre[j], &s.resize_nodes[j]));
   HS_HIP(add_event(s.ev_pre));
-  for (Op& op : s.infer) HS_HIP(add_kernel(op, nullptr));
+  for (size_t j = 0; j < s.infer.size(); ++j) {
+    if ((int)j == s.wait_idx && wait_ev) {
+      hipGraphNode_t n = nullptr;
+      HS_HIP(hipGraphAddEventWaitNode(&n, s.graph, &prev, 1, wait_ev));
+      prev = n;
+    }
+    HS_HIP(add_kernel(s.infer[j], nullptr));
+    if ((int)j == s.record_idx) HS_HIP(add_event(s.ev_state));
+  }
   HS_HIP(add_event(s.ev_infer));
   for (Op& op : s.post) HS_HIP(add_kernel(op, nullptr));
   HS_HIP(hipGraphInstantiate(&s.graph_exec, s.graph, nullptr, nullptr, 0));
@@ -1020,7 +1077,11 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
   app->depth = desc->queue_depth;
   size_t need = 0;
   st = build_plan(desc, app, &need);
-  for (size_t i = 0; st == HS_OK && i < app->slots.size(); ++i) st = build_slot_graph(app->slots[i]);
+  for (size_t i = 0; st == HS_OK && i < app->slots.size(); ++i) {
+    const size_t n_slots = app->slots.size();
+    st = build_slot_graph(app->slots[i],
+                          n_slots > 1 ? app->slots[(i + n_slots - 1) % n_slots].ev_state : nullptr);
+  }
   if (st == HS_OK) st = make_streams(app, nullptr, nullptr, 0);
   if (st != HS_OK) {
     for (Slot& s : app->slots) {
@@ -1030,6 +1091,7 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
       if (s.ev_infer) (void)hipEventDestroy(s.ev_infer);
       if (s.ev_post) (void)hipEventDestroy(s.ev_post);
       if (s.ev_overlay) (void)hipEventDestroy(s.ev_overlay);
+      if (s.ev_state) (void)hipEventDestroy(s.ev_state);
     }
     if (app->pinned) (void)hipHostFree(app->pinned);
     delete app;
@@ -1054,6 +1116,7 @@ hs_status hs_destroy_app(hs_app* app) {
   app->cv_work.notify_all();
   if (app->completer.joinable()) app->completer.join();   // drains pending frames first
   (void)hipStreamSynchronize(app->s_infer);
+  (void)hipStreamSynchronize(app->s_infer2);
   (void)hipStreamSynchronize(app->s_overlay);
   collect_timing(app);
   for (Slot& s : app->slots) {
@@ -1063,8 +1126,10 @@ hs_status hs_destroy_app(hs_app* app) {
     (void)hipEventDestroy(s.ev_infer);
     (void)hipEventDestroy(s.ev_post);
     (void)hipEventDestroy(s.ev_overlay);
+    (void)hipEventDestroy(s.ev_state);
   }
   if (app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
+  if (app->s_infer2 != app->s_infer) (void)hipStreamDestroy(app->s_infer2);
   (void)hipStreamDestroy(app->s_infer);
   if (app->pinned) (void)hipHostFree(app->pinned);
   {
@@ -1076,6 +1141,13 @@ hs_status hs_destroy_app(hs_app* app) {
   return HS_OK;
 }
 
+// Lane the most recently submitted frame ran in (0 before the first frame).
+static int last_frame_lane(hs_app* app) {
+  std::lock_guard<std::mutex> lk(app->mu);
+  if (app->n_submitted == 0) return app->lanes == 2 ? 1 : 0;   // "next frame" = lane 0 either way
+  return app->slots[(app->n_submitted - 1) % app->depth].lane;
+}
+
 hs_status hs_reset_state(hs_app* app) {
   if (!app) { set_error("hs_reset_state: NULL"); return HS_E_INVAL; }
   if (frames_in_flight(app)) { set_error("hs_reset_state: frames in flight"); return HS_E_STATE; }
@@ -1084,6 +1156,8 @@ hs_status hs_reset_state(hs_app* app) {
   const size_t n = (size_t)app->map_w * app->map_h * app->batch;
   launch_fill_zero(app->d_c, n * app->hid * sizeof(float), app->s_infer);
   launch_fill_zero(app->d_concat, n * app->concat_pitch * sizeof(f16), app->s_infer);
+  if (app->d_concat1)
+    launch_fill_zero(app->d_concat1, n * app->concat_pitch * sizeof(f16), app->s_infer);
   HS_HIP(hipGetLastError());
   HS_HIP(hipStreamSynchronize(app->s_infer));
   return HS_OK;
@@ -1105,8 +1179,10 @@ hs_status hs_get_state(hs_app* app, int stream, float* h_out, float* c_out) {
       for (int j = 0; j < hid; ++j) c_out[(size_t)j * n + m] = tmp[m * hid + j];
   }
   if (h_out) {
+    // h of the last frame sits where the NEXT frame's gate convolution will read it
+    const f16* cat = app->lanes == 2 && last_frame_lane(app) == 0 ? app->d_concat1 : app->d_concat;
     std::vector<f16> tmp(n * app->concat_pitch);
-    HS_HIP(hipMemcpy(tmp.data(), app->d_concat + (size_t)stream * n * app->concat_pitch,
+    HS_HIP(hipMemcpy(tmp.data(), cat + (size_t)stream * n * app->concat_pitch,
                      tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
     for (size_t m = 0; m < n; ++m)
       for (int j = 0; j < hid; ++j)
@@ -1123,7 +1199,8 @@ hs_status hs_get_features(hs_app* app, int stream, float* x_out) {
   HS_HIP(hipSetDevice(app->ctx->device));
   const size_t n = (size_t)app->map_w * app->map_h;
   std::vector<f16> tmp(n * app->concat_pitch);
-  HS_HIP(hipMemcpy(tmp.data(), app->d_concat + (size_t)stream * n * app->concat_pitch,
+  const f16* cat = app->lanes == 2 && last_frame_lane(app) == 1 ? app->d_concat1 : app->d_concat;
+  HS_HIP(hipMemcpy(tmp.data(), cat + (size_t)stream * n * app->concat_pitch,
                    tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
   for (size_t m = 0; m < n; ++m)
     for (int j = 0; j < app->x_ch; ++j)
@@ -1231,22 +1308,35 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
   }
 
   hs_status st = HS_OK;
+  hipStream_t lane_stream = s->lane ? app->s_infer2 : app->s_infer;
   if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
     void* args[1];
     hipKernelNodeParams kp = node_params(s->pre[0], args);
     HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_nodes[0], &kp));
-    HS_HIP(hipGraphLaunch(s->graph_exec, app->s_infer));
+    HS_HIP(hipGraphLaunch(s->graph_exec, lane_stream));
   } else {
-    st = run_ops(app, s->pre, app->s_infer);
+    st = run_ops(app, s->pre, lane_stream);
     if (st != HS_OK) return st;
-    HS_HIP(hipEventRecord(s->ev_pre, app->s_infer));
-    st = run_ops(app, s->infer, app->s_infer);
+    HS_HIP(hipEventRecord(s->ev_pre, lane_stream));
+    if (s->wait_idx >= 0) {
+      // the recurrent cell waits for the previous frame's state update (other lane)
+      Slot& before = app->slots[(size_t)((s - app->slots.data()) + app->depth - 1) % app->depth];
+      st = run_ops(app, s->infer, lane_stream, 0, (size_t)s->wait_idx);
+      if (st != HS_OK) return st;
+      if (app->depth > 1) HS_HIP(hipStreamWaitEvent(lane_stream, before.ev_state, 0));
+      st = run_ops(app, s->infer, lane_stream, (size_t)s->wait_idx, (size_t)s->record_idx + 1);
+      if (st != HS_OK) return st;
+      HS_HIP(hipEventRecord(s->ev_state, lane_stream));
+      st = run_ops(app, s->infer, lane_stream, (size_t)s->record_idx + 1);
+    } else {
+      st = run_ops(app, s->infer, lane_stream);
+    }
     if (st != HS_OK) return st;
-    HS_HIP(hipEventRecord(s->ev_infer, app->s_infer));
-    st = run_ops(app, s->post, app->s_infer);
+    HS_HIP(hipEventRecord(s->ev_infer, lane_stream));
+    st = run_ops(app, s->post, lane_stream);
     if (st != HS_OK) return st;
   }
-  HS_HIP(hipEventRecord(s->ev_post, app->s_infer));
+  HS_HIP(hipEventRecord(s->ev_post, lane_stream));
   HS_HIP(hipStreamWaitEvent(app->s_overlay, s->ev_post, 0));
   st = run_ops(app, s->overlay, app->s_overlay);
   if (st != HS_OK) return st;

@@ -254,6 +254,50 @@ def test_config5_full_size_batch12_sampled_streams(hs, ctx):
         s.close()
 
 
+@pytest.mark.parametrize("mode", ["HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER"])
+def test_back_to_back_frames_overlap_and_match_one_at_a_time(hs, ctx, mode):
+    """Consecutive frames of one stream run in two lanes and may overlap on the GPU; only the
+    recurrent cell chains them.  Eight frames submitted as fast as the queue takes them must give,
+    frame by frame and bit for bit, what the same frames give when each is waited for before the
+    next is submitted, and the same final recurrent state."""
+    from paper_2402_04466_amd.harness import AppStream
+    T = 8
+    frames = list(si.tool_scene_frames(T, 360, 640, 17))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 2)
+    s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=640, frame_h=360, net_w=288,
+                  net_h=160, blob=blob, palette=PAL, queue_depth=4)
+    hs.hs_set_launch_mode(s.app, getattr(hs, mode))
+    try:
+        d_in = [s.upload_frame(f) for f in frames]
+        d_out = [s.new_output() for _ in range(T)]
+        ref = []
+        for t in range(T):                                   # one at a time
+            assert s.submit(d_in[t], d_out[t], t) == hs.HS_OK
+            r = s.wait()
+            ref.append(s.fetch(r, d_out[t]))
+        ref_h, ref_c = s.state(r)
+        ref_x = s.features(r)
+        hs.hs_reset_state(s.app)
+        for o in d_out:
+            o.zero_()
+        torch.cuda.synchronize()
+        got, sub = [], 0
+        while len(got) < T:                                   # as fast as the queue takes them
+            while sub < T and s.submit(d_in[sub], d_out[sub], sub) == hs.HS_OK:
+                sub += 1
+            r = s.wait()
+            assert r.frame_id == len(got)
+            got.append(s.fetch(r, d_out[len(got)]))
+        for t in range(T):
+            for k in ("logits", "mask", "argmax_idx", "overlay"):
+                assert np.array_equal(ref[t][k], got[t][k]), f"frame {t}: {k} differs"
+        h, c = s.state(r)
+        assert np.array_equal(h, ref_h) and np.array_equal(c, ref_c)
+        assert np.array_equal(s.features(r), ref_x)
+    finally:
+        s.close()
+
+
 def test_graph_and_kernel_by_kernel_launch_paths_agree(hs, ctx):
     """The pre-built HIP graph of stages 1-3 is replayed for several frames (with the host's
     own synchronisation and read-backs between replays) and must give, frame by frame and
