@@ -254,8 +254,9 @@ def test_config5_full_size_batch12_sampled_streams(hs, ctx):
         s.close()
 
 
-@pytest.mark.parametrize("mode", ["HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER"])
-def test_back_to_back_frames_overlap_and_match_one_at_a_time(hs, ctx, mode):
+@pytest.mark.parametrize("mode,depth", [("HS_LAUNCH_GRAPH", 4), ("HS_LAUNCH_EAGER", 4),
+                                        ("HS_LAUNCH_GRAPH", 2), ("HS_LAUNCH_GRAPH", 3)])
+def test_back_to_back_frames_overlap_and_match_one_at_a_time(hs, ctx, mode, depth):
     """Consecutive frames of one stream run in two lanes and may overlap on the GPU; only the
     recurrent cell chains them.  Eight frames submitted as fast as the queue takes them must give,
     frame by frame and bit for bit, what the same frames give when each is waited for before the
@@ -264,8 +265,9 @@ def test_back_to_back_frames_overlap_and_match_one_at_a_time(hs, ctx, mode):
     T = 8
     frames = list(si.tool_scene_frames(T, 360, 640, 17))
     blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 2)
+    # depth 3: an odd queue cannot alternate lanes strictly and runs in a single lane
     s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=640, frame_h=360, net_w=288,
-                  net_h=160, blob=blob, palette=PAL, queue_depth=4)
+                  net_h=160, blob=blob, palette=PAL, queue_depth=depth)
     hs.hs_set_launch_mode(s.app, getattr(hs, mode))
     try:
         d_in = [s.upload_frame(f) for f in frames]
