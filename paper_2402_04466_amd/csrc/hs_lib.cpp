@@ -165,6 +165,7 @@ struct hs_app {
   f16* d_concat1 = nullptr;       // lane 1 (NULL with a single lane)
   int concat_pitch = 0, hid = 0, x_ch = 0;
   int lanes = 1;
+  hipStream_t lane_last_stream[2] = {nullptr, nullptr};   // stream each lane's latest frame used
   // streams / partition: s_infer2 carries lane 1 (equal to s_infer when partitioned, so that a
   // partition keeps to one hardware queue)
   hipStream_t s_infer = nullptr, s_infer2 = nullptr, s_overlay = nullptr;
@@ -873,9 +874,11 @@ static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* m
       return HS_E_DEVICE;
     }
   } else {
+    // two lanes: the overlay follows its frame's stream (the lanes already overlap one frame's
+    // overlay with the next frame's first stages), so an application keeps to two streams
     HS_HIP(hipStreamCreateWithFlags(&si, hipStreamNonBlocking));
-    hipError_t e = hipStreamCreateWithFlags(&so, hipStreamNonBlocking);
-    if (e == hipSuccess && app->lanes == 2) e = hipStreamCreateWithFlags(&si2, hipStreamNonBlocking);
+    hipError_t e = app->lanes == 2 ? hipStreamCreateWithFlags(&si2, hipStreamNonBlocking)
+                                   : hipStreamCreateWithFlags(&so, hipStreamNonBlocking);
     if (e != hipSuccess) {
       (void)hipStreamDestroy(si);
       if (so) (void)hipStreamDestroy(so);
@@ -889,6 +892,7 @@ static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* m
   if (app->s_infer) (void)hipStreamDestroy(app->s_infer);
   app->s_infer = si;
   app->s_infer2 = si2;
+  app->lane_last_stream[0] = app->lane_last_stream[1] = nullptr;   // no frame is in flight here
   app->s_overlay = so;
   return HS_OK;
 }
@@ -1117,7 +1121,7 @@ hs_status hs_destroy_app(hs_app* app) {
   if (app->completer.joinable()) app->completer.join();   // drains pending frames first
   (void)hipStreamSynchronize(app->s_infer);
   (void)hipStreamSynchronize(app->s_infer2);
-  (void)hipStreamSynchronize(app->s_overlay);
+  if (app->s_overlay) (void)hipStreamSynchronize(app->s_overlay);
   collect_timing(app);
   for (Slot& s : app->slots) {
     if (s.graph_exec) (void)hipGraphExecDestroy(s.graph_exec);
@@ -1128,7 +1132,7 @@ hs_status hs_destroy_app(hs_app* app) {
     (void)hipEventDestroy(s.ev_overlay);
     (void)hipEventDestroy(s.ev_state);
   }
-  if (app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
+  if (app->s_overlay && app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
   if (app->s_infer2 != app->s_infer) (void)hipStreamDestroy(app->s_infer2);
   (void)hipStreamDestroy(app->s_infer);
   if (app->pinned) (void)hipHostFree(app->pinned);
@@ -1271,6 +1275,7 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
     if (d_frames[j] == d_overlay_outs[j]) { set_error("hs_submit_batch: output aliases input"); return HS_E_INVAL; }
   }
   Slot* s = nullptr;
+  bool idle = false;   // nothing in flight: this frame cannot overlap with an earlier one
   {
     std::lock_guard<std::mutex> lk(app->mu);
     if (!app->completer_error.empty()) {
@@ -1282,6 +1287,7 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
       return HS_E_QUEUE_FULL;
     }
     s = &app->slots[app->n_submitted % app->depth];
+    idle = app->n_completed == app->n_submitted;
   }
   HS_HIP(hipSetDevice(app->ctx->device));
   const size_t n_map = (size_t)app->map_w * app->map_h;
@@ -1308,7 +1314,16 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
   }
 
   hs_status st = HS_OK;
-  hipStream_t lane_stream = s->lane ? app->s_infer2 : app->s_infer;
+  // A frame that finds the application idle runs on the first stream whatever its lane (paced
+  // streams then use one queue, like a single-lane application); otherwise on its lane's stream,
+  // behind the lane's previous frame if that one ran elsewhere (they share activation buffers).
+  hipStream_t lane_stream = (idle || !s->lane) ? app->s_infer : app->s_infer2;
+  if (!idle && app->lane_last_stream[s->lane] && app->lane_last_stream[s->lane] != lane_stream &&
+      app->depth >= 2) {
+    Slot& same_lane = app->slots[(size_t)((s - app->slots.data()) + app->depth - 2) % app->depth];
+    HS_HIP(hipStreamWaitEvent(lane_stream, same_lane.ev_post, 0));
+  }
+  app->lane_last_stream[s->lane] = lane_stream;
   if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
     void* args[1];
     hipKernelNodeParams kp = node_params(s->pre[0], args);
@@ -1337,10 +1352,11 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
     if (st != HS_OK) return st;
   }
   HS_HIP(hipEventRecord(s->ev_post, lane_stream));
-  HS_HIP(hipStreamWaitEvent(app->s_overlay, s->ev_post, 0));
-  st = run_ops(app, s->overlay, app->s_overlay);
+  hipStream_t ov_stream = app->s_overlay ? app->s_overlay : lane_stream;
+  if (ov_stream != lane_stream) HS_HIP(hipStreamWaitEvent(ov_stream, s->ev_post, 0));
+  st = run_ops(app, s->overlay, ov_stream);
   if (st != HS_OK) return st;
-  HS_HIP(hipEventRecord(s->ev_overlay, app->s_overlay));
+  HS_HIP(hipEventRecord(s->ev_overlay, ov_stream));
   const uint64_t t_enq = now_ns();
   for (int j = 0; j < B; ++j) s->results[j].t_enqueued_ns = t_enq;
   {
