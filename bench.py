@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--partition-groups", type=int, default=0, metavar="G",
                     help="with --partition equal: CU groups (8 CUs, one per XCD) per application "
                          "instead of an equal share of the device; the last group serves the overlay")
+    ap.add_argument("--tiny-groups", type=int, default=0, metavar="G",
+                    help="with a partition and --tiny-apps: CU groups per small-network application; "
+                         "the other applications share the rest equally")
     ap.add_argument("--hog", type=int, default=0, metavar="K",
                     help="K extra applications that submit frames back to back during the paced "
                          "latency run (saturating neighbours, not counted in the latency figures); "
@@ -156,7 +159,21 @@ def main():
             tiny.append(s)
             tiny_frames.append([[s.upload_frame(f)] for f in si.uniform_frames(8, 240, 320, 50 + i)])
             tiny_outs.append([[s.new_output()] for _ in range(args.queue_depth)])
-    if args.partition != "none":
+    if args.partition != "none" and args.tiny_groups and tiny:
+        # unequal slices: G groups per small application, the rest split among the others
+        n_big = args.streams + args.hog
+        total_groups = n_cus // 8
+        big_groups = (total_groups - args.tiny_groups * len(tiny)) // max(n_big, 1)
+        if big_groups < 2 or args.tiny_groups < 2:
+            raise SystemExit("partition sizes do not fit (every application needs >= 2 CU groups)")
+        at = 0
+        for s in streams + hogs + tiny:
+            g = args.tiny_groups if s in tiny else big_groups
+            cus = list(range(at * 8, (at + g) * 8))
+            at += g
+            ci, co = (cus, cus) if args.partition == "equal-shared" else (cus[:-8], cus[-8:])
+            hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+    elif args.partition != "none":
         for s, (ci, co) in zip(streams + tiny + hogs,
                                equal_partitions(n_cus, args.streams + args.tiny_apps + args.hog,
                                                 groups_per_app=args.partition_groups)):
@@ -353,7 +370,7 @@ def main():
                    "streams": args.streams, "batch": args.batch, "partition": args.partition,
                    "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
-                   "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "annotate": bool(args.annotate), "device_cus": n_cus},
+                   "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "tiny_groups": args.tiny_groups, "annotate": bool(args.annotate), "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),
