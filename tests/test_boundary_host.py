@@ -150,3 +150,14 @@ def test_mann_whitney_matches_oracle_and_rejects_empty(hs):
     assert same["u"] == 3.0 and same["z"] == 0.0 and not same["significant"]
     with pytest.raises(hs.HsError):
         hs.hs_mann_whitney_u([], [1.0])
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more must exit with a message, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""

@@ -379,6 +379,19 @@ def test_partition_admission_and_masked_results_identical(hs, ctx):
         b.close()
 
 
+def test_device_copy_kernel(hs, ctx):
+    """The plain copy kernel that byte counters are calibrated against: exact, ragged sizes too."""
+    for nbytes in (16, 4096 + 16, 3 * 1024 * 1024 + 48):
+        a = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda:0")
+        b = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        hs.hs_device_copy(ctx, b.data_ptr(), a.data_ptr(), nbytes)
+        torch.cuda.synchronize()
+        assert torch.equal(b[:nbytes], a) and int(b[nbytes:].sum()) == 0
+    with pytest.raises(hs.HsError):
+        hs.hs_device_copy(ctx, 256, 512, 24)          # not a multiple of 16
+
+
 def test_kernel_timing_reports_every_family(hs, ctx):
     from paper_2402_04466_amd.harness import AppStream
     frames = list(si.uniform_frames(1, 240, 320, 2))
