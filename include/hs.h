@@ -83,7 +83,10 @@ typedef struct {
                             /* [Cout][Cin][kh][kw]; copied and repacked to fp16 at create */
   size_t weight_floats;     /* number of floats in the blob; must match the network      */
   uint8_t palette[HS_NUM_TOOLS][3]; /* overlay colour per tool channel, RGB              */
-  int queue_depth;          /* frames (batches) that may be in flight or unpolled, 1..64 */
+  int queue_depth;          /* frames (batches) that may be in flight or unpolled, 1..64. */
+                            /* With an even depth consecutive frames run in two lanes (own */
+                            /* activation buffers and stream) and overlap on the GPU; only */
+                            /* the recurrent cell chains them. Results do not depend on it. */
   int batch;                /* streams served by this application, 1..16. With batch > 1  */
                             /* the streams share one weight copy and every submit carries */
                             /* one frame of each stream; stages 1, 3, 4 run per stream,   */

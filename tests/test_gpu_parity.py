@@ -300,6 +300,39 @@ def test_back_to_back_frames_overlap_and_match_one_at_a_time(hs, ctx, mode, dept
         s.close()
 
 
+def test_long_back_to_back_run_is_deterministic(hs, ctx):
+    """96 frames as fast as the queue takes them, twice from a reset state: every frame's logits
+    and the final recurrent state must repeat exactly (no race between overlapping frames)."""
+    from paper_2402_04466_amd.harness import AppStream
+    T = 96
+    frames = list(si.tool_scene_frames(8, 360, 640, 23))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 3)
+    s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=640, frame_h=360, net_w=288,
+                  net_h=160, blob=blob, palette=PAL, queue_depth=4)
+    try:
+        d_in = [s.upload_frame(f) for f in frames]
+        d_out = [s.new_output() for _ in range(4)]
+
+        def run():
+            got, sub = [], 0
+            while len(got) < T:
+                while sub < T and s.submit(d_in[sub % 8], d_out[sub % 4], sub) == hs.HS_OK:
+                    sub += 1
+                r = s.wait()
+                assert r.frame_id == len(got)
+                got.append(s.fetch(r)["logits"].copy())
+            return got, s.state(r)
+        a, (ha, ca) = run()
+        hs.hs_reset_state(s.app)
+        b, (hb, cb) = run()
+        for t in range(T):
+            assert np.array_equal(a[t], b[t]), f"frame {t} differs between the two runs"
+        assert np.array_equal(ha, hb) and np.array_equal(ca, cb)
+        assert not np.array_equal(a[0], a[8])     # same input, different state: the cell is live
+    finally:
+        s.close()
+
+
 def test_graph_and_kernel_by_kernel_launch_paths_agree(hs, ctx):
     """The pre-built HIP graph of stages 1-3 is replayed for several frames (with the host's
     own synchronisation and read-backs between replays) and must give, frame by frame and
