@@ -10,6 +10,7 @@
 #include <cmath>
 #include <condition_variable>
 #include <cstring>
+#include <memory>
 #include <mutex>
 #include <string>
 #include <thread>
@@ -107,6 +108,9 @@ struct Tensor {
 };
 
 enum SlotState { SLOT_FREE = 0, SLOT_INFLIGHT = 1, SLOT_DONE = 2 };
+// Two lanes: with more frames in flight the submitting host thread (one graph launch per frame,
+// about 75 us) is the limit, not the GPU (four lanes were measured: no gain).
+constexpr int kMaxLanes = 2;
 
 struct Slot {
   std::vector<Op> pre;     // stage 1: one launch, blockIdx.y = stream of the batch
@@ -114,7 +118,7 @@ struct Slot {
   std::vector<Op> post;    // stage 3
   std::vector<Op> overlay; // stage 4: one launch, blockIdx.y = stream of the batch
   hipEvent_t ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr, ev_overlay = nullptr;
-  // Consecutive frames alternate between two lanes (activation sets + streams) and overlap;
+  // Consecutive frames rotate over the lanes (activation sets + streams) and overlap;
   // the recurrent cell is the only thing that chains them: its gate convolution (op wait_idx)
   // waits for the previous frame's state update, whose kernel (op record_idx) is followed by a
   // record of ev_state.  -1: the network has no recurrent state.
@@ -161,14 +165,15 @@ struct hs_app {
   bool stateful = false;
   // recurrent state
   float* d_c = nullptr;
-  f16* d_concat = nullptr;        // lane 0: [x_t ; h_{t-1}] of the frames that run in lane 0
-  f16* d_concat1 = nullptr;       // lane 1 (NULL with a single lane)
+  f16* d_concat[kMaxLanes] = {nullptr};   // per lane: [x_t ; h_{t-1}] of the frames that run there
   int concat_pitch = 0, hid = 0, x_ch = 0;
   int lanes = 1;
-  hipStream_t lane_last_stream[2] = {nullptr, nullptr};   // stream each lane's latest frame used
-  // streams / partition: s_infer2 carries lane 1 (equal to s_infer when partitioned, so that a
-  // partition keeps to one hardware queue)
-  hipStream_t s_infer = nullptr, s_infer2 = nullptr, s_overlay = nullptr;
+  hipStream_t lane_last_stream[kMaxLanes] = {nullptr};   // stream each lane's latest frame used
+  // streams / partition: s_lane[i] carries lane i (all equal to s_lane[0] when partitioned, so
+  // that a partition keeps to one hardware queue); s_overlay is NULL when the overlay follows
+  // its frame's lane stream
+  hipStream_t s_lane[kMaxLanes] = {nullptr};
+  hipStream_t s_overlay = nullptr;
   bool partitioned = false;
   uint32_t claim[HS_MAX_CU_WORDS] = {0};
   // ring
@@ -652,23 +657,32 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     }
   };
   bind_partial(b);
-  // Second lane: the same plan over its own activations and scratch (weights shared), so that
-  // consecutive frames can overlap.  Needs an even queue depth (slot i runs in lane i % 2 and
-  // frames must alternate strictly).  The cell state c is shared; every lane's state update
-  // writes h where the OTHER lane's gate convolution reads it.
-  const int lanes = depth % 2 == 0 ? 2 : 1;
-  Builder b1(*d, create ? d->d_workspace : nullptr, false, true);
-  if (lanes == 2) {
-    b1.carve.off = b.carve.off;
-    b1.d_w = b.d_w;
-    b1.walk(ph, pw);
-    bind_partial(b1);
-    b.carve.off = b1.carve.off;
+  // Further lanes: the same plan over their own activations and scratch (weights shared), so
+  // that consecutive frames can overlap.  Slot i runs in lane i % lanes and frames must rotate
+  // strictly, hence lanes divides the queue depth.  The cell state c is shared; a lane's state
+  // update writes h where the NEXT lane's gate convolution reads it.
+  const int lanes = depth % kMaxLanes == 0 ? kMaxLanes : 1;
+  std::vector<std::unique_ptr<Builder>> extra;
+  std::vector<Builder*> lane_b{&b};
+  for (int l = 1; l < lanes; ++l) {
+    extra.emplace_back(new Builder(*d, create ? d->d_workspace : nullptr, false, true));
+    Builder& bl = *extra.back();
+    bl.carve.off = lane_b.back()->carve.off;
+    bl.d_w = b.d_w;
+    bl.walk(ph, pw);
+    bind_partial(bl);
+    lane_b.push_back(&bl);
+  }
+  if (lanes > 1) {
+    b.carve.off = lane_b.back()->carve.off;
     if (b.stateful) {
-      LstmEpilogueParams& l0 = b.ops[b.logits_op].lstm;
-      LstmEpilogueParams& l1 = b1.ops[b1.logits_op].lstm;
-      l1.c = l0.c;
-      std::swap(l0.h_out, l1.h_out);
+      std::vector<f16*> own_h(lanes);
+      for (int l = 0; l < lanes; ++l) own_h[l] = lane_b[l]->ops[b.logits_op].lstm.h_out;
+      for (int l = 0; l < lanes; ++l) {
+        LstmEpilogueParams& ll = lane_b[l]->ops[b.logits_op].lstm;
+        ll.c = b.ops[b.logits_op].lstm.c;
+        ll.h_out = own_h[(l + 1) % lanes];
+      }
     }
   }
   float* d_lut32 = b.carve.take<float>(256);
@@ -698,8 +712,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     return HS_E_NOMEM;
   }
   app->map_h = mh; app->map_w = mw; app->stateful = b.stateful; app->batch = B;
-  app->d_c = b.d_c; app->d_concat = b.d_concat; app->concat_pitch = 768; app->hid = 256;
-  app->d_concat1 = lanes == 2 ? b1.d_concat : nullptr;
+  app->d_c = b.d_c; app->concat_pitch = 768; app->hid = 256;
+  for (int l = 0; l < lanes; ++l) app->d_concat[l] = lane_b[l]->d_concat;
   app->lanes = lanes;
   app->x_ch = 512;
 
@@ -719,8 +733,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     HS_HIP(hipMemset(sb[i].netin, 0, (size_t)B * ph * pw * 4 * sizeof(f16)));
   if (app->stateful) {
     HS_HIP(hipMemset(app->d_c, 0, B * n_map * 256 * sizeof(float)));
-    HS_HIP(hipMemset(app->d_concat, 0, B * n_map * 768 * sizeof(f16)));
-    if (app->d_concat1) HS_HIP(hipMemset(app->d_concat1, 0, B * n_map * 768 * sizeof(f16)));
+    for (int l = 0; l < lanes; ++l)
+      HS_HIP(hipMemset(app->d_concat[l], 0, B * n_map * 768 * sizeof(f16)));
   }
   HS_HIP(hipDeviceSynchronize());
 
@@ -764,8 +778,8 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
                      (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0));
       s.pre.push_back(r);
     }
-    s.lane = lanes == 2 ? i % 2 : 0;
-    s.infer = s.lane ? b1.ops : b.ops;
+    s.lane = i % lanes;
+    s.infer = lane_b[s.lane]->ops;
     if (b.stateful) { s.wait_idx = b.lstm_conv_op; s.record_idx = b.logits_op; }
     if (s.infer[b.first_conv_op].fam == F_STEM) s.infer[b.first_conv_op].stem.in = s.d_netin;
     else s.infer[b.first_conv_op].conv.in = s.d_netin;
@@ -859,40 +873,49 @@ static void completer_main(hs_app* app) {
   }
 }
 
+static void destroy_streams(hs_app* app) {
+  if (app->s_overlay && app->s_overlay != app->s_lane[0]) (void)hipStreamDestroy(app->s_overlay);
+  for (int l = kMaxLanes - 1; l >= 0; --l)
+    if (app->s_lane[l] && (l == 0 || app->s_lane[l] != app->s_lane[0]))
+      (void)hipStreamDestroy(app->s_lane[l]);
+  for (int l = 0; l < kMaxLanes; ++l) app->s_lane[l] = nullptr;
+  app->s_overlay = nullptr;
+}
+
 static hs_status make_streams(hs_app* app, const uint32_t* mi, const uint32_t* mo, int n_words) {
-  hipStream_t si = nullptr, so = nullptr, si2 = nullptr;
+  hipStream_t sl[kMaxLanes] = {nullptr};
+  hipStream_t so = nullptr;
+  hipError_t e = hipSuccess;
   if (mi && std::memcmp(mi, mo, sizeof(uint32_t) * (size_t)n_words) == 0) {
-    // equal masks: one stream, i.e. one hardware queue, carries all four stages
-    HS_HIP(hipExtStreamCreateWithCUMask(&si, (uint32_t)n_words, mi));
-    so = si;
+    // equal masks: one stream, i.e. one hardware queue, carries all four stages of every lane
+    e = hipExtStreamCreateWithCUMask(&sl[0], (uint32_t)n_words, mi);
+    so = sl[0];
   } else if (mi) {
-    HS_HIP(hipExtStreamCreateWithCUMask(&si, (uint32_t)n_words, mi));
-    hipError_t e = hipExtStreamCreateWithCUMask(&so, (uint32_t)n_words, mo);
-    if (e != hipSuccess) {
-      (void)hipStreamDestroy(si);
-      set_error("hipExtStreamCreateWithCUMask failed: %s", hipGetErrorString(e));
-      return HS_E_DEVICE;
-    }
+    e = hipExtStreamCreateWithCUMask(&sl[0], (uint32_t)n_words, mi);
+    if (e == hipSuccess) e = hipExtStreamCreateWithCUMask(&so, (uint32_t)n_words, mo);
+  } else if (app->lanes > 1) {
+    // the overlay follows its frame's stream (the lanes already overlap one frame's overlay
+    // with the next frame's first stages): lanes streams per application, no more
+    for (int l = 0; l < app->lanes && e == hipSuccess; ++l)
+      e = hipStreamCreateWithFlags(&sl[l], hipStreamNonBlocking);
   } else {
-    // two lanes: the overlay follows its frame's stream (the lanes already overlap one frame's
-    // overlay with the next frame's first stages), so an application keeps to two streams
-    HS_HIP(hipStreamCreateWithFlags(&si, hipStreamNonBlocking));
-    hipError_t e = app->lanes == 2 ? hipStreamCreateWithFlags(&si2, hipStreamNonBlocking)
-                                   : hipStreamCreateWithFlags(&so, hipStreamNonBlocking);
-    if (e != hipSuccess) {
-      (void)hipStreamDestroy(si);
-      if (so) (void)hipStreamDestroy(so);
-      set_error("hipStreamCreateWithFlags failed: %s", hipGetErrorString(e));
-      return HS_E_DEVICE;
-    }
+    e = hipStreamCreateWithFlags(&sl[0], hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&so, hipStreamNonBlocking);
   }
-  if (!si2) si2 = si;   // partitioned, or a single lane: both lanes in one queue, in order
-  if (app->s_overlay && app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
-  if (app->s_infer2 && app->s_infer2 != app->s_infer) (void)hipStreamDestroy(app->s_infer2);
-  if (app->s_infer) (void)hipStreamDestroy(app->s_infer);
-  app->s_infer = si;
-  app->s_infer2 = si2;
-  app->lane_last_stream[0] = app->lane_last_stream[1] = nullptr;   // no frame is in flight here
+  if (e != hipSuccess) {
+    for (int l = 0; l < kMaxLanes; ++l)
+      if (sl[l]) (void)hipStreamDestroy(sl[l]);
+    if (so && so != sl[0]) (void)hipStreamDestroy(so);
+    set_error("creating the application's streams failed: %s", hipGetErrorString(e));
+    return HS_E_DEVICE;
+  }
+  for (int l = 1; l < kMaxLanes; ++l)
+    if (!sl[l]) sl[l] = sl[0];   // partitioned, or fewer lanes: in one queue, in order
+  destroy_streams(app);
+  for (int l = 0; l < kMaxLanes; ++l) {
+    app->s_lane[l] = sl[l];
+    app->lane_last_stream[l] = nullptr;   // no frame is in flight here
+  }
   app->s_overlay = so;
   return HS_OK;
 }
@@ -1119,8 +1142,8 @@ hs_status hs_destroy_app(hs_app* app) {
   }
   app->cv_work.notify_all();
   if (app->completer.joinable()) app->completer.join();   // drains pending frames first
-  (void)hipStreamSynchronize(app->s_infer);
-  (void)hipStreamSynchronize(app->s_infer2);
+  for (int l = 0; l < kMaxLanes; ++l)
+    if (app->s_lane[l]) (void)hipStreamSynchronize(app->s_lane[l]);
   if (app->s_overlay) (void)hipStreamSynchronize(app->s_overlay);
   collect_timing(app);
   for (Slot& s : app->slots) {
@@ -1132,9 +1155,7 @@ hs_status hs_destroy_app(hs_app* app) {
     (void)hipEventDestroy(s.ev_overlay);
     (void)hipEventDestroy(s.ev_state);
   }
-  if (app->s_overlay && app->s_overlay != app->s_infer) (void)hipStreamDestroy(app->s_overlay);
-  if (app->s_infer2 != app->s_infer) (void)hipStreamDestroy(app->s_infer2);
-  (void)hipStreamDestroy(app->s_infer);
+  destroy_streams(app);
   if (app->pinned) (void)hipHostFree(app->pinned);
   {
     std::lock_guard<std::mutex> lk(app->ctx->mu);
@@ -1148,7 +1169,7 @@ hs_status hs_destroy_app(hs_app* app) {
 // Lane the most recently submitted frame ran in (0 before the first frame).
 static int last_frame_lane(hs_app* app) {
   std::lock_guard<std::mutex> lk(app->mu);
-  if (app->n_submitted == 0) return app->lanes == 2 ? 1 : 0;   // "next frame" = lane 0 either way
+  if (app->n_submitted == 0) return app->lanes - 1;   // so that the "next" lane is lane 0
   return app->slots[(app->n_submitted - 1) % app->depth].lane;
 }
 
@@ -1158,12 +1179,11 @@ hs_status hs_reset_state(hs_app* app) {
   if (!app->stateful) return HS_OK;
   HS_HIP(hipSetDevice(app->ctx->device));
   const size_t n = (size_t)app->map_w * app->map_h * app->batch;
-  launch_fill_zero(app->d_c, n * app->hid * sizeof(float), app->s_infer);
-  launch_fill_zero(app->d_concat, n * app->concat_pitch * sizeof(f16), app->s_infer);
-  if (app->d_concat1)
-    launch_fill_zero(app->d_concat1, n * app->concat_pitch * sizeof(f16), app->s_infer);
+  launch_fill_zero(app->d_c, n * app->hid * sizeof(float), app->s_lane[0]);
+  for (int l = 0; l < app->lanes; ++l)
+    launch_fill_zero(app->d_concat[l], n * app->concat_pitch * sizeof(f16), app->s_lane[0]);
   HS_HIP(hipGetLastError());
-  HS_HIP(hipStreamSynchronize(app->s_infer));
+  HS_HIP(hipStreamSynchronize(app->s_lane[0]));
   return HS_OK;
 }
 
@@ -1184,7 +1204,7 @@ hs_status hs_get_state(hs_app* app, int stream, float* h_out, float* c_out) {
   }
   if (h_out) {
     // h of the last frame sits where the NEXT frame's gate convolution will read it
-    const f16* cat = app->lanes == 2 && last_frame_lane(app) == 0 ? app->d_concat1 : app->d_concat;
+    const f16* cat = app->d_concat[(last_frame_lane(app) + 1) % app->lanes];
     std::vector<f16> tmp(n * app->concat_pitch);
     HS_HIP(hipMemcpy(tmp.data(), cat + (size_t)stream * n * app->concat_pitch,
                      tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
@@ -1203,7 +1223,7 @@ hs_status hs_get_features(hs_app* app, int stream, float* x_out) {
   HS_HIP(hipSetDevice(app->ctx->device));
   const size_t n = (size_t)app->map_w * app->map_h;
   std::vector<f16> tmp(n * app->concat_pitch);
-  const f16* cat = app->lanes == 2 && last_frame_lane(app) == 1 ? app->d_concat1 : app->d_concat;
+  const f16* cat = app->d_concat[last_frame_lane(app)];
   HS_HIP(hipMemcpy(tmp.data(), cat + (size_t)stream * n * app->concat_pitch,
                    tmp.size() * sizeof(f16), hipMemcpyDeviceToHost));
   for (size_t m = 0; m < n; ++m)
@@ -1317,10 +1337,11 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
   // A frame that finds the application idle runs on the first stream whatever its lane (paced
   // streams then use one queue, like a single-lane application); otherwise on its lane's stream,
   // behind the lane's previous frame if that one ran elsewhere (they share activation buffers).
-  hipStream_t lane_stream = (idle || !s->lane) ? app->s_infer : app->s_infer2;
+  hipStream_t lane_stream = idle ? app->s_lane[0] : app->s_lane[s->lane];
   if (!idle && app->lane_last_stream[s->lane] && app->lane_last_stream[s->lane] != lane_stream &&
-      app->depth >= 2) {
-    Slot& same_lane = app->slots[(size_t)((s - app->slots.data()) + app->depth - 2) % app->depth];
+      app->depth >= app->lanes) {
+    Slot& same_lane =
+        app->slots[(size_t)((s - app->slots.data()) + app->depth - app->lanes) % app->depth];
     HS_HIP(hipStreamWaitEvent(lane_stream, same_lane.ev_post, 0));
   }
   app->lane_last_stream[s->lane] = lane_stream;
