@@ -69,6 +69,9 @@ def parse():
                     help="overlay also draws argmax markers and tool labels (off in the headline "
                          "workload)")
     ap.add_argument("--paced-frames", type=int, default=60)
+    ap.add_argument("--repeats", type=int, default=1,
+                    help="repeat the paced latency run this many times (state reset in between) "
+                         "and pool the trimmed latencies, as the paper pools its repeated runs")
     ap.add_argument("--distinct-frames", type=int, default=8)
     ap.add_argument("--queue-depth", type=int, default=4)
     ap.add_argument("--launch-mode", choices=["graph", "eager"], default="graph",
@@ -245,28 +248,32 @@ def main():
             hs.hs_set_cpu_affinity(s.app, cores[(2 * i + 1) % len(cores)])
     tiny_paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
                   for f in tiny_frames]
-    results, dropped = run_paced(streams + tiny, paced + tiny_paced, args.fps, outs + tiny_outs,
-                                 pin_cpus=pins)
-    tiny_results, results = results[len(streams):], results[:len(streams)]
-    tiny_m = None
-    if tiny:
-        tl = []
+    lat_ms, tl, dropped, results = [], [], [], []
+    for rep in range(max(1, args.repeats)):
+        if rep:
+            for s in streams + tiny:
+                hs.hs_reset_state(s.app)
+        res_all, drop = run_paced(streams + tiny, paced + tiny_paced, args.fps, outs + tiny_outs,
+                                  pin_cpus=pins)
+        dropped.extend(drop)
+        tiny_results, results = res_all[len(streams):], res_all[:len(streams)]
         for rs in tiny_results:
             per = [(r[0].t_overlay_done_ns - r[0].t_submit_ns) / 1e6 for r in rs]
             t = min(10, len(per) // 6)
             tl.extend(per[t:len(per) - t])
+        for rs in results:
+            for j in range(args.batch):
+                per = [(r[j].t_overlay_done_ns - r[j].t_submit_ns) / 1e6 for r in rs]
+                t = min(10, len(per) // 6)
+                lat_ms.extend(per[t:len(per) - t])   # trim each stream's warm-up / cool-down
+    tiny_m = None
+    if tiny:
         tm = hs.hs_latency_metrics_compute(tl, trim=False)
         tiny_m = {k: (int(v) if k == "n" else round(v, 4)) for k, v in tm.items()}
     hog_stop.set()
     for t in hog_threads:
         t.join()
     t_hog = time.perf_counter() - t_hog
-    lat_ms = []
-    for rs in results:
-        for j in range(args.batch):
-            per = [(r[j].t_overlay_done_ns - r[j].t_submit_ns) / 1e6 for r in rs]
-            t = min(10, len(per) // 6)
-            lat_ms.extend(per[t:len(per) - t])   # trim each stream's warm-up / cool-down
     m = hs.hs_latency_metrics_compute(lat_ms, trim=False)
     mwu = None
     if args.compare_latencies:
@@ -371,7 +378,7 @@ def main():
                    "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
                    "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "tiny_groups": args.tiny_groups, "annotate": bool(args.annotate), "device_cus": n_cus},
-        "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]),
+        "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]), "repeats": max(1, args.repeats),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),
                        "std": round(m["std"], 4), "tail": round(m["tail"], 4),
