@@ -23,9 +23,9 @@ from .postprocess import postprocess, logit_threshold
 from .overlay import overlay, alpha_q8
 from .annotate import annotate, anchor
 from .metrics import determinism_metrics, trim_count, mann_whitney_z
-from .pipeline import OracleApp
+from .pipeline import OracleApp, OracleGroup, draw_layer
 
 __all__ = ["resize_bilinear_u8", "normalize_lut", "preprocess", "conv2d", "maxpool2d",
            "relu", "sigmoid", "Tiny4Net", "ResNet18ConvLSTMNet", "convlstm_step",
            "split_blob", "basic_block", "postprocess", "logit_threshold", "overlay", "alpha_q8", "annotate", "anchor",
-           "determinism_metrics", "trim_count", "mann_whitney_z", "OracleApp"]
+           "determinism_metrics", "trim_count", "mann_whitney_z", "OracleApp", "OracleGroup", "draw_layer"]

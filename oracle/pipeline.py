@@ -43,3 +43,35 @@ class OracleApp:
         if hasattr(self.net, "h") and self.net.h is not None:
             res["h"], res["c"] = self.net.h, self.net.c
         return res
+
+
+class OracleGroup:
+    """A multi-network application (paper Section III-B): every member network looks at the
+    same frame, each through its own format conversion, inference and postprocess, and ONE
+    visualisation draws all their layers over the original frame.  Reading taken here for
+    "renders the aggregated overlaid layers": layers are drawn in member order, each member's
+    mask blend followed by its annotations, every layer on top of the picture left by the
+    layer before it (ordinary back-to-front compositing)."""
+
+    def __init__(self, members):
+        self.members = list(members)
+
+    def reset(self):
+        for m in self.members:
+            m.reset()
+
+    def process(self, frame: np.ndarray) -> dict:
+        per_member = [m.process(frame) for m in self.members]   # each on the ORIGINAL frame
+        out = np.array(frame, dtype=np.uint8, copy=True)
+        for m, r in zip(self.members, per_member):
+            out = draw_layer(out, r["mask"], r["argmax_idx"], r["present"], m)
+        return {"members": per_member, "overlay": out}
+
+
+def draw_layer(img: np.ndarray, mask, argmax_idx, present, member: OracleApp) -> np.ndarray:
+    """One member's layer over img: its mask blend, then its annotations if it has any."""
+    out = overlay(img, mask, member.palette, member.alpha)
+    if member.glyphs is not None:
+        out = annotate(out, argmax_idx, present, mask.shape[2], mask.shape[1], member.palette,
+                       member.glyphs, *member.marker)
+    return out
