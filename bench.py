@@ -68,6 +68,10 @@ def parse():
     ap.add_argument("--annotate", action="store_true",
                     help="overlay also draws argmax markers and tool labels (off in the headline "
                          "workload)")
+    ap.add_argument("--group-nets", type=int, default=1, metavar="N",
+                    help="every application runs N networks side by side on each frame and draws "
+                         "their layers in one overlay launch (the paper's multi-network "
+                         "application, Section III-B); needs --batch 1")
     ap.add_argument("--paced-frames", type=int, default=60)
     ap.add_argument("--repeats", type=int, default=1,
                     help="repeat the paced latency run this many times (state reset in between) "
@@ -112,7 +116,7 @@ def main():
     import numpy as np
     import torch
     import paper_2402_04466_amd as hs
-    from paper_2402_04466_amd.harness import AppStream, run_paced
+    from paper_2402_04466_amd.harness import AppStream, GroupStream, run_paced
     import synth_inputs as si
 
     FW, FH, NW, NH = 1920, 1080, 854, 480
@@ -127,14 +131,28 @@ def main():
             hs.hs_device_copy(ctx, b.data_ptr(), a.data_ptr(), nbytes)
         del a, b
     blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    grouped = args.group_nets > 1
+    if grouped and args.batch != 1:
+        raise SystemExit("--group-nets needs --batch 1")
+
+    def apps_of(s):
+        """The library applications behind one benchmark stream."""
+        return [m.app for m in s.members] if isinstance(s, GroupStream) else [s.app]
+
     streams, frames = [], []
     for i in range(args.streams):
-        s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW,
-                      net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
-                      queue_depth=args.queue_depth, batch=args.batch,
-                      glyphs=si.DEFAULT_GLYPHS if args.annotate else None)
-        hs.hs_set_launch_mode(s.app, hs.HS_LAUNCH_GRAPH if args.launch_mode == "graph"
-                              else hs.HS_LAUNCH_EAGER)
+        members = []
+        for j in range(args.group_nets):
+            # members of a group differ in weights (seed) and colours, not in architecture
+            members.append(AppStream(
+                ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=FW, frame_h=FH, net_w=NW, net_h=NH,
+                blob=blob if j == 0 else si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1 + j),
+                palette=np.roll(si.DEFAULT_PALETTE, j, axis=0).copy(),
+                queue_depth=args.queue_depth, batch=args.batch,
+                glyphs=si.DEFAULT_GLYPHS if args.annotate else None))
+            hs.hs_set_launch_mode(members[-1].app, hs.HS_LAUNCH_GRAPH
+                                  if args.launch_mode == "graph" else hs.HS_LAUNCH_EAGER)
+        s = GroupStream(ctx, members) if grouped else members[0]
         streams.append(s)
         per_stream = []
         for j in range(args.batch):
@@ -169,6 +187,8 @@ def main():
         big_groups = (total_groups - args.tiny_groups * len(tiny)) // max(n_big, 1)
         if big_groups < 2 or args.tiny_groups < 2:
             raise SystemExit("partition sizes do not fit (every application needs >= 2 CU groups)")
+        if grouped:
+            raise SystemExit("--tiny-groups is not combined with --group-nets")
         at = 0
         for s in streams + hogs + tiny:
             g = args.tiny_groups if s in tiny else big_groups
@@ -177,12 +197,13 @@ def main():
             ci, co = (cus, cus) if args.partition == "equal-shared" else (cus[:-8], cus[-8:])
             hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
     elif args.partition != "none":
-        for s, (ci, co) in zip(streams + tiny + hogs,
-                               equal_partitions(n_cus, args.streams + args.tiny_apps + args.hog,
-                                                groups_per_app=args.partition_groups)):
+        # one partition per library application (every network of a group gets its own)
+        units = [a for s in streams + tiny + hogs for a in apps_of(s)]
+        for a, (ci, co) in zip(units, equal_partitions(n_cus, len(units),
+                                                       groups_per_app=args.partition_groups)):
             if args.partition == "equal-shared":
                 ci = co = ci + co
-            hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+            hs.hs_set_partition(a, hs.cu_mask_words(ci), hs.cu_mask_words(co))
     outs = [[[s.new_output() for _ in range(args.batch)] for _ in range(args.queue_depth)]
             for s in streams]
     torch.cuda.synchronize()
@@ -217,7 +238,8 @@ def main():
 
     # ---- latency determinism at a fixed frame rate (paper Section V-A metrics) -------------
     for s in streams:
-        hs.hs_reset_state(s.app)
+        for a in apps_of(s):
+            hs.hs_reset_state(a)
     paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
              for f in frames]
     hog_stop = threading.Event()
@@ -245,14 +267,16 @@ def main():
         cores = sorted(os.sched_getaffinity(0))
         pins = [cores[(2 * i) % len(cores)] for i in range(len(streams) + len(tiny))]
         for i, s in enumerate(streams + tiny):
-            hs.hs_set_cpu_affinity(s.app, cores[(2 * i + 1) % len(cores)])
+            for a in apps_of(s):
+                hs.hs_set_cpu_affinity(a, cores[(2 * i + 1) % len(cores)])
     tiny_paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
                   for f in tiny_frames]
     lat_ms, tl, dropped, results = [], [], [], []
     for rep in range(max(1, args.repeats)):
         if rep:
             for s in streams + tiny:
-                hs.hs_reset_state(s.app)
+                for a in apps_of(s):
+                    hs.hs_reset_state(a)
         res_all, drop = run_paced(streams + tiny, paced + tiny_paced, args.fps, outs + tiny_outs,
                                   pin_cpus=pins)
         dropped.extend(drop)
@@ -299,14 +323,15 @@ def main():
 
     # ---- roofline of the dominant kernel: HIP events around every launch -------------------
     s0 = streams[0]
-    hs.hs_set_kernel_timing(s0.app, True)
+    app0 = apps_of(s0)[0]     # a group: its first network (and the shared overlay launch)
+    hs.hs_set_kernel_timing(app0, True)
     n_prof = 20
     for k in range(n_prof):
         assert s0.submit_batch(frames[0][k % len(frames[0])], outs[0][k % len(outs[0])],
                                k) == hs.HS_OK
         s0.wait_batch()
-    kt = hs.hs_get_kernel_times(s0.app)
-    hs.hs_set_kernel_timing(s0.app, False)
+    kt = hs.hs_get_kernel_times(app0)
+    hs.hs_set_kernel_timing(app0, False)
     dom = max(kt, key=lambda e: e["total_ms"])
     if dom["flops"] > 0:
         ach = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
@@ -373,8 +398,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.streams * args.batch} stream(s) x 1920x1080 RGB uint8 -> 854x480 fp16, "
                                "ResNet-18-style + ConvLSTM(256) + 8-ch head, sigmoid/threshold/"
-                               "argmax, alpha-blend overlay on the 1080p frame",
-                   "streams": args.streams, "batch": args.batch, "partition": args.partition,
+                               "argmax, alpha-blend overlay on the 1080p frame"
+                               + (f"; {args.group_nets} such networks per stream, one overlay "
+                                  "launch for their layers" if grouped else ""),
+                   "streams": args.streams, "batch": args.batch, "group_nets": args.group_nets,
+                   "partition": args.partition,
                    "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
                    "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "tiny_groups": args.tiny_groups, "annotate": bool(args.annotate), "device_cus": n_cus},

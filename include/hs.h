@@ -43,6 +43,7 @@ extern "C" {
 
 typedef struct hs_ctx hs_ctx; /* one per device, opaque */
 typedef struct hs_app hs_app; /* one per application stream, opaque */
+typedef struct hs_group hs_group; /* applications that share frames and one overlay, opaque */
 
 typedef enum {
   HS_OK = 0,
@@ -253,6 +254,42 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
                           uint8_t* const* d_overlay_outs, uint64_t frame_id);
 hs_status hs_poll_batch(hs_app* app, hs_result* out);
 hs_status hs_wait_batch(hs_app* app, hs_result* out, uint64_t timeout_ns);
+
+/* ---- multi-network applications (Section III-B) ------------------------------------- */
+
+/* The paper's second application runs three networks on every frame, each behind its own
+ * format converter, in parallel GPU streams, and one visualisation renders the aggregated
+ * layers over the original frame.  Here: a group of 1..HS_MAX_GROUP applications of one
+ * context (each created with hs_create_app: own network, network input size, threshold,
+ * palette, alpha, annotation settings, workspace; batch 1; identical frame_w, frame_h and
+ * frame_pitch).  hs_submit_group hands ONE frame to all members: each runs stages 1-3 on its
+ * own stream(s), side by side on the GPU, and a single stage-4 launch, on member 0's overlay
+ * stream after every member's stage 3, draws the members' layers in member order -- a
+ * member's mask blend, then its annotations, each layer over the picture the previous one
+ * left -- into d_overlay_out (the frame is read once and written once).
+ * Results arrive as n_members consecutive hs_result entries (member order) once every member
+ * has finished the frame; all carry the same t_submit_ns and d_overlay, and t_overlay_done_ns
+ * is stamped by each member's completion thread when the shared overlay launch completes.
+ * While grouped, members are driven only through the group: their own submit / poll / wait /
+ * destroy calls return HS_E_STATE; hs_set_partition, hs_reset_state, hs_get_state and the
+ * launch-mode and timing calls still address single members (the shared overlay launch is
+ * accounted to member 0).  One thread at a time submits to a group, one thread at a time polls.
+ *
+ * hs_create_group: HS_E_INVAL for NULL / foreign / repeated / batched members or differing
+ * frame geometry, HS_E_STATE if a member is already grouped or has frames in flight or
+ * unpolled.  The members array is copied.
+ * hs_destroy_group: waits for in-flight frames, then releases the members (results not yet
+ * polled stay available through the members' own poll calls). */
+#define HS_MAX_GROUP 4
+hs_status hs_create_group(hs_ctx* ctx, hs_app* const* members, int n_members, hs_group** out);
+hs_status hs_destroy_group(hs_group* group);
+/* Same frame rules as hs_submit_frame. HS_E_QUEUE_FULL (nothing enqueued for any member) when
+ * a member has no free slot. */
+hs_status hs_submit_group(hs_group* group, const uint8_t* d_frame, uint8_t* d_overlay_out,
+                          uint64_t frame_id);
+/* out[0 .. n_members-1]. Non-blocking / blocking as hs_poll_result / hs_wait_result. */
+hs_status hs_poll_group(hs_group* group, hs_result* out);
+hs_status hs_wait_group(hs_group* group, hs_result* out, uint64_t timeout_ns);
 
 /* How hs_submit_frame hands stages 1-3 to the GPU: as one pre-built HIP graph per queue slot
  * (default; one launch call per frame instead of ~35) or kernel by kernel. Results are

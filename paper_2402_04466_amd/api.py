@@ -19,7 +19,9 @@ __all__ = [
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
-    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
+    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch",
+    "hs_create_group", "hs_destroy_group", "hs_submit_group", "hs_poll_group", "hs_wait_group",
+    "HS_MAX_GROUP", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
     "hs_get_kernel_times", "hs_device_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
@@ -28,6 +30,7 @@ HS_E_QUEUE_FULL, HS_E_NOT_READY, HS_E_DEVICE, HS_E_STATE = -4, -5, -6, -7
 HS_NET_TINY4, HS_NET_RESNET18_CONVLSTM = 1, 2
 HS_NUM_TOOLS, HS_MAX_CU_WORDS = 8, 8
 HS_LAUNCH_GRAPH, HS_LAUNCH_EAGER = 0, 1
+HS_MAX_GROUP = 4
 
 _STATUS_NAME = {0: "HS_OK", -1: "HS_E_INVAL", -2: "HS_E_NOMEM", -3: "HS_E_OVERSUBSCRIBED",
                 -4: "HS_E_QUEUE_FULL", -5: "HS_E_NOT_READY", -6: "HS_E_DEVICE", -7: "HS_E_STATE"}
@@ -97,6 +100,13 @@ def load() -> C.CDLL:
     if not os.path.exists(path):
         raise HsError(HS_E_DEVICE, f"{path} is missing: build it with "
                                    "`python -m paper_2402_04466_amd.build`")
+    # PyTorch (the caller's source of device memory) ships its own copy of the HIP runtime.  It
+    # has to be loaded first: if libhs binds to another copy before it, the process ends up
+    # with two runtimes and torch finds no GPU.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     P = C.POINTER
     sig = {
@@ -117,6 +127,11 @@ def load() -> C.CDLL:
         "hs_submit_frame": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
         "hs_poll_result": (C.c_int, [C.c_void_p, P(hs_result)]),
         "hs_wait_result": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
+        "hs_create_group": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, P(C.c_void_p)]),
+        "hs_destroy_group": (C.c_int, [C.c_void_p]),
+        "hs_submit_group": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
+        "hs_poll_group": (C.c_int, [C.c_void_p, P(hs_result)]),
+        "hs_wait_group": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
         "hs_latency_metrics_compute": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int,
                                                  P(hs_latency_metrics)]),
         "hs_mann_whitney_u": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, P(hs_mwu)]),
@@ -305,6 +320,39 @@ def hs_wait_batch(app: int, batch: int, timeout_ns: int = 10_000_000_000):
     """Returns a list of `batch` hs_result (stream order), or None on time-out."""
     r = (hs_result * batch)()
     st = _check(load().hs_wait_batch(app, r, timeout_ns), soft=(HS_E_NOT_READY,))
+    return list(r) if st == HS_OK else None
+
+
+def hs_create_group(ctx: int, members) -> int:
+    """members: application handles (ints), in layer order. Returns the group handle."""
+    n = len(members)
+    arr = (C.c_void_p * n)(*[int(m) for m in members])
+    out = C.c_void_p()
+    _check(load().hs_create_group(ctx, arr, n, C.byref(out)))
+    return out.value
+
+
+def hs_destroy_group(group: int) -> None:
+    _check(load().hs_destroy_group(group))
+
+
+def hs_submit_group(group: int, d_frame: int, d_overlay_out: int, frame_id: int) -> int:
+    """Returns HS_OK or HS_E_QUEUE_FULL; raises on any other status."""
+    return _check(load().hs_submit_group(group, d_frame, d_overlay_out, frame_id),
+                  soft=(HS_E_QUEUE_FULL,))
+
+
+def hs_poll_group(group: int, n_members: int):
+    """Returns a list of n_members hs_result (member order), or None if nothing has finished."""
+    r = (hs_result * n_members)()
+    st = _check(load().hs_poll_group(group, r), soft=(HS_E_NOT_READY,))
+    return list(r) if st == HS_OK else None
+
+
+def hs_wait_group(group: int, n_members: int, timeout_ns: int = 10_000_000_000):
+    """Returns a list of n_members hs_result (member order), or None on time-out."""
+    r = (hs_result * n_members)()
+    st = _check(load().hs_wait_group(group, r, timeout_ns), soft=(HS_E_NOT_READY,))
     return list(r) if st == HS_OK else None
 
 

@@ -144,12 +144,11 @@ struct PostParams {
 KernelDesc describe(const PostParams& p);
 
 // ---- stage 4: overlay ---------------------------------------------------------------------
-struct OverlayParams {
-  const uint8_t* src[kMaxBatch]; uint8_t* dst[kMaxBatch];   // per stream
-  int batch; size_t pitch; int wf, hf;
+constexpr int kMaxLayers = 4;   // networks whose results one overlay launch can draw
+// What one network contributes to the picture: its channel map, colours and annotations.
+struct OverlayLayer {
   const uint8_t* kmap; int wm, hm;   // [batch][hm][wm]: lowest set mask channel or 0xff
-  float rcp_gpr, rcp_hf, rcp_wf, rcp_wm;   // 1/ceil(wf/16), 1/hf, 1/wf, 1/wm: division estimates
-                                     // (needs wf*wm, hf*hm and ceil(wf/16)*hf below 2^31)
+  float rcp_wm;                      // 1/wm: division estimate (needs wf*wm and hf*hm below 2^31)
   int a;                             // Q8 alpha, 0..256
   uint32_t pal[8];                   // R | G<<8 | B<<16
   // annotation layer: cross-hair and 'T'<k> label per present tool, opaque, in tool order
@@ -157,6 +156,13 @@ struct OverlayParams {
   int arm, half, scale;              // marker arm / half thickness, pixels per glyph cell
   float rcp_scale;                   // 1/scale
   uint64_t glyph[9];                 // bit (5*row + col) of glyph g, col 0 = leftmost
+};
+struct OverlayParams {
+  const uint8_t* src[kMaxBatch]; uint8_t* dst[kMaxBatch];   // per stream
+  int batch; size_t pitch; int wf, hf;
+  float rcp_gpr, rcp_hf, rcp_wf;     // 1/ceil(wf/16), 1/hf, 1/wf (ceil(wf/16)*hf below 2^31)
+  int n_layers;                      // layers drawn in order, each over the one before
+  OverlayLayer layer[kMaxLayers];
 };
 KernelDesc describe(const OverlayParams& p);
 

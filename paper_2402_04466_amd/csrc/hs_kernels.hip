@@ -969,6 +969,168 @@ KernelDesc describe(const PostParams& p) {
 // contiguous, a wavefront moves its 3072 bytes as fully coalesced 16-byte vectors and regroups
 // them through LDS, instead of every lane touching its own 48-byte span.
 // =============================================================================================
+// One layer of stage 4 applied to a group of 16 pixels held in registers (w[0..11], word j starts
+// with channel j mod 3): blend of the layer's channel map, then its annotations.
+__device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, const OverlayLayer& L,
+                                                    uint32_t (&w)[12], int Y, int X0, int by) {
+  const int my = (int)udiv_est((uint32_t)(Y * L.hm), (uint32_t)p.hf, p.rcp_hf);
+  const uint8_t* krow = L.kmap + ((size_t)by * L.hm + my) * L.wm;
+  const int ia = 256 - L.a;
+  const int mx0 = (int)udiv_est((uint32_t)(X0 * L.wm), (uint32_t)p.wf, p.rcp_wf);
+  const uint8_t k0 = krow[mx0], k1 = krow[min(mx0 + 1, L.wm - 1)];
+  // Most groups see one channel for all 16 pixels: nothing to draw, or one colour.  Then the
+  // blend runs on two bytes per 32-bit operation: even and odd bytes of a word are 16-bit
+  // fields, (256 - a) * byte + (a * colour + 128) never exceeds 65408, so no field carries into
+  // its neighbour.
+  const int mx_last = (int)udiv_est((uint32_t)((X0 + 15) * L.wm), (uint32_t)p.wf, p.rcp_wf);
+  const bool one_cell = mx_last == mx0 || (mx_last == mx0 + 1 && k1 == k0);
+  if (one_cell) {
+    if (k0 != 0xff) {
+      const uint32_t col = L.pal[k0];
+      uint32_t t[3];
+#pragma unroll
+      for (int c = 0; c < 3; ++c) t[c] = (uint32_t)L.a * ((col >> (8 * c)) & 0xffu) + 128u;
+#pragma unroll
+      for (int j = 0; j < 12; ++j) {
+        const uint32_t ce = t[j % 3] | (t[(j + 2) % 3] << 16);        // bytes 0 and 2
+        const uint32_t co = t[(j + 1) % 3] | (t[(j + 3) % 3] << 16);  // bytes 1 and 3
+        const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
+        w[j] = (((e * (uint32_t)ia + ce) >> 8) & 0x00ff00ffu) |
+               ((o * (uint32_t)ia + co) & 0xff00ff00u);
+      }
+    }
+  } else if (mx_last == mx0 + 1) {
+    // two cells: pixels [0, s) see k0, [s, 16) see k1.  Same packed blend with the colour
+    // term chosen per byte (byte index < 3*s), then bytes of an undrawn cell are restored.
+    const int rem = X0 * L.wm - mx0 * p.wf;
+    const int s3 = 3 * (int)udiv_est((uint32_t)(p.wf - rem + L.wm - 1), (uint32_t)L.wm, L.rcp_wm);
+    const uint32_t c0 = k0 != 0xff ? L.pal[k0 & 7] : 0u, c1 = k1 != 0xff ? L.pal[k1 & 7] : 0u;
+    const uint32_t d0 = k0 != 0xff ? 0xffffffffu : 0u, d1 = k1 != 0xff ? 0xffffffffu : 0u;
+    uint32_t t0[3], t1[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      t0[c] = (uint32_t)L.a * ((c0 >> (8 * c)) & 0xffu) + 128u;
+      t1[c] = (uint32_t)L.a * ((c1 >> (8 * c)) & 0xffu) + 128u;
+    }
+#pragma unroll
+    for (int j = 0; j < 12; ++j) {
+      const uint32_t tb0 = 4 * j + 0 < s3 ? t0[j % 3] : t1[j % 3];
+      const uint32_t tb1 = 4 * j + 1 < s3 ? t0[(j + 1) % 3] : t1[(j + 1) % 3];
+      const uint32_t tb2 = 4 * j + 2 < s3 ? t0[(j + 2) % 3] : t1[(j + 2) % 3];
+      const uint32_t tb3 = 4 * j + 3 < s3 ? t0[(j + 3) % 3] : t1[(j + 3) % 3];
+      const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
+      const uint32_t blended = (((e * (uint32_t)ia + (tb0 | (tb2 << 16))) >> 8) & 0x00ff00ffu) |
+                               ((o * (uint32_t)ia + (tb1 | (tb3 << 16))) & 0xff00ff00u);
+      const int nb = min(4, max(0, s3 - 4 * j));                    // leading bytes of cell 0
+      const uint32_t low = nb == 4 ? 0xffffffffu : ((1u << (8 * nb)) - 1u);
+      const uint32_t draw = (low & d0) | (~low & d1);
+      w[j] = (blended & draw) | (w[j] & ~draw);
+    }
+  } else {
+    int mx = mx0;
+    int rem = X0 * L.wm - mx0 * p.wf;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint8_t k = mx == mx0 ? k0 : (mx == mx0 + 1 ? k1 : krow[mx]);
+      if (k != 0xff) {
+        const uint32_t col = L.pal[k];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+          const int byte = 3 * i + c;                 // literal after unrolling
+          const uint32_t pc = (col >> (8 * c)) & 0xffu;
+          const uint32_t old = (w[byte >> 2] >> (8 * (byte & 3))) & 0xffu;
+          const uint32_t nw = (L.a * pc + ia * old + 128u) >> 8;
+          w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (nw << (8 * (byte & 3)));
+        }
+      }
+      rem += L.wm;
+      while (rem >= p.wf) { rem -= p.wf; ++mx; }
+    }
+  }
+  if (L.marks) {
+    // annotation layer: a tool's drawing lies in one box; only groups that meet a box look
+    // closer, pixel by pixel, tools in increasing order (later tools paint over earlier ones)
+    const int* mk = L.marks + (size_t)by * 16;
+    const int lab_w = 11 * L.scale, lab_h = 7 * L.scale;
+#pragma unroll 1
+    for (int k = 0; k < 8; ++k) {
+      const int cx = mk[2 * k], cy = mk[2 * k + 1];
+      if (cx < 0) continue;
+      const int ox = cx + L.arm + 2, oy = cy - lab_h - 2;          // label origin
+      if (Y < min(cy - L.arm, oy) || Y > cy + L.arm || X0 + 15 < cx - L.arm || X0 >= ox + lab_w)
+        continue;
+      const uint32_t col = L.pal[k];
+      // what this row paints, as pixel intervals around cx and a bit per label pixel
+      const int dy = abs(Y - cy);
+      const int reach = dy <= L.half ? L.arm : (dy <= L.arm ? L.half : -1);   // |X - cx| <= reach
+      uint64_t lab_lo = 0, lab_hi = 0;       // label pixels lx = 0..63 and 64..87 of this row
+      if (Y >= oy && Y < oy + lab_h) {
+        const int gy = (int)udiv_est((uint32_t)(Y - oy), (uint32_t)L.scale, L.rcp_scale);
+        const uint32_t cells = (uint32_t)((L.glyph[0] >> (5 * gy)) & 31ull) |
+                               ((uint32_t)((L.glyph[1 + k] >> (5 * gy)) & 31ull) << 6);
+        const uint64_t run = (1ull << L.scale) - 1ull;               // scale <= 8 pixels per cell
+        for (int cell = 0; cell < 11; ++cell) {
+          if (!((cells >> cell) & 1u)) continue;
+          const int at = cell * L.scale;
+          if (at < 64) lab_lo |= run << at;
+          if (at + L.scale > 64) lab_hi |= at >= 64 ? run << (at - 64) : run >> (64 - at);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int X = X0 + i, lx = X - ox;
+        bool hit = abs(X - cx) <= reach;
+        if (lx >= 0 && lx < lab_w) hit = hit || (((lx < 64 ? lab_lo >> lx : lab_hi >> (lx - 64)) & 1ull) != 0);
+        if (hit) {
+#pragma unroll
+          for (int c = 0; c < 3; ++c) {
+            const int byte = 3 * i + c;               // literal after unrolling
+            const uint32_t pc = (col >> (8 * c)) & 0xffu;
+            w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (pc << (8 * (byte & 3)));
+          }
+        }
+      }
+    }
+  }
+}
+
+// The same layer applied to one pixel (x[0..2]) of a ragged row tail.
+__device__ __forceinline__ void overlay_layer_pixel(const OverlayParams& p, const OverlayLayer& L,
+                                                    uint32_t (&x)[3], int Y, int X, int by) {
+  const int my = (int)udiv_est((uint32_t)(Y * L.hm), (uint32_t)p.hf, p.rcp_hf);
+  const int mx = (int)udiv_est((uint32_t)(X * L.wm), (uint32_t)p.wf, p.rcp_wf);
+  const uint8_t k = L.kmap[((size_t)by * L.hm + my) * L.wm + mx];
+  int paint = -1;                          // tool whose marker or label covers this pixel
+  if (L.marks) {
+    const int* mk = L.marks + (size_t)by * 16;
+    for (int t = 0; t < 8; ++t) {
+      const int cx = mk[2 * t], cy = mk[2 * t + 1];
+      if (cx < 0) continue;
+      const int dx = abs(X - cx), dy = abs(Y - cy);
+      bool hit = (dx <= L.arm && dy <= L.half) || (dy <= L.arm && dx <= L.half);
+      const int lx = X - (cx + L.arm + 2), ly = Y - (cy - 7 * L.scale - 2);
+      if (lx >= 0 && lx < 11 * L.scale && ly >= 0 && ly < 7 * L.scale) {
+        const int cell = lx / L.scale, gy = ly / L.scale;
+        const int gi = cell >= 6 ? 1 : 0, gx = cell - 6 * gi;
+        if (gx < 5) hit = hit || ((L.glyph[gi ? 1 + t : 0] >> (5 * gy + gx)) & 1ull);
+      }
+      if (hit) paint = t;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    if (k != 0xff) {
+      const uint32_t pc = (L.pal[k] >> (8 * c)) & 0xffu;
+      x[c] = (L.a * pc + (256 - L.a) * x[c] + 128u) >> 8;
+    }
+    if (paint >= 0) x[c] = (L.pal[paint] >> (8 * c)) & 0xffu;
+  }
+}
+
+// LAYERS == false: exactly one layer (every single-network application).  LAYERS == true: the
+// n_layers layers of a multi-network application are applied in order, each on the result of
+// the one before, while the pixels sit in registers (one read and one write of the frame).
+template <bool LAYERS>
 __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
   __shared__ u32x4 s_x[4][192];
   const int gpr = (p.wf + 15) >> 4;                              // groups per row
@@ -981,15 +1143,10 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
   if (g >= gpr * p.hf) return;
   // all quotients by float estimate + exact fix-up (operands < 2^31, quotients < 2^22)
   const int Y = (int)udiv_est((uint32_t)g, (uint32_t)gpr, p.rcp_gpr), X0 = (g - Y * gpr) * 16;
-  const int my = (int)udiv_est((uint32_t)(Y * p.hm), (uint32_t)p.hf, p.rcp_hf);
-  const uint8_t* krow = p.kmap + ((size_t)blockIdx.y * p.hm + my) * p.wm;
   const uint8_t* srow = p.src[blockIdx.y] + (size_t)Y * p.pitch;
   uint8_t* drow = p.dst[blockIdx.y] + (size_t)Y * p.pitch;
-  const int ia = 256 - p.a;
   const int npx = min(16, p.wf - X0);
-  const int mx0 = (int)udiv_est((uint32_t)(X0 * p.wm), (uint32_t)p.wf, p.rcp_wf);
-  int mx = mx0;
-  int rem = X0 * p.wm - mx * p.wf;
+  const int nl = LAYERS ? p.n_layers : 1;
   if (npx == 16) {
     u32x4 v[3];
     if (coalesced) {
@@ -1006,121 +1163,14 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
       const u32x4* s4 = reinterpret_cast<const u32x4*>(srow + (size_t)X0 * 3);
       v[0] = s4[0]; v[1] = s4[1]; v[2] = s4[2];
     }
-    const uint8_t k0 = krow[mx0], k1 = krow[min(mx0 + 1, p.wm - 1)];
     uint32_t w[12];
 #pragma unroll
     for (int i = 0; i < 12; ++i) w[i] = v[i >> 2][i & 3];
-    // Most groups see one channel for all 16 pixels: nothing to draw, or one colour.  Then the
-    // blend runs on two bytes per 32-bit operation: even and odd bytes of a word are 16-bit
-    // fields, (256 - a) * byte + (a * colour + 128) never exceeds 65408, so no field carries into
-    // its neighbour.  Word j of the group starts with channel j mod 3.
-    const int mx_last = (int)udiv_est((uint32_t)((X0 + 15) * p.wm), (uint32_t)p.wf, p.rcp_wf);
-    const bool one_cell = mx_last == mx0 || (mx_last == mx0 + 1 && k1 == k0);
-    if (one_cell) {
-      if (k0 != 0xff) {
-        const uint32_t col = p.pal[k0];
-        uint32_t t[3];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) t[c] = (uint32_t)p.a * ((col >> (8 * c)) & 0xffu) + 128u;
-#pragma unroll
-        for (int j = 0; j < 12; ++j) {
-          const uint32_t ce = t[j % 3] | (t[(j + 2) % 3] << 16);        // bytes 0 and 2
-          const uint32_t co = t[(j + 1) % 3] | (t[(j + 3) % 3] << 16);  // bytes 1 and 3
-          const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
-          w[j] = (((e * (uint32_t)ia + ce) >> 8) & 0x00ff00ffu) |
-                 ((o * (uint32_t)ia + co) & 0xff00ff00u);
-        }
-      }
-    } else if (mx_last == mx0 + 1) {
-      // two cells: pixels [0, s) see k0, [s, 16) see k1.  Same packed blend with the colour
-      // term chosen per byte (byte index < 3*s), then bytes of an undrawn cell are restored.
-      const int s3 = 3 * (int)udiv_est((uint32_t)(p.wf - rem + p.wm - 1), (uint32_t)p.wm, p.rcp_wm);
-      const uint32_t c0 = k0 != 0xff ? p.pal[k0 & 7] : 0u, c1 = k1 != 0xff ? p.pal[k1 & 7] : 0u;
-      const uint32_t d0 = k0 != 0xff ? 0xffffffffu : 0u, d1 = k1 != 0xff ? 0xffffffffu : 0u;
-      uint32_t t0[3], t1[3];
-#pragma unroll
-      for (int c = 0; c < 3; ++c) {
-        t0[c] = (uint32_t)p.a * ((c0 >> (8 * c)) & 0xffu) + 128u;
-        t1[c] = (uint32_t)p.a * ((c1 >> (8 * c)) & 0xffu) + 128u;
-      }
-#pragma unroll
-      for (int j = 0; j < 12; ++j) {
-        const uint32_t tb0 = 4 * j + 0 < s3 ? t0[j % 3] : t1[j % 3];
-        const uint32_t tb1 = 4 * j + 1 < s3 ? t0[(j + 1) % 3] : t1[(j + 1) % 3];
-        const uint32_t tb2 = 4 * j + 2 < s3 ? t0[(j + 2) % 3] : t1[(j + 2) % 3];
-        const uint32_t tb3 = 4 * j + 3 < s3 ? t0[(j + 3) % 3] : t1[(j + 3) % 3];
-        const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
-        const uint32_t blended = (((e * (uint32_t)ia + (tb0 | (tb2 << 16))) >> 8) & 0x00ff00ffu) |
-                                 ((o * (uint32_t)ia + (tb1 | (tb3 << 16))) & 0xff00ff00u);
-        const int nb = min(4, max(0, s3 - 4 * j));                    // leading bytes of cell 0
-        const uint32_t low = nb == 4 ? 0xffffffffu : ((1u << (8 * nb)) - 1u);
-        const uint32_t draw = (low & d0) | (~low & d1);
-        w[j] = (blended & draw) | (w[j] & ~draw);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const uint8_t k = mx == mx0 ? k0 : (mx == mx0 + 1 ? k1 : krow[mx]);
-        if (k != 0xff) {
-          const uint32_t col = p.pal[k];
-#pragma unroll
-          for (int c = 0; c < 3; ++c) {
-            const int byte = 3 * i + c;                 // literal after unrolling
-            const uint32_t pc = (col >> (8 * c)) & 0xffu;
-            const uint32_t old = (w[byte >> 2] >> (8 * (byte & 3))) & 0xffu;
-            const uint32_t nw = (p.a * pc + ia * old + 128u) >> 8;
-            w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (nw << (8 * (byte & 3)));
-          }
-        }
-        rem += p.wm;
-        while (rem >= p.wf) { rem -= p.wf; ++mx; }
-      }
-    }
-    if (p.marks) {
-      // annotation layer: a tool's drawing lies in one box; only groups that meet a box look
-      // closer, pixel by pixel, tools in increasing order (later tools paint over earlier ones)
-      const int* mk = p.marks + (size_t)blockIdx.y * 16;
-      const int lab_w = 11 * p.scale, lab_h = 7 * p.scale;
+    if (LAYERS) {
 #pragma unroll 1
-      for (int k = 0; k < 8; ++k) {
-        const int cx = mk[2 * k], cy = mk[2 * k + 1];
-        if (cx < 0) continue;
-        const int ox = cx + p.arm + 2, oy = cy - lab_h - 2;          // label origin
-        if (Y < min(cy - p.arm, oy) || Y > cy + p.arm || X0 + 15 < cx - p.arm ||
-            X0 >= ox + lab_w)
-          continue;
-        const uint32_t col = p.pal[k];
-        // what this row paints, as pixel intervals around cx and a bit per label pixel
-        const int dy = abs(Y - cy);
-        const int reach = dy <= p.half ? p.arm : (dy <= p.arm ? p.half : -1);   // |X - cx| <= reach
-        uint64_t lab_lo = 0, lab_hi = 0;       // label pixels lx = 0..63 and 64..87 of this row
-        if (Y >= oy && Y < oy + lab_h) {
-          const int gy = (int)udiv_est((uint32_t)(Y - oy), (uint32_t)p.scale, p.rcp_scale);
-          const uint32_t cells = (uint32_t)((p.glyph[0] >> (5 * gy)) & 31ull) |
-                                 ((uint32_t)((p.glyph[1 + k] >> (5 * gy)) & 31ull) << 6);
-          const uint64_t run = (1ull << p.scale) - 1ull;               // scale <= 8 pixels per cell
-          for (int cell = 0; cell < 11; ++cell) {
-            if (!((cells >> cell) & 1u)) continue;
-            const int at = cell * p.scale;
-            if (at < 64) lab_lo |= run << at;
-            if (at + p.scale > 64) lab_hi |= at >= 64 ? run << (at - 64) : run >> (64 - at);
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int X = X0 + i, lx = X - ox;
-          bool hit = abs(X - cx) <= reach;
-          if (lx >= 0 && lx < lab_w) hit = hit || (((lx < 64 ? lab_lo >> lx : lab_hi >> (lx - 64)) & 1ull) != 0);
-          if (hit) {
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-              const int byte = 3 * i + c;               // literal after unrolling
-              const uint32_t pc = (col >> (8 * c)) & 0xffu;
-              w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (pc << (8 * (byte & 3)));
-            }
-          }
-        }
-      }
+      for (int l = 0; l < nl; ++l) overlay_layer_group(p, p.layer[l], w, Y, X0, (int)blockIdx.y);
+    } else {
+      overlay_layer_group(p, p.layer[0], w, Y, X0, (int)blockIdx.y);
     }
     if (coalesced) {
 #pragma unroll
@@ -1145,43 +1195,19 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
     }
   } else {
     for (int i = 0; i < npx; ++i) {
-      const uint8_t k = krow[mx];
       const int X = X0 + i;
-      int paint = -1;                          // tool whose marker or label covers this pixel
-      if (p.marks) {
-        const int* mk = p.marks + (size_t)blockIdx.y * 16;
-        for (int t = 0; t < 8; ++t) {
-          const int cx = mk[2 * t], cy = mk[2 * t + 1];
-          if (cx < 0) continue;
-          const int dx = abs(X - cx), dy = abs(Y - cy);
-          bool hit = (dx <= p.arm && dy <= p.half) || (dy <= p.arm && dx <= p.half);
-          const int lx = X - (cx + p.arm + 2), ly = Y - (cy - 7 * p.scale - 2);
-          if (lx >= 0 && lx < 11 * p.scale && ly >= 0 && ly < 7 * p.scale) {
-            const int cell = lx / p.scale, gy = ly / p.scale;
-            const int gi = cell >= 6 ? 1 : 0, gx = cell - 6 * gi;
-            if (gx < 5) hit = hit || ((p.glyph[gi ? 1 + t : 0] >> (5 * gy + gx)) & 1ull);
-          }
-          if (hit) paint = t;
-        }
-      }
-      for (int c = 0; c < 3; ++c) {
-        uint32_t x = srow[(size_t)X * 3 + c];
-        if (k != 0xff) {
-          const uint32_t pc = (p.pal[k] >> (8 * c)) & 0xffu;
-          x = (p.a * pc + ia * x + 128u) >> 8;
-        }
-        if (paint >= 0) x = (p.pal[paint] >> (8 * c)) & 0xffu;
-        drow[(size_t)X * 3 + c] = (uint8_t)x;
-      }
-      rem += p.wm;
-      while (rem >= p.wf) { rem -= p.wf; ++mx; }
+      uint32_t x[3];
+      for (int c = 0; c < 3; ++c) x[c] = srow[(size_t)X * 3 + c];
+      for (int l = 0; l < nl; ++l) overlay_layer_pixel(p, p.layer[l], x, Y, X, (int)blockIdx.y);
+      for (int c = 0; c < 3; ++c) drow[(size_t)X * 3 + c] = (uint8_t)x[c];
     }
   }
 }
 
 KernelDesc describe(const OverlayParams& p) {
   const unsigned groups = (unsigned)(((p.wf + 15) >> 4) * p.hf);
-  return KernelDesc{(const void*)k_overlay, dim3((groups + 255) / 256, p.batch), dim3(256), 0};
+  const void* f = p.n_layers > 1 ? (const void*)k_overlay<true> : (const void*)k_overlay<false>;
+  return KernelDesc{f, dim3((groups + 255) / 256, p.batch), dim3(256), 0};
 }
 
 // ---------------------------------------------------------------------------------------------

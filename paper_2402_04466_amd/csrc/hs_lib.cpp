@@ -192,6 +192,15 @@ struct hs_app {
   double acc_ms[F_COUNT] = {0}, acc_flops[F_COUNT] = {0}, acc_bytes[F_COUNT] = {0};
   uint64_t acc_n[F_COUNT] = {0};
   void* pinned = nullptr;
+  hs_group* group = nullptr;   // set while the application is a member of a multi-network group
+};
+
+// A multi-network application: the members run stages 1-3 on the same frame side by side, one
+// overlay launch of the group draws all their layers.
+struct hs_group {
+  hs_ctx* ctx = nullptr;
+  std::vector<hs_app*> members;
+  std::vector<Op> overlay;   // one op; its layers are refilled from the members' slots per frame
 };
 
 namespace hs {
@@ -801,24 +810,27 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
       OverlayParams& op = o.overlay;
       std::memset(&op, 0, sizeof(op));
       op.batch = B; op.pitch = d->frame_pitch;
-      op.wf = d->frame_w; op.hf = d->frame_h; op.kmap = sb[i].kmap; op.wm = mw; op.hm = mh;
+      op.wf = d->frame_w; op.hf = d->frame_h;
       op.rcp_gpr = 1.0f / (float)((d->frame_w + 15) / 16);
       op.rcp_hf = 1.0f / (float)d->frame_h; op.rcp_wf = 1.0f / (float)d->frame_w;
-      op.rcp_wm = 1.0f / (float)mw;
-      op.a = a_q8;
-      op.marks = sb[i].marks;
-      op.arm = d->marker_arm; op.half = d->marker_half; op.scale = d->glyph_scale;
-      op.rcp_scale = 1.0f / (float)std::max(1, d->glyph_scale);
+      op.n_layers = 1;
+      OverlayLayer& L = op.layer[0];
+      L.kmap = sb[i].kmap; L.wm = mw; L.hm = mh;
+      L.rcp_wm = 1.0f / (float)mw;
+      L.a = a_q8;
+      L.marks = sb[i].marks;
+      L.arm = d->marker_arm; L.half = d->marker_half; L.scale = d->glyph_scale;
+      L.rcp_scale = 1.0f / (float)std::max(1, d->glyph_scale);
       for (int g = 0; g < 9; ++g) {
         uint64_t bits = 0;
         for (int r = 0; r < 7; ++r)
           for (int c = 0; c < 5; ++c)
             if ((d->glyphs[g][r] >> (4 - c)) & 1) bits |= 1ull << (5 * r + c);
-        op.glyph[g] = bits;
+        L.glyph[g] = bits;
       }
       for (int k = 0; k < 8; ++k)
-        op.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
-                    ((uint32_t)d->palette[k][2] << 16);
+        L.pal[k] = (uint32_t)d->palette[k][0] | ((uint32_t)d->palette[k][1] << 8) |
+                   ((uint32_t)d->palette[k][2] << 16);
       o.bytes = B * (6.0 * d->frame_w * d->frame_h + 1.0 * n_map);
       s.overlay.push_back(o);
     }
@@ -1135,6 +1147,7 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
 
 hs_status hs_destroy_app(hs_app* app) {
   if (!app) { set_error("hs_destroy_app: NULL"); return HS_E_INVAL; }
+  if (app->group) { set_error("hs_destroy_app: destroy the application's group first"); return HS_E_STATE; }
   (void)hipSetDevice(app->ctx->device);
   {
     std::lock_guard<std::mutex> lk(app->mu);
@@ -1281,9 +1294,25 @@ hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
   return HS_OK;
 }
 
-hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
-                          uint8_t* const* d_overlay_outs, uint64_t frame_id) {
-  const uint64_t t_submit = now_ns();
+// Marks the slot as in flight and wakes the completion thread (the last step of a submit).
+static void finish_submit(hs_app* app, Slot* s) {
+  const uint64_t t_enq = now_ns();
+  for (hs_result& r : s->results) r.t_enqueued_ns = t_enq;
+  {
+    std::lock_guard<std::mutex> lk(app->mu);
+    s->state = SLOT_INFLIGHT;
+    app->n_submitted++;
+  }
+  app->cv_work.notify_one();
+}
+
+// Enqueues stages 1-3 of one batch and, with own_overlay, stage 4 as well.  Without it the
+// caller draws the overlay (a group), records s->ev_overlay and calls finish_submit; *slot_out
+// and *stream_out then name the slot taken and the stream whose tail is the ev_post record.
+static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
+                               uint8_t* const* d_overlay_outs, uint64_t frame_id,
+                               uint64_t t_submit, bool own_overlay, Slot** slot_out,
+                               hipStream_t* stream_out) {
   if (!app || !d_frames || !d_overlay_outs) { set_error("hs_submit_batch: NULL argument"); return HS_E_INVAL; }
   const int B = app->batch;
   for (int j = 0; j < B; ++j) {
@@ -1373,20 +1402,33 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
     if (st != HS_OK) return st;
   }
   HS_HIP(hipEventRecord(s->ev_post, lane_stream));
+  if (!own_overlay) {
+    *slot_out = s;
+    *stream_out = lane_stream;
+    return HS_OK;
+  }
   hipStream_t ov_stream = app->s_overlay ? app->s_overlay : lane_stream;
   if (ov_stream != lane_stream) HS_HIP(hipStreamWaitEvent(ov_stream, s->ev_post, 0));
   st = run_ops(app, s->overlay, ov_stream);
   if (st != HS_OK) return st;
   HS_HIP(hipEventRecord(s->ev_overlay, ov_stream));
-  const uint64_t t_enq = now_ns();
-  for (int j = 0; j < B; ++j) s->results[j].t_enqueued_ns = t_enq;
-  {
-    std::lock_guard<std::mutex> lk(app->mu);
-    s->state = SLOT_INFLIGHT;
-    app->n_submitted++;
-  }
-  app->cv_work.notify_one();
+  finish_submit(app, s);
   return HS_OK;
+}
+
+static hs_status refuse_grouped(hs_app* app, const char* fn) {
+  if (app && app->group) {
+    set_error("%s: the application is a member of a group; use the hs_*_group calls", fn);
+    return HS_E_STATE;
+  }
+  return HS_OK;
+}
+
+hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
+                          uint8_t* const* d_overlay_outs, uint64_t frame_id) {
+  const uint64_t t_submit = now_ns();
+  if (refuse_grouped(app, "hs_submit_batch") != HS_OK) return HS_E_STATE;
+  return submit_stages(app, d_frames, d_overlay_outs, frame_id, t_submit, true, nullptr, nullptr);
 }
 
 hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
@@ -1418,6 +1460,7 @@ static hs_status deliver_locked(hs_app* app, hs_result* out) {
 
 hs_status hs_poll_batch(hs_app* app, hs_result* out) {
   if (!app || !out) { set_error("hs_poll_batch: NULL argument"); return HS_E_INVAL; }
+  if (refuse_grouped(app, "hs_poll_batch") != HS_OK) return HS_E_STATE;
   std::lock_guard<std::mutex> lk(app->mu);
   if (app->n_delivered >= app->n_completed) {
     set_error("hs_poll_batch: no finished frame");
@@ -1428,6 +1471,7 @@ hs_status hs_poll_batch(hs_app* app, hs_result* out) {
 
 hs_status hs_wait_batch(hs_app* app, hs_result* out, uint64_t timeout_ns) {
   if (!app || !out) { set_error("hs_wait_batch: NULL argument"); return HS_E_INVAL; }
+  if (refuse_grouped(app, "hs_wait_batch") != HS_OK) return HS_E_STATE;
   std::unique_lock<std::mutex> lk(app->mu);
   const bool ok = app->cv_done.wait_for(lk, std::chrono::nanoseconds(timeout_ns), [&] {
     return app->n_delivered < app->n_completed;
@@ -1453,6 +1497,138 @@ hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns) {
     return HS_E_STATE;
   }
   return hs_wait_batch(app, out, timeout_ns);
+}
+
+// ---- multi-network applications ---------------------------------------------------------------
+static_assert(HS_MAX_GROUP == kMaxLayers, "one overlay layer per group member");
+
+hs_status hs_create_group(hs_ctx* ctx, hs_app* const* members, int n_members, hs_group** out) {
+  if (!ctx || !members || !out) { set_error("hs_create_group: NULL argument"); return HS_E_INVAL; }
+  if (n_members < 1 || n_members > kMaxLayers) {
+    set_error("hs_create_group: %d members, 1..%d allowed", n_members, kMaxLayers);
+    return HS_E_INVAL;
+  }
+  for (int i = 0; i < n_members; ++i) {
+    hs_app* a = members[i];
+    if (!a || a->ctx != ctx) { set_error("hs_create_group: member %d is NULL or of another context", i); return HS_E_INVAL; }
+    for (int j = 0; j < i; ++j)
+      if (members[j] == a) { set_error("hs_create_group: member %d listed twice", i); return HS_E_INVAL; }
+    if (a->batch != 1) { set_error("hs_create_group: member %d batches %d streams", i, a->batch); return HS_E_INVAL; }
+    const hs_app_desc &d = a->desc, &d0 = members[0]->desc;
+    if (d.frame_w != d0.frame_w || d.frame_h != d0.frame_h || d.frame_pitch != d0.frame_pitch) {
+      set_error("hs_create_group: member %d takes another frame geometry than member 0", i);
+      return HS_E_INVAL;
+    }
+    if (a->group) { set_error("hs_create_group: member %d already belongs to a group", i); return HS_E_STATE; }
+    std::lock_guard<std::mutex> lk(a->mu);
+    if (a->n_delivered != a->n_submitted) {
+      set_error("hs_create_group: member %d has frames in flight or unpolled", i);
+      return HS_E_STATE;
+    }
+  }
+  hs_group* g = new (std::nothrow) hs_group();
+  if (!g) { set_error("hs_create_group: out of host memory"); return HS_E_NOMEM; }
+  g->ctx = ctx;
+  g->members.assign(members, members + n_members);
+  // the frame-level fields of the overlay launch come from member 0; layers are set per frame
+  Op o = members[0]->slots[0].overlay[0];
+  o.overlay.n_layers = n_members;
+  double map_bytes = 0;
+  for (hs_app* a : g->members) map_bytes += (double)a->map_w * a->map_h;
+  o.bytes = 6.0 * members[0]->desc.frame_w * members[0]->desc.frame_h + map_bytes;
+  g->overlay.push_back(o);
+  for (hs_app* a : g->members) a->group = g;
+  *out = g;
+  return HS_OK;
+}
+
+hs_status hs_destroy_group(hs_group* group) {
+  if (!group) { set_error("hs_destroy_group: NULL"); return HS_E_INVAL; }
+  for (hs_app* a : group->members) {   // frames in flight still need the group's bookkeeping
+    std::unique_lock<std::mutex> lk(a->mu);
+    a->cv_done.wait(lk, [&] { return a->n_completed == a->n_submitted; });
+  }
+  for (hs_app* a : group->members) a->group = nullptr;
+  delete group;
+  return HS_OK;
+}
+
+hs_status hs_submit_group(hs_group* group, const uint8_t* d_frame, uint8_t* d_overlay_out,
+                          uint64_t frame_id) {
+  const uint64_t t_submit = now_ns();
+  if (!group || !d_frame || !d_overlay_out) { set_error("hs_submit_group: NULL argument"); return HS_E_INVAL; }
+  const size_t n = group->members.size();
+  // nothing is enqueued unless every member can take the frame
+  for (size_t i = 0; i < n; ++i) {
+    hs_app* a = group->members[i];
+    std::lock_guard<std::mutex> lk(a->mu);
+    if (!a->completer_error.empty()) {
+      set_error("device error in an earlier frame: %s", a->completer_error.c_str());
+      return HS_E_DEVICE;
+    }
+    if (a->n_submitted - a->n_delivered >= (uint64_t)a->depth) {
+      set_error("hs_submit_group: queue of member %d full (%d slots)", (int)i, a->depth);
+      return HS_E_QUEUE_FULL;
+    }
+  }
+  Slot* slot[kMaxLayers];
+  hipStream_t tail[kMaxLayers];
+  OverlayParams& op = group->overlay[0].overlay;
+  for (size_t i = 0; i < n; ++i) {
+    hs_status st = submit_stages(group->members[i], &d_frame, &d_overlay_out, frame_id, t_submit,
+                                 false, &slot[i], &tail[i]);
+    if (st != HS_OK) return st;
+    op.layer[i] = slot[i]->overlay[0].overlay.layer[0];
+  }
+  op.src[0] = d_frame;
+  op.dst[0] = d_overlay_out;
+  // one launch draws every member's layer, on member 0's overlay stream, after all stage 3s
+  hs_app* a0 = group->members[0];
+  hipStream_t ov_stream = a0->s_overlay ? a0->s_overlay : tail[0];
+  for (size_t i = 0; i < n; ++i)
+    if (tail[i] != ov_stream) HS_HIP(hipStreamWaitEvent(ov_stream, slot[i]->ev_post, 0));
+  hs_status st = run_ops(a0, group->overlay, ov_stream);
+  if (st != HS_OK) return st;
+  for (size_t i = 0; i < n; ++i) HS_HIP(hipEventRecord(slot[i]->ev_overlay, ov_stream));
+  for (size_t i = 0; i < n; ++i) finish_submit(group->members[i], slot[i]);
+  return HS_OK;
+}
+
+// Delivers one frame's results of all members if every member has finished it.
+static hs_status deliver_group(hs_group* group, hs_result* out) {
+  for (hs_app* a : group->members) {
+    std::lock_guard<std::mutex> lk(a->mu);
+    if (a->n_delivered >= a->n_completed) {
+      set_error("hs_poll_group: no finished frame");
+      return HS_E_NOT_READY;
+    }
+  }
+  hs_status worst = HS_OK;
+  for (size_t i = 0; i < group->members.size(); ++i) {
+    hs_app* a = group->members[i];
+    std::lock_guard<std::mutex> lk(a->mu);
+    const hs_status st = deliver_locked(a, out + i);
+    if (st != HS_OK) worst = st;
+  }
+  return worst;
+}
+
+hs_status hs_poll_group(hs_group* group, hs_result* out) {
+  if (!group || !out) { set_error("hs_poll_group: NULL argument"); return HS_E_INVAL; }
+  return deliver_group(group, out);
+}
+
+hs_status hs_wait_group(hs_group* group, hs_result* out, uint64_t timeout_ns) {
+  if (!group || !out) { set_error("hs_wait_group: NULL argument"); return HS_E_INVAL; }
+  const auto deadline = std::chrono::steady_clock::now() + std::chrono::nanoseconds(timeout_ns);
+  for (hs_app* a : group->members) {
+    std::unique_lock<std::mutex> lk(a->mu);
+    if (!a->cv_done.wait_until(lk, deadline, [&] { return a->n_delivered < a->n_completed; })) {
+      set_error("hs_wait_group: timed out");
+      return HS_E_NOT_READY;
+    }
+  }
+  return deliver_group(group, out);
 }
 
 hs_status hs_set_launch_mode(hs_app* app, int mode) {

@@ -1,7 +1,8 @@
 """Small harness over the binding: PyTorch supplies device memory (workspace, frames,
 overlay outputs); everything that computes runs inside libhs.
 
-``AppStream`` is one application stream (paper Section III-A); ``run_paced`` drives several
+``AppStream`` is one application stream (paper Section III-A), ``GroupStream`` a multi-network
+application (Section III-B); ``run_paced`` drives several
 of them concurrently at a fixed frame rate, one submitting thread per stream, the way the
 paper runs one process per application instance (Section V-B).
 """
@@ -140,6 +141,51 @@ class AppStream:
             api.hs_destroy_app(self.app)
             self.app = None
             self._held.clear()
+
+
+class GroupStream:
+    """A multi-network application (paper Section III-B): AppStream members that all look at the
+    same frame and share one overlay launch.  Offers the batch-style calls run_paced uses; a
+    result is the list of the members' hs_result for one frame (member order)."""
+
+    def __init__(self, ctx: int, members):
+        self.members = list(members)
+        self.group = api.hs_create_group(ctx, [m.app for m in self.members])
+        self.batch = 1
+        self._held = {}
+        m0 = self.members[0]
+        self.frame_w, self.frame_h, self.frame_pitch = m0.frame_w, m0.frame_h, m0.frame_pitch
+        self.upload_frame, self.new_output = m0.upload_frame, m0.new_output
+
+    def submit(self, d_frame: torch.Tensor, d_out: torch.Tensor, frame_id: int) -> int:
+        st = api.hs_submit_group(self.group, d_frame.data_ptr(), d_out.data_ptr(), frame_id)
+        if st == api.HS_OK:
+            self._held[frame_id] = (d_frame, d_out)
+        return st
+
+    def submit_batch(self, d_frames, d_outs, frame_id: int) -> int:
+        return self.submit(d_frames[0], d_outs[0], frame_id)
+
+    def poll_batch(self):
+        rs = api.hs_poll_group(self.group, len(self.members))
+        if rs is not None:
+            self._held.pop(rs[0].frame_id, None)
+        return rs
+
+    def wait_batch(self, timeout_s: float = 30.0):
+        rs = api.hs_wait_group(self.group, len(self.members), int(timeout_s * 1e9))
+        if rs is None:
+            raise TimeoutError("no result within %.1f s" % timeout_s)
+        self._held.pop(rs[0].frame_id, None)
+        return rs
+
+    def close(self):
+        if self.group:
+            api.hs_destroy_group(self.group)
+            self.group = None
+        for m in self.members:
+            m.close()
+        self._held.clear()
 
 
 def run_paced(streams, frames, fps: float, outputs, pin_cpus=None):
