@@ -263,7 +263,9 @@ hs_status hs_wait_batch(hs_app* app, hs_result* out, uint64_t timeout_ns);
  * context (each created with hs_create_app: own network, network input size, threshold,
  * palette, alpha, annotation settings, workspace; batch 1; identical frame_w, frame_h and
  * frame_pitch).  hs_submit_group hands ONE frame to all members: each runs stages 1-3 on its
- * own stream(s), side by side on the GPU, and a single stage-4 launch, on member 0's overlay
+ * own stream(s), side by side on the GPU (member 0's work is enqueued by the calling thread,
+ * every other member's by a thread of its own, as the paper's inference operator spawns one CPU
+ * thread per parallel inference), and a single stage-4 launch, on member 0's overlay
  * stream after every member's stage 3, draws the members' layers in member order -- a
  * member's mask blend, then its annotations, each layer over the picture the previous one
  * left -- into d_overlay_out (the frame is read once and written once).
@@ -321,7 +323,9 @@ hs_status hs_mann_whitney_u(const double* a, size_t na, const double* b, size_t 
 
 /* Pin the application's completion thread (the one that observes the end of a frame and
  * stamps its departure) to one CPU core, cpu = -1 lifts the pin (paper Section IV-C, CPU
- * affinity). The caller pins its own submitting thread with sched_setaffinity.
+ * affinity). The caller pins its own submitting thread with sched_setaffinity. For a member
+ * of a group (call it after hs_create_group) the thread that enqueues this member's stages is
+ * pinned to the same core.
  * HS_E_INVAL if the core does not exist or the operating system refuses. */
 hs_status hs_set_cpu_affinity(hs_app* app, int cpu);
 

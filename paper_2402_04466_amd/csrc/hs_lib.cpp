@@ -197,10 +197,31 @@ struct hs_app {
 
 // A multi-network application: the members run stages 1-3 on the same frame side by side, one
 // overlay launch of the group draws all their layers.
+// The paper's inference operator launches the parallel inferences from one CPU thread each
+// (Section III-B); likewise every member but the first has a thread that enqueues its stages
+// 1-3 while the caller's thread enqueues the first member's, so the host launch costs overlap.
+struct GroupWorker {
+  std::thread th;
+  std::mutex mu;
+  std::condition_variable cv;
+  bool has_job = false, done = false, stop = false;
+  // the job: one frame for member `app`
+  hs_app* app = nullptr;
+  const uint8_t* d_frame = nullptr;
+  uint8_t* d_out = nullptr;
+  uint64_t frame_id = 0, t_submit = 0;
+  // its outcome
+  hs_status status = HS_OK;
+  std::string error;
+  Slot* slot = nullptr;
+  hipStream_t tail = nullptr;
+};
+
 struct hs_group {
   hs_ctx* ctx = nullptr;
   std::vector<hs_app*> members;
   std::vector<Op> overlay;   // one op; its layers are refilled from the members' slots per frame
+  std::vector<std::unique_ptr<GroupWorker>> workers;   // workers[i] serves members[i + 1]
 };
 
 namespace hs {
@@ -1502,6 +1523,27 @@ hs_status hs_wait_result(hs_app* app, hs_result* out, uint64_t timeout_ns) {
 // ---- multi-network applications ---------------------------------------------------------------
 static_assert(HS_MAX_GROUP == kMaxLayers, "one overlay layer per group member");
 
+static void group_worker_main(GroupWorker* w, int device) {
+  (void)hipSetDevice(device);
+  for (;;) {
+    {
+      std::unique_lock<std::mutex> lk(w->mu);
+      w->cv.wait(lk, [&] { return w->has_job || w->stop; });
+      if (!w->has_job) return;
+      w->has_job = false;
+    }
+    const hs_status st = submit_stages(w->app, &w->d_frame, &w->d_out, w->frame_id, w->t_submit,
+                                       false, &w->slot, &w->tail);
+    {
+      std::lock_guard<std::mutex> lk(w->mu);
+      w->status = st;
+      if (st != HS_OK) w->error = hs_last_error();
+      w->done = true;
+    }
+    w->cv.notify_all();
+  }
+}
+
 hs_status hs_create_group(hs_ctx* ctx, hs_app* const* members, int n_members, hs_group** out) {
   if (!ctx || !members || !out) { set_error("hs_create_group: NULL argument"); return HS_E_INVAL; }
   if (n_members < 1 || n_members > kMaxLayers) {
@@ -1537,6 +1579,12 @@ hs_status hs_create_group(hs_ctx* ctx, hs_app* const* members, int n_members, hs
   for (hs_app* a : g->members) map_bytes += (double)a->map_w * a->map_h;
   o.bytes = 6.0 * members[0]->desc.frame_w * members[0]->desc.frame_h + map_bytes;
   g->overlay.push_back(o);
+  for (int i = 1; i < n_members; ++i) {
+    g->workers.emplace_back(new GroupWorker());
+    GroupWorker* w = g->workers.back().get();
+    w->app = members[i];
+    w->th = std::thread(group_worker_main, w, ctx->device);
+  }
   for (hs_app* a : g->members) a->group = g;
   *out = g;
   return HS_OK;
@@ -1547,6 +1595,14 @@ hs_status hs_destroy_group(hs_group* group) {
   for (hs_app* a : group->members) {   // frames in flight still need the group's bookkeeping
     std::unique_lock<std::mutex> lk(a->mu);
     a->cv_done.wait(lk, [&] { return a->n_completed == a->n_submitted; });
+  }
+  for (auto& w : group->workers) {
+    {
+      std::lock_guard<std::mutex> lk(w->mu);
+      w->stop = true;
+    }
+    w->cv.notify_all();
+    w->th.join();
   }
   for (hs_app* a : group->members) a->group = nullptr;
   delete group;
@@ -1574,12 +1630,28 @@ hs_status hs_submit_group(hs_group* group, const uint8_t* d_frame, uint8_t* d_ov
   Slot* slot[kMaxLayers];
   hipStream_t tail[kMaxLayers];
   OverlayParams& op = group->overlay[0].overlay;
-  for (size_t i = 0; i < n; ++i) {
-    hs_status st = submit_stages(group->members[i], &d_frame, &d_overlay_out, frame_id, t_submit,
-                                 false, &slot[i], &tail[i]);
-    if (st != HS_OK) return st;
-    op.layer[i] = slot[i]->overlay[0].overlay.layer[0];
+  for (auto& w : group->workers) {   // members 1.. on their own threads
+    {
+      std::lock_guard<std::mutex> lk(w->mu);
+      w->d_frame = d_frame; w->d_out = d_overlay_out;
+      w->frame_id = frame_id; w->t_submit = t_submit;
+      w->done = false;
+      w->has_job = true;
+    }
+    w->cv.notify_all();
   }
+  hs_status st0 = submit_stages(group->members[0], &d_frame, &d_overlay_out, frame_id, t_submit,
+                                false, &slot[0], &tail[0]);
+  std::string err0 = st0 != HS_OK ? hs_last_error() : "";
+  for (size_t i = 1; i < n; ++i) {   // always collect every worker, also after a failure
+    GroupWorker* w = group->workers[i - 1].get();
+    std::unique_lock<std::mutex> lk(w->mu);
+    w->cv.wait(lk, [&] { return w->done; });
+    slot[i] = w->slot; tail[i] = w->tail;
+    if (st0 == HS_OK && w->status != HS_OK) { st0 = w->status; err0 = w->error; }
+  }
+  if (st0 != HS_OK) { set_error("%s", err0.c_str()); return st0; }
+  for (size_t i = 0; i < n; ++i) op.layer[i] = slot[i]->overlay[0].overlay.layer[0];
   op.src[0] = d_frame;
   op.dst[0] = d_overlay_out;
   // one launch draws every member's layer, on member 0's overlay stream, after all stage 3s
@@ -1653,7 +1725,13 @@ hs_status hs_set_cpu_affinity(hs_app* app, int cpu) {
     if (cpu >= CPU_SETSIZE) { set_error("hs_set_cpu_affinity: no such core %d", cpu); return HS_E_INVAL; }
     CPU_SET(cpu, &set);
   }
-  const int rc = pthread_setaffinity_np(app->completer.native_handle(), sizeof(set), &set);
+  int rc = pthread_setaffinity_np(app->completer.native_handle(), sizeof(set), &set);
+  if (rc == 0 && app->group) {   // a group member's submitting thread follows its completion thread
+    const auto& m = app->group->members;
+    const size_t i = (size_t)(std::find(m.begin(), m.end(), app) - m.begin());
+    if (i >= 1 && i < m.size())
+      rc = pthread_setaffinity_np(app->group->workers[i - 1]->th.native_handle(), sizeof(set), &set);
+  }
   if (rc != 0) {
     set_error("hs_set_cpu_affinity: core %d refused (%s)", cpu, strerror(rc));
     return HS_E_INVAL;
