@@ -971,13 +971,41 @@ KernelDesc describe(const PostParams& p) {
 // =============================================================================================
 // One layer of stage 4 applied to a group of 16 pixels held in registers (w[0..11], word j starts
 // with channel j mod 3): blend of the layer's channel map, then its annotations.
-__device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, const OverlayLayer& L,
-                                                    uint32_t (&w)[12], int Y, int X0, int by) {
+// Colour of channel k (0..7).  A select chain over the eight scalar palette words: indexing the
+// kernel-argument array with a per-lane k would be a vector load from memory, one more full
+// memory latency between the channel byte and the blend.
+__device__ __forceinline__ uint32_t overlay_colour(const OverlayLayer& L, uint32_t k) {
+  uint32_t c = L.pal[0];
+#pragma unroll
+  for (uint32_t i = 1; i < 8; ++i) c = k == i ? L.pal[i] : c;
+  return c;
+}
+
+// The channel-map cells a group of 16 pixels starting at (X0, Y) can see in layer L: its first
+// cell, and the two channel bytes fetched up front (a third cell, on tiny frames, on demand).
+struct OverlayCells {
+  const uint8_t* krow;
+  int mx0;
+  uint8_t k0, k1;
+};
+__device__ __forceinline__ OverlayCells overlay_cells(const OverlayParams& p, const OverlayLayer& L,
+                                                      int Y, int X0, int by) {
+  OverlayCells c;
   const int my = (int)udiv_est((uint32_t)(Y * L.hm), (uint32_t)p.hf, p.rcp_hf);
-  const uint8_t* krow = L.kmap + ((size_t)by * L.hm + my) * L.wm;
+  c.krow = L.kmap + ((size_t)by * L.hm + my) * L.wm;
+  c.mx0 = (int)udiv_est((uint32_t)(X0 * L.wm), (uint32_t)p.wf, p.rcp_wf);
+  c.k0 = c.krow[c.mx0];
+  c.k1 = c.krow[min(c.mx0 + 1, L.wm - 1)];
+  return c;
+}
+
+__device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, const OverlayLayer& L,
+                                                    const OverlayCells& cells, uint32_t (&w)[12],
+                                                    int Y, int X0, int by) {
+  const uint8_t* krow = cells.krow;
   const int ia = 256 - L.a;
-  const int mx0 = (int)udiv_est((uint32_t)(X0 * L.wm), (uint32_t)p.wf, p.rcp_wf);
-  const uint8_t k0 = krow[mx0], k1 = krow[min(mx0 + 1, L.wm - 1)];
+  const int mx0 = cells.mx0;
+  const uint8_t k0 = cells.k0, k1 = cells.k1;
   // Most groups see one channel for all 16 pixels: nothing to draw, or one colour.  Then the
   // blend runs on two bytes per 32-bit operation: even and odd bytes of a word are 16-bit
   // fields, (256 - a) * byte + (a * colour + 128) never exceeds 65408, so no field carries into
@@ -986,7 +1014,7 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
   const bool one_cell = mx_last == mx0 || (mx_last == mx0 + 1 && k1 == k0);
   if (one_cell) {
     if (k0 != 0xff) {
-      const uint32_t col = L.pal[k0];
+      const uint32_t col = overlay_colour(L, k0);
       uint32_t t[3];
 #pragma unroll
       for (int c = 0; c < 3; ++c) t[c] = (uint32_t)L.a * ((col >> (8 * c)) & 0xffu) + 128u;
@@ -1004,7 +1032,8 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
     // term chosen per byte (byte index < 3*s), then bytes of an undrawn cell are restored.
     const int rem = X0 * L.wm - mx0 * p.wf;
     const int s3 = 3 * (int)udiv_est((uint32_t)(p.wf - rem + L.wm - 1), (uint32_t)L.wm, L.rcp_wm);
-    const uint32_t c0 = k0 != 0xff ? L.pal[k0 & 7] : 0u, c1 = k1 != 0xff ? L.pal[k1 & 7] : 0u;
+    const uint32_t c0 = k0 != 0xff ? overlay_colour(L, k0) : 0u;
+    const uint32_t c1 = k1 != 0xff ? overlay_colour(L, k1) : 0u;
     const uint32_t d0 = k0 != 0xff ? 0xffffffffu : 0u, d1 = k1 != 0xff ? 0xffffffffu : 0u;
     uint32_t t0[3], t1[3];
 #pragma unroll
@@ -1033,7 +1062,7 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
     for (int i = 0; i < 16; ++i) {
       const uint8_t k = mx == mx0 ? k0 : (mx == mx0 + 1 ? k1 : krow[mx]);
       if (k != 0xff) {
-        const uint32_t col = L.pal[k];
+        const uint32_t col = overlay_colour(L, k);
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
           const int byte = 3 * i + c;                 // literal after unrolling
@@ -1120,10 +1149,10 @@ __device__ __forceinline__ void overlay_layer_pixel(const OverlayParams& p, cons
 #pragma unroll
   for (int c = 0; c < 3; ++c) {
     if (k != 0xff) {
-      const uint32_t pc = (L.pal[k] >> (8 * c)) & 0xffu;
+      const uint32_t pc = (overlay_colour(L, k) >> (8 * c)) & 0xffu;
       x[c] = (L.a * pc + (256 - L.a) * x[c] + 128u) >> 8;
     }
-    if (paint >= 0) x[c] = (L.pal[paint] >> (8 * c)) & 0xffu;
+    if (paint >= 0) x[c] = (overlay_colour(L, (uint32_t)paint) >> (8 * c)) & 0xffu;
   }
 }
 
@@ -1148,6 +1177,8 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
   const int npx = min(16, p.wf - X0);
   const int nl = LAYERS ? p.n_layers : 1;
   if (npx == 16) {
+    // the first layer's map bytes are requested before the pixels, so the two fetches overlap
+    const OverlayCells first = overlay_cells(p, p.layer[0], Y, X0, (int)blockIdx.y);
     u32x4 v[3];
     if (coalesced) {
       // the wavefront's 64 groups are 3072 contiguous bytes: fetch them as 3 x 64 consecutive
@@ -1166,11 +1197,12 @@ __global__ __launch_bounds__(256) void k_overlay(OverlayParams p) {
     uint32_t w[12];
 #pragma unroll
     for (int i = 0; i < 12; ++i) w[i] = v[i >> 2][i & 3];
+    overlay_layer_group(p, p.layer[0], first, w, Y, X0, (int)blockIdx.y);
     if (LAYERS) {
 #pragma unroll 1
-      for (int l = 0; l < nl; ++l) overlay_layer_group(p, p.layer[l], w, Y, X0, (int)blockIdx.y);
-    } else {
-      overlay_layer_group(p, p.layer[0], w, Y, X0, (int)blockIdx.y);
+      for (int l = 1; l < nl; ++l)
+        overlay_layer_group(p, p.layer[l], overlay_cells(p, p.layer[l], Y, X0, (int)blockIdx.y), w,
+                            Y, X0, (int)blockIdx.y);
     }
     if (coalesced) {
 #pragma unroll

@@ -12,6 +12,8 @@
 #include <cstring>
 #include <memory>
 #include <mutex>
+#include <new>
+#include <stdexcept>
 #include <string>
 #include <thread>
 #include <pthread.h>
@@ -627,9 +629,9 @@ static hs_status validate_desc(const hs_app_desc* d) {
     set_error("unknown network kind %d", d->net);
     return HS_E_INVAL;
   }
-  if (!(d->std > 0.0f) || !(d->threshold > 0.0f && d->threshold < 1.0f) ||
-      !(d->alpha >= 0.0f && d->alpha <= 1.0f)) {
-    set_error("std must be > 0, threshold in (0,1), alpha in [0,1]");
+  if (!std::isfinite(d->mean) || !(d->std > 0.0f) || !std::isfinite(d->std) ||
+      !(d->threshold > 0.0f && d->threshold < 1.0f) || !(d->alpha >= 0.0f && d->alpha <= 1.0f)) {
+    set_error("mean must be finite, std finite and > 0, threshold in (0,1), alpha in [0,1]");
     return HS_E_INVAL;
   }
   if (d->annotate && (d->marker_arm < 0 || d->marker_arm > 64 || d->marker_half < 0 ||
@@ -1050,6 +1052,21 @@ static hs_status build_slot_graph(Slot& s, hipEvent_t wait_ev) {
 }  // namespace hs
 
 // ================================================================================================
+// No C++ exception may cross the C boundary: calls that allocate host memory or start threads
+// run inside this guard.
+template <class F>
+static hs_status guarded(const char* fn, F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    hs::set_error("%s: out of host memory", fn);
+    return HS_E_NOMEM;
+  } catch (const std::exception& e) {
+    hs::set_error("%s: %s", fn, e.what());
+    return HS_E_DEVICE;
+  }
+}
+
 extern "C" {
 
 hs_status hs_init(int device, hs_ctx** out) {
@@ -1109,13 +1126,16 @@ hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t byt
 }
 
 hs_status hs_query_workspace(const hs_app_desc* desc, size_t* bytes) {
+  return guarded("hs_query_workspace", [&]() -> hs_status {
   if (!bytes) { set_error("hs_query_workspace: NULL bytes"); return HS_E_INVAL; }
   hs_status st = validate_desc(desc);
   if (st != HS_OK) return st;
   return build_plan(desc, nullptr, bytes);
+  });
 }
 
 hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
+  return guarded("hs_create_app", [&]() -> hs_status {
   if (!ctx || !out) { set_error("hs_create_app: NULL argument"); return HS_E_INVAL; }
   *out = nullptr;
   hs_status st = validate_desc(desc);
@@ -1130,7 +1150,8 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
     return HS_E_INVAL;
   }
   HS_HIP(hipSetDevice(ctx->device));
-  hs_app* app = new hs_app();
+  hs_app* app = new (std::nothrow) hs_app();
+  if (!app) { set_error("hs_create_app: out of host memory"); return HS_E_NOMEM; }
   app->ctx = ctx;
   app->desc = *desc;
   app->desc.weights = nullptr;   // not retained
@@ -1153,6 +1174,7 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
       if (s.ev_overlay) (void)hipEventDestroy(s.ev_overlay);
       if (s.ev_state) (void)hipEventDestroy(s.ev_state);
     }
+    destroy_streams(app);
     if (app->pinned) (void)hipHostFree(app->pinned);
     delete app;
     return st;
@@ -1164,6 +1186,7 @@ hs_status hs_create_app(hs_ctx* ctx, const hs_app_desc* desc, hs_app** out) {
   }
   *out = app;
   return HS_OK;
+  });
 }
 
 hs_status hs_destroy_app(hs_app* app) {
@@ -1268,6 +1291,7 @@ hs_status hs_get_features(hs_app* app, int stream, float* x_out) {
 
 hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
                            const uint32_t* cu_mask_overlay, int n_words) {
+  return guarded("hs_set_partition", [&]() -> hs_status {
   if (!app) { set_error("hs_set_partition: NULL app"); return HS_E_INVAL; }
   if ((cu_mask_infer == nullptr) != (cu_mask_overlay == nullptr)) {
     set_error("hs_set_partition: give both masks or neither");
@@ -1313,6 +1337,7 @@ hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
   for (int w = 0; w < n_words; ++w) app->claim[w] = cu_mask_infer[w] | cu_mask_overlay[w];
   app->partitioned = true;
   return HS_OK;
+  });
 }
 
 // Marks the slot as in flight and wakes the completion thread (the last step of a submit).
@@ -1545,6 +1570,7 @@ static void group_worker_main(GroupWorker* w, int device) {
 }
 
 hs_status hs_create_group(hs_ctx* ctx, hs_app* const* members, int n_members, hs_group** out) {
+  return guarded("hs_create_group", [&]() -> hs_status {
   if (!ctx || !members || !out) { set_error("hs_create_group: NULL argument"); return HS_E_INVAL; }
   if (n_members < 1 || n_members > kMaxLayers) {
     set_error("hs_create_group: %d members, 1..%d allowed", n_members, kMaxLayers);
@@ -1588,6 +1614,7 @@ hs_status hs_create_group(hs_ctx* ctx, hs_app* const* members, int n_members, hs
   for (hs_app* a : g->members) a->group = g;
   *out = g;
   return HS_OK;
+  });
 }
 
 hs_status hs_destroy_group(hs_group* group) {
