@@ -443,3 +443,65 @@ def test_kernel_timing_reports_every_family(hs, ctx):
         assert abs(t["conv_mfma"]["flops"] / 3 - 36.6e6) < 0.5e6     # 36.6 MFLOP per frame
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("partition", ["none", "shared", "split"])
+def test_concurrent_paced_streams_match_solo_runs(hs, ctx, partition):
+    """Configurations 3 and 4 in the way the benchmark drives them: several applications, one
+    submitting thread each, paced at a fixed rate and overlapping on the GPU, unpartitioned or
+    on disjoint CU sets (one stream per partition, or inference / overlay on separate sets).
+    Every frame of every stream must equal, bit for bit, what the same application computes
+    when it runs alone (the recurrent state makes frame k depend on frames 0..k-1), and the
+    first frame is checked against the oracle."""
+    from paper_2402_04466_amd.harness import AppStream, run_paced
+    fw, fh = 640, 360
+    specs = [("resnet18_convlstm", hs.HS_NET_RESNET18_CONVLSTM, si.RESNET18_CONVLSTM_LAYERS, 224, 128),
+             ("tiny4", hs.HS_NET_TINY4, si.TINY4_LAYERS, 128, 128),
+             ("resnet18_convlstm", hs.HS_NET_RESNET18_CONVLSTM, si.RESNET18_CONVLSTM_LAYERS, 160, 96),
+             ("tiny4", hs.HS_NET_TINY4, si.TINY4_LAYERS, 96, 64)]
+    n_frames = depth = 12      # one queue slot per frame: every frame's buffers stay readable
+    n_cus = hs.hs_device_cus(ctx)
+    apps, frames, blobs = [], [], []
+    try:
+        for i, (name, net, layers, nw, nh) in enumerate(specs):
+            blob = si.he_normal_blob(layers, 10 + i)
+            blobs.append(blob)
+            apps.append(AppStream(ctx, net=net, frame_w=fw, frame_h=fh, net_w=nw, net_h=nh,
+                                  blob=blob, palette=PAL, queue_depth=depth))
+            frames.append([apps[-1].upload_frame(f)
+                           for f in si.tool_scene_frames(n_frames, fh, fw, 60 + i)])
+        host_frames = [list(si.tool_scene_frames(1, fh, fw, 60 + i))[0] for i in range(len(specs))]
+        # solo reference: one application at a time, one frame at a time
+        solo = []
+        for a, fr in zip(apps, frames):
+            per = []
+            for k, d_in in enumerate(fr):
+                o = a.new_output()
+                assert a.submit(d_in, o, k) == hs.HS_OK
+                per.append(a.fetch(a.wait(), o))
+            solo.append(per)
+            hs.hs_reset_state(a.app)
+        if partition != "none":
+            per_app = (n_cus // 8 // len(apps)) * 8
+            for i, a in enumerate(apps):
+                cus = list(range(i * per_app, (i + 1) * per_app))
+                ci, co = (cus, cus) if partition == "shared" else (cus[:-8], cus[-8:])
+                hs.hs_set_partition(a.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+        outs = [[[a.new_output()] for _ in range(n_frames)] for a in apps]
+        print(f"[concurrent {partition}] {len(apps)} applications x {n_frames} frames", flush=True)
+        results, dropped = run_paced(apps, [[[t] for t in fr] for fr in frames], 2000.0, outs)
+        assert sum(dropped) == 0
+        for i, (a, rs) in enumerate(zip(apps, results)):
+            assert [r[0].frame_id for r in rs] == list(range(n_frames))
+            for k, r in enumerate(rs):
+                g = a.fetch(r[0], outs[i][k][0])
+                for key in ("net_input", "logits", "heat", "mask", "argmax_idx", "present", "overlay"):
+                    assert np.array_equal(g[key], solo[i][k][key]), (partition, i, k, key)
+        for i, (name, net, layers, nw, nh) in enumerate(specs):
+            o32, _ = make_oracles(name, blobs[i], nw, nh, True, PAL)
+            check_frame(solo[i][0], host_frames[i], o32.process(host_frames[i]), None,
+                        threshold=0.5, alpha=0.5, palette=PAL, fp32_input=False,
+                        tag=f"concurrent/{i}")
+    finally:
+        for a in apps:
+            a.close()
