@@ -78,8 +78,9 @@ def parse():
                          "and pool the trimmed latencies, as the paper pools its repeated runs")
     ap.add_argument("--distinct-frames", type=int, default=8)
     ap.add_argument("--queue-depth", type=int, default=4)
-    ap.add_argument("--launch-mode", choices=["graph", "eager"], default="graph",
-                    help="stages 1-3 as one HIP graph per frame, or kernel by kernel")
+    ap.add_argument("--launch-mode", choices=["graph", "eager"], default="eager",
+                    help="stages 1-3 kernel by kernel (the library's default: lowest latency), "
+                         "or as one HIP graph per frame")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="first run the library's plain copy kernel 4 times over this many MiB "
                          "(reference dispatches for scaling rocprofv3 byte counters)")

@@ -187,7 +187,7 @@ struct hs_app {
   std::thread completer;
   bool stop = false;
   std::string completer_error;
-  int launch_mode = HS_LAUNCH_GRAPH;
+  int launch_mode = HS_LAUNCH_EAGER;
   // kernel timing
   bool timing = false;
   std::vector<TimedLaunch> timed;

@@ -92,14 +92,18 @@ def test_group_of_three_networks_matches_oracle(hs, ctx, fw, fh):
         grp.close()
 
 
-def test_group_equals_members_run_alone_and_calls_are_guarded(hs, ctx):
-    """Two frames in flight through a group (depth 2, no wait in between) give bit-identical
-    per-member outputs to the same applications run alone; grouped members refuse direct calls."""
+@pytest.mark.parametrize("mode", ["HS_LAUNCH_EAGER", "HS_LAUNCH_GRAPH"])
+def test_group_equals_members_run_alone_and_calls_are_guarded(hs, ctx, mode):
+    """Two frames in flight through a group (depth 2, no wait in between; members launched kernel
+    by kernel or as graphs) give bit-identical per-member outputs to the same applications run
+    alone; grouped members refuse direct calls."""
     from paper_2402_04466_amd import api
     fw, fh = 640, 360
     specs = _specs(fw, fh)
     frames = si.uniform_frames(4, fh, fw, 41)
     grp, _ = _build(hs, ctx, specs, fw, fh, depth=2)
+    for m in grp.members:
+        hs.hs_set_launch_mode(m.app, getattr(hs, mode))
     solo, _ = _build(hs, ctx, specs, fw, fh, depth=2)
     api.hs_destroy_group(solo.group)      # the same three applications, ungrouped
     solo.group = None

@@ -229,7 +229,6 @@ def test_config5_full_size_batch12_sampled_streams(hs, ctx):
     frames = {j: list(si.tool_scene_frames(T, 1080, 1920, 13 + j)) for j in range(B)}
     s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=1920, frame_h=1080, net_w=854,
                   net_h=480, blob=blob, palette=PAL, queue_depth=2, batch=B)
-    hs.hs_set_launch_mode(s.app, hs.HS_LAUNCH_GRAPH)
     oracles = {j: make_oracles("resnet18_convlstm", blob, 854, 480, True, PAL) for j in sampled}
     try:
         for t in range(T):
@@ -255,7 +254,8 @@ def test_config5_full_size_batch12_sampled_streams(hs, ctx):
 
 
 @pytest.mark.parametrize("mode,depth", [("HS_LAUNCH_GRAPH", 4), ("HS_LAUNCH_EAGER", 4),
-                                        ("HS_LAUNCH_GRAPH", 2), ("HS_LAUNCH_GRAPH", 3)])
+                                        ("HS_LAUNCH_GRAPH", 2), ("HS_LAUNCH_GRAPH", 3),
+                                        ("HS_LAUNCH_EAGER", 2), ("HS_LAUNCH_EAGER", 3)])
 def test_back_to_back_frames_overlap_and_match_one_at_a_time(hs, ctx, mode, depth):
     """Consecutive frames of one stream run in two lanes and may overlap on the GPU; only the
     recurrent cell chains them.  Eight frames submitted as fast as the queue takes them must give,
