@@ -118,6 +118,7 @@ def main():
     import torch
     import paper_2402_04466_amd as hs
     from paper_2402_04466_amd.harness import AppStream, GroupStream, run_paced
+    from paper_2402_04466_amd.harness import run_back_to_back as harness_back_to_back
     import synth_inputs as si
 
     FW, FH, NW, NH = 1920, 1080, 854, 480
@@ -210,26 +211,15 @@ def main():
     torch.cuda.synchronize()
 
     def run_back_to_back(n_frames: int):
-        """Every stream submits n_frames as fast as its queue allows; returns elapsed s."""
-        def worker(i):
-            s, fr, ou = streams[i], frames[i], outs[i]
-            done = 0
-            for k in range(n_frames):
-                while s.submit_batch(fr[k % len(fr)], ou[k % len(ou)], k) != hs.HS_OK:
-                    s.wait_batch()
-                    done += 1
-            while done < n_frames:
-                s.wait_batch()
-                done += 1
-        th = [threading.Thread(target=worker, args=(i,)) for i in range(len(streams))]
+        """Every stream submits n_frames as fast as its queue allows (the library's native
+        driver, one submitting thread per application).  Returns elapsed s: the driver's own
+        clock from starting the submitting threads to collecting the last result, bracketed by
+        device synchronisation on both sides (the interpreter's pauses -- a garbage collection
+        can take 40 ms -- stay out of the timed region)."""
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for t in th:
-            t.start()
-        for t in th:
-            t.join()
+        _, elapsed = harness_back_to_back(streams, frames, outs, n_frames)
         torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        return elapsed
 
     # ---- throughput: W warm-up steps, then exactly K timed steps per stream ---------------
     run_back_to_back(args.warmup)
@@ -272,14 +262,16 @@ def main():
                 hs.hs_set_cpu_affinity(a, cores[(2 * i + 1) % len(cores)])
     tiny_paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
                   for f in tiny_frames]
-    lat_ms, tl, dropped, results = [], [], [], []
+    lat_ms, tl, dropped, results, kept, lateness_us = [], [], [], [], [], []
     for rep in range(max(1, args.repeats)):
         if rep:
             for s in streams + tiny:
                 for a in apps_of(s):
                     hs.hs_reset_state(a)
-        res_all, drop = run_paced(streams + tiny, paced + tiny_paced, args.fps, outs + tiny_outs,
-                                  pin_cpus=pins)
+        res_all, drop, late = run_paced(streams + tiny, paced + tiny_paced, args.fps,
+                                        outs + tiny_outs, pin_cpus=pins,
+                                        n_frames=args.paced_frames, with_lateness=True)
+        lateness_us.extend(v / 1e3 for per in late for v in per)
         dropped.extend(drop)
         tiny_results, results = res_all[len(streams):], res_all[:len(streams)]
         for rs in tiny_results:
@@ -287,9 +279,10 @@ def main():
             t = min(10, len(per) // 6)
             tl.extend(per[t:len(per) - t])
         for rs in results:
+            t = min(10, len(rs) // 6)
+            kept.extend((rep, k, r[0]) for k, r in list(enumerate(rs))[t:len(rs) - t])
             for j in range(args.batch):
                 per = [(r[j].t_overlay_done_ns - r[j].t_submit_ns) / 1e6 for r in rs]
-                t = min(10, len(per) // 6)
                 lat_ms.extend(per[t:len(per) - t])   # trim each stream's warm-up / cool-down
     tiny_m = None
     if tiny:
@@ -321,6 +314,16 @@ def main():
                        ("overlay", "t_post_done_ns", "t_overlay_done_ns")):
         v = [(getattr(r[0], b) - getattr(r[0], a)) / 1e6 for rs in results for r in rs]
         stage_ms[name] = round(float(np.median(v)), 4)
+    # where the slowest kept frame spent its time (a late completion stamp, i.e.
+    # host scheduling, shows up in "pre": the stage stamps are derived backwards from it)
+    w_rep, w_k, worst = max(kept, key=lambda e: e[2].t_overlay_done_ns - e[2].t_submit_ns)
+    worst_ms = {"pre": (worst.t_pre_done_ns - worst.t_submit_ns) / 1e6,
+                "infer": (worst.t_infer_done_ns - worst.t_pre_done_ns) / 1e6,
+                "post": (worst.t_post_done_ns - worst.t_infer_done_ns) / 1e6,
+                "overlay": (worst.t_overlay_done_ns - worst.t_post_done_ns) / 1e6,
+                "enqueue": (worst.t_enqueued_ns - worst.t_submit_ns) / 1e6}
+    worst_ms = {k: round(v, 4) for k, v in worst_ms.items()}
+    worst_ms["repeat"], worst_ms["frame"] = w_rep, w_k
 
     # ---- roofline of the dominant kernel: HIP events around every launch -------------------
     s0 = streams[0]
@@ -412,7 +415,10 @@ def main():
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),
                        "std": round(m["std"], 4), "tail": round(m["tail"], 4),
                        "flatness": round(m["flatness"], 4), "dropped": int(sum(dropped)),
-                       "stage_median_ms": stage_ms, "per_stream_p50": per_stream_p50,
+                       "submit_lateness_us": {"p50": round(float(np.median(lateness_us)), 1),
+                                              "max": round(float(np.max(lateness_us)), 1)},
+                       "stage_median_ms": stage_ms, "slowest_frame_stage_ms": worst_ms,
+                       "per_stream_p50": per_stream_p50,
                        "mann_whitney": mwu, "pinned_cpus": bool(args.pin_cpus),
                        "tiny_apps": tiny_m,
                        "hog_frames_per_s": round(sum(hog_count) / t_hog, 1) if hogs else None},

@@ -347,6 +347,40 @@ hs_status hs_get_kernel_times(hs_app* app, hs_kernel_time* entries, int max_entr
  * WRITE_SIZE) are scaled. */
 hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes);
 
+/* ---- native stream driver --------------------------------------------------------- */
+
+/* One source of frames: an application (batch >= 1) or a group, with the device buffers it
+ * cycles through.  d_frames / d_outs are HOST arrays of n_frames * batch / n_outs * batch
+ * device pointers; frame k submits entries (k % n_frames) * batch .. + batch - 1 as input and
+ * (k % n_outs) * batch .. as overlay output (n_outs >= queue_depth keeps an output untouched
+ * until its result has been collected).  frame_id = k. */
+typedef struct {
+  hs_app* app;               /* ignored when group != NULL                                 */
+  hs_group* group;           /* a multi-network application, batch must be 1               */
+  const uint8_t* const* d_frames;
+  uint8_t* const* d_outs;
+  int n_frames, n_outs, batch;
+  int results_per_frame;     /* batch, or the group's member count                         */
+  int cpu;                   /* core the submitting thread pins itself to, -1: none        */
+} hs_feed;
+/* Drives n_feeds sources concurrently, one submitting thread each (the paper runs one
+ * process per application, Section V-B), for n_frames frames per source, and returns when
+ * every result has been collected.  fps > 0: frame k of every source is submitted at
+ * t0 + k / fps (absolute deadlines, clock_nanosleep on CLOCK_MONOTONIC); a frame that finds
+ * its queue full is dropped and counted.  fps == 0: back to back, as fast as the queues take
+ * the frames (nothing is dropped: a full queue is waited on).
+ * results[i] receives the collected frames of source i in order, results_per_frame entries
+ * each (HOST array of n_frames * results_per_frame entries; with drops the tail stays
+ * unwritten); dropped[i] (may be NULL) the number of dropped frames; lateness_ns[i] (array or
+ * the whole argument may be NULL) how long after its deadline frame k was submitted;
+ * *elapsed_s (may be NULL) the wall time from starting the submitting threads to the
+ * collection of the last result, i.e. with all GPU work of the run complete.
+ * The sources must not be used by other threads meanwhile.  First failing status of any
+ * source is returned after all threads have ended. */
+hs_status hs_run_feeds(const hs_feed* feeds, int n_feeds, double fps, int n_frames,
+                       hs_result* const* results, int* dropped, int64_t* const* lateness_ns,
+                       double* elapsed_s);
+
 /* Thread-local, never NULL; valid until the next failing call on this thread. */
 const char* hs_last_error(void);
 /* Library version string. */

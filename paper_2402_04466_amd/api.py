@@ -21,7 +21,7 @@ __all__ = [
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
     "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch",
     "hs_create_group", "hs_destroy_group", "hs_submit_group", "hs_poll_group", "hs_wait_group",
-    "HS_MAX_GROUP", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
+    "HS_MAX_GROUP", "hs_feed", "hs_run_feeds", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
     "hs_get_kernel_times", "hs_device_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
@@ -87,6 +87,12 @@ class hs_kernel_time(C.Structure):
 _lib = None
 
 
+class hs_feed(C.Structure):
+    _fields_ = [("app", C.c_void_p), ("group", C.c_void_p), ("d_frames", C.c_void_p),
+                ("d_outs", C.c_void_p), ("n_frames", C.c_int), ("n_outs", C.c_int),
+                ("batch", C.c_int), ("results_per_frame", C.c_int), ("cpu", C.c_int)]
+
+
 def lib_path() -> str:
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhs.so")
 
@@ -132,6 +138,8 @@ def load() -> C.CDLL:
         "hs_submit_group": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
         "hs_poll_group": (C.c_int, [C.c_void_p, P(hs_result)]),
         "hs_wait_group": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
+        "hs_run_feeds": (C.c_int, [P(hs_feed), C.c_int, C.c_double, C.c_int, C.c_void_p,
+                                   P(C.c_int), C.c_void_p, P(C.c_double)]),
         "hs_latency_metrics_compute": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int,
                                                  P(hs_latency_metrics)]),
         "hs_mann_whitney_u": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, P(hs_mwu)]),
@@ -354,6 +362,44 @@ def hs_wait_group(group: int, n_members: int, timeout_ns: int = 10_000_000_000):
     r = (hs_result * n_members)()
     st = _check(load().hs_wait_group(group, r, timeout_ns), soft=(HS_E_NOT_READY,))
     return list(r) if st == HS_OK else None
+
+
+def hs_run_feeds(feeds, fps: float, n_frames: int):
+    """feeds: dicts with app (int) or group (int), frames and outs (lists, one entry per distinct
+    frame / output, each a sequence of `batch` device pointers), results_per_frame, cpu (-1: no
+    pin).  Returns (results, dropped, lateness_ns, elapsed_s): per feed the list of collected frames, each a
+    list of results_per_frame hs_result; the number of dropped frames; the submit lateness of
+    every frame in ns (zeros when fps == 0); the run's wall time in seconds, taken inside the
+    library."""
+    n = len(feeds)
+    arr = (hs_feed * n)()
+    keep, res_bufs, late_bufs = [], [], []
+    for i, f in enumerate(feeds):
+        batch = len(f["frames"][0])
+        fr = (C.c_void_p * (len(f["frames"]) * batch))(*[int(p) for row in f["frames"] for p in row])
+        ou = (C.c_void_p * (len(f["outs"]) * batch))(*[int(p) for row in f["outs"] for p in row])
+        keep += [fr, ou]
+        arr[i].app = f.get("app") or None
+        arr[i].group = f.get("group") or None
+        arr[i].d_frames = C.cast(fr, C.c_void_p)
+        arr[i].d_outs = C.cast(ou, C.c_void_p)
+        arr[i].n_frames, arr[i].n_outs, arr[i].batch = len(f["frames"]), len(f["outs"]), batch
+        arr[i].results_per_frame = int(f["results_per_frame"])
+        arr[i].cpu = int(f.get("cpu", -1))
+        res_bufs.append((hs_result * (n_frames * arr[i].results_per_frame))())
+        late_bufs.append((C.c_int64 * n_frames)())
+    res_ptrs = (C.c_void_p * n)(*[C.addressof(b) for b in res_bufs])
+    late_ptrs = (C.c_void_p * n)(*[C.addressof(b) for b in late_bufs])
+    dropped = (C.c_int * n)()
+    elapsed = C.c_double()
+    _check(load().hs_run_feeds(arr, n, float(fps), n_frames, res_ptrs, dropped, late_ptrs,
+                               C.byref(elapsed)))
+    results = []
+    for i in range(n):
+        per = arr[i].results_per_frame
+        done = n_frames - dropped[i]
+        results.append([[res_bufs[i][k * per + j] for j in range(per)] for k in range(done)])
+    return results, list(dropped), [list(b) for b in late_bufs], elapsed.value
 
 
 def hs_latency_metrics_compute(latencies, trim: bool = True) -> dict:

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libhs.so")
 
-SOURCES = ["hs_host.cpp", "hs_lib.cpp", "hs_kernels.hip"]
+SOURCES = ["hs_host.cpp", "hs_lib.cpp", "hs_driver.cpp", "hs_kernels.hip"]
 
 
 def hipcc() -> str:

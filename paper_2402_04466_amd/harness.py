@@ -188,44 +188,40 @@ class GroupStream:
         self._held.clear()
 
 
-def run_paced(streams, frames, fps: float, outputs, pin_cpus=None):
-    """Submit frame k of every application at t0 + k/fps from one thread per application and
-    collect the per-frame results.  ``frames[i][k]`` / ``outputs[i][q]`` are lists with one
-    device tensor per stream of application i (length ``batch``).  Returns, per application, the
-    list of per-frame result lists (one hs_result per stream), plus the number of frames dropped
-    because the queue was full.  ``pin_cpus[i]``: CPU core the submitting thread of application
-    i pins itself to."""
-    n_streams = len(streams)
-    results = [[] for _ in range(n_streams)]
-    dropped = [0] * n_streams
-    n = max(len(f) for f in frames)
-    t0 = time.monotonic() + 0.05
-    period = 1.0 / fps
+def _feeds(streams, frames, outputs, pin_cpus):
+    feeds = []
+    for i, s in enumerate(streams):
+        f = {"frames": [[t.data_ptr() for t in row] for row in frames[i]],
+             "outs": [[t.data_ptr() for t in row] for row in outputs[i]],
+             "cpu": -1 if pin_cpus is None else pin_cpus[i]}
+        if isinstance(s, GroupStream):
+            f["group"], f["results_per_frame"] = s.group, len(s.members)
+        else:
+            f["app"], f["results_per_frame"] = s.app, s.batch
+        feeds.append(f)
+    return feeds
 
-    def worker(i):
-        s = streams[i]
-        fr = frames[i]
-        if pin_cpus is not None:      # paper Section IV-C: one core per application's submitter
-            os.sched_setaffinity(0, {pin_cpus[i]})
-        for k in range(n):
-            deadline = t0 + k * period
-            while True:
-                r = s.poll_batch()
-                if r is None:
-                    break
-                results[i].append(r)
-            dt = deadline - time.monotonic()
-            if dt > 0:
-                time.sleep(dt)
-            st = s.submit_batch(fr[k % len(fr)], outputs[i][k % len(outputs[i])], k)
-            if st != api.HS_OK:
-                dropped[i] += 1
-        while len(results[i]) + dropped[i] < n:
-            results[i].append(s.wait_batch())
 
-    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n_streams)]
-    for t in threads:
-        t.start()
-    for t in threads:
-        t.join()
-    return results, dropped
+def run_paced(streams, frames, fps: float, outputs, pin_cpus=None, n_frames=None,
+              with_lateness: bool = False):
+    """Frame k of every application is submitted at t0 + k/fps by the library's native driver
+    (one submitting thread per application, absolute deadlines: `hs_run_feeds`), the way the
+    paper runs one process per application instance (Section V-B).  ``frames[i][k]`` /
+    ``outputs[i][q]`` are lists with one device tensor per stream of application i (length
+    ``batch``; a group takes one); frame k uses ``frames[i][k % len]`` and
+    ``outputs[i][k % len]``.  Returns, per application, the list of per-frame result lists (one
+    hs_result per stream, or per member of a group), plus the number of frames dropped because
+    the queue was full.  ``pin_cpus[i]``: CPU core the submitting thread of application i pins
+    itself to."""
+    n = n_frames if n_frames is not None else max(len(f) for f in frames)
+    results, dropped, late, _ = api.hs_run_feeds(_feeds(streams, frames, outputs, pin_cpus), fps, n)
+    return (results, dropped, late) if with_lateness else (results, dropped)
+
+
+def run_back_to_back(streams, frames, outputs, n_frames: int):
+    """Every application submits n_frames frames as fast as its queue takes them (native driver,
+    one thread each).  Returns the per-application results as run_paced does and the wall time
+    of the run in seconds, measured inside the library from the start of the submitting threads
+    to the collection of the last result (all GPU work of the run is complete then)."""
+    results, _, _, elapsed = api.hs_run_feeds(_feeds(streams, frames, outputs, None), 0.0, n_frames)
+    return results, elapsed
