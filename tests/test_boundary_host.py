@@ -31,14 +31,35 @@ def test_binding_struct_sizes_match_the_header(tmp_path):
     src = tmp_path / "sz.c"
     src.write_text('#include <stdio.h>\n#include "hs.h"\nint main(void){printf("%zu %zu %zu %zu\\n",'
                    "sizeof(hs_app_desc),sizeof(hs_result),sizeof(hs_latency_metrics),"
-                   "sizeof(hs_kernel_time));return 0;}\n")
+                   "sizeof(hs_kernel_time));printf(\"%zu %zu\\n\",sizeof(hs_feed),sizeof(hs_mwu));"
+                   "return 0;}\n")
     exe = tmp_path / "sz"
     import subprocess
     subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
     want = [int(v) for v in subprocess.check_output([str(exe)]).split()]
+    from paper_2402_04466_amd import api
     got = [ctypes.sizeof(c) for c in (hs.hs_app_desc, hs.hs_result, hs.hs_latency_metrics,
-                                      hs.hs_kernel_time)]
+                                      hs.hs_kernel_time, hs.hs_feed, api.hs_mwu)]
     assert got == want
+
+
+def test_stream_driver_and_group_calls_reject_bad_arguments_without_a_gpu():
+    """Argument checks come before any GPU work, so they can be exercised here."""
+    from paper_2402_04466_amd import api
+    lib = api.load()
+    assert lib.hs_run_feeds(None, 1, 60.0, 10, None, None, None, None) == hs.HS_E_INVAL
+    feeds = (hs.hs_feed * 1)()                       # all-zero feed: no application, no buffers
+    res = (ctypes.c_void_p * 1)()
+    assert lib.hs_run_feeds(feeds, 1, 60.0, 10, res, None, None, None) == hs.HS_E_INVAL
+    assert "feed 0" in hs.hs_last_error()
+    assert lib.hs_run_feeds(feeds, 1, -1.0, 10, res, None, None, None) == hs.HS_E_INVAL
+    assert lib.hs_run_feeds(feeds, 0, 60.0, 10, res, None, None, None) == hs.HS_E_INVAL
+    out = ctypes.c_void_p()
+    assert lib.hs_create_group(None, None, 2, ctypes.byref(out)) == hs.HS_E_INVAL
+    assert lib.hs_destroy_group(None) == hs.HS_E_INVAL
+    assert lib.hs_submit_group(None, None, None, 0) == hs.HS_E_INVAL
+    assert lib.hs_poll_group(None, None) == hs.HS_E_INVAL
+    assert lib.hs_wait_group(None, None, 0) == hs.HS_E_INVAL
 
 
 # ---- admission control ---------------------------------------------------------------------
