@@ -182,3 +182,15 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=60)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_seeded_inputs_hash_to_the_recorded_values():
+    """The generators behind every benchmark configuration still produce the recorded bytes."""
+    import importlib.util
+    path = os.path.join(ROOT, "tests", "golden", "make_input_hashes.py")
+    spec = importlib.util.spec_from_file_location("make_input_hashes", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = [l.rstrip("\n") for l in open(os.path.join(ROOT, "tests", "golden", "input_hashes.txt"))
+            if not l.startswith("#")]
+    assert list(mod.lines()) == want
