@@ -182,6 +182,7 @@ def main():
             tiny.append(s)
             tiny_frames.append([[s.upload_frame(f)] for f in si.uniform_frames(8, 240, 320, 50 + i)])
             tiny_outs.append([[s.new_output()] for _ in range(args.queue_depth)])
+    part_cus = {}     # library application -> (CUs of its inference mask, of its overlay mask)
     if args.partition != "none" and args.tiny_groups and tiny:
         # unequal slices: G groups per small application, the rest split among the others
         n_big = args.streams + args.hog
@@ -198,6 +199,7 @@ def main():
             at += g
             ci, co = (cus, cus) if args.partition == "equal-shared" else (cus[:-8], cus[-8:])
             hs.hs_set_partition(s.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+            part_cus[s.app] = (len(ci), len(co))
     elif args.partition != "none":
         # one partition per library application (every network of a group gets its own)
         units = [a for s in streams + tiny + hogs for a in apps_of(s)]
@@ -206,6 +208,7 @@ def main():
             if args.partition == "equal-shared":
                 ci = co = ci + co
             hs.hs_set_partition(a, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+            part_cus[a] = (len(ci), len(co))
     outs = [[[s.new_output() for _ in range(args.batch)] for _ in range(args.queue_depth)]
             for s in streams]
     torch.cuda.synchronize()
@@ -369,6 +372,32 @@ def main():
             d["GB/s"] = round(e["bytes"] / (e["total_ms"] * 1e-3) / 1e9, 1)
         kernels[e["name"]] = d
 
+    # what the first application's share of the device can pull and compute: a plain copy of the
+    # overlay's shape under the same CU mask, and the fp16 MFMA peak of its CUs
+    part = None
+    if args.partition != "none":
+        per_app = args.batch * FH * s0.frame_pitch
+        src = torch.full((per_app,), 3, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        sec = hs.hs_partition_copy(app0, dst.data_ptr(), src.data_ptr(), per_app, 20)
+        copy_gbs = 2.0 * per_app / sec / 1e9
+        cus = part_cus.get(app0)
+        part = {"application": 0, "cus_inference": cus[0], "cus_overlay": cus[1],
+                "copy_GB/s": round(copy_gbs, 1)}
+        ov = next((e for e in kt if e["name"] == "overlay"), None)
+        if ov and ov["total_ms"] > 0:
+            ov_gbs = ov["bytes"] / (ov["total_ms"] * 1e-3) / 1e9
+            part["overlay_GB/s"] = round(ov_gbs, 1)
+            part["overlay_vs_copy"] = round(ov_gbs / copy_gbs, 3)
+        cv = next((e for e in kt if e["name"] == "conv_mfma"), None)
+        if cv and cv["total_ms"] > 0:
+            peak = cus[0] * PEAK_FP16_TFLOPS / 256.0
+            ach = cv["flops"] / (cv["total_ms"] * 1e-3) / 1e12
+            part["conv_TFLOP/s"] = round(ach, 2)
+            part["conv_peak_of_its_cus_TFLOP/s"] = round(peak, 1)
+            part["conv_frac_of_its_cus"] = round(ach / peak, 4)
+        del src, dst
     for s in streams + tiny + hogs:
         s.close()
     hs.hs_shutdown(ctx)
@@ -423,6 +452,7 @@ def main():
                        "tiny_apps": tiny_m,
                        "hog_frames_per_s": round(sum(hog_count) / t_hog, 1) if hogs else None},
         "roofline": roof,
+        "partition_share": part,
         "kernels": kernels,
         "cpu_baseline": cpu,
     }

@@ -381,6 +381,15 @@ hs_status hs_run_feeds(const hs_feed* feeds, int n_feeds, double fps, int n_fram
                        hs_result* const* results, int* dropped, int64_t* const* lateness_ns,
                        double* elapsed_s);
 
+/* The same plain copy, `repeats` times back to back on the application's overlay stream, i.e.
+ * under the CU mask the application's partition gives that stream (all CUs when it is not
+ * partitioned); *seconds_per_copy = GPU time between events around the repeats / repeats (one
+ * untimed copy first).  It measures what the partition's CUs can pull: the denominator for the
+ * byte-bound kernels of a partitioned application.  Same argument rules as hs_device_copy;
+ * HS_E_STATE while frames are in flight. */
+hs_status hs_partition_copy(hs_app* app, void* d_dst, const void* d_src, size_t bytes,
+                            int repeats, double* seconds_per_copy);
+
 /* Thread-local, never NULL; valid until the next failing call on this thread. */
 const char* hs_last_error(void);
 /* Library version string. */

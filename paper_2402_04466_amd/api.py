@@ -22,7 +22,7 @@ __all__ = [
     "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch",
     "hs_create_group", "hs_destroy_group", "hs_submit_group", "hs_poll_group", "hs_wait_group",
     "HS_MAX_GROUP", "hs_feed", "hs_run_feeds", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
-    "hs_get_kernel_times", "hs_device_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
+    "hs_get_kernel_times", "hs_device_copy", "hs_partition_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
 HS_OK, HS_E_INVAL, HS_E_NOMEM, HS_E_OVERSUBSCRIBED = 0, -1, -2, -3
@@ -148,6 +148,8 @@ def load() -> C.CDLL:
         "hs_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int]),
         "hs_get_kernel_times": (C.c_int, [C.c_void_p, P(hs_kernel_time), C.c_int, P(C.c_int)]),
         "hs_device_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+        "hs_partition_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int,
+                                        P(C.c_double)]),
         "hs_last_error": (C.c_char_p, []),
         "hs_version": (C.c_char_p, []),
     }
@@ -425,6 +427,13 @@ def hs_set_cpu_affinity(app: int, cpu: int) -> None:
 
 def hs_device_copy(ctx: int, d_dst: int, d_src: int, nbytes: int) -> None:
     _check(load().hs_device_copy(ctx, d_dst, d_src, nbytes))
+
+
+def hs_partition_copy(app: int, d_dst: int, d_src: int, nbytes: int, repeats: int = 10) -> float:
+    """Seconds per copy of nbytes on the application's overlay stream (under its CU mask)."""
+    sec = C.c_double()
+    _check(load().hs_partition_copy(app, d_dst, d_src, nbytes, repeats, C.byref(sec)))
+    return sec.value
 
 
 def hs_set_launch_mode(app: int, mode: int) -> None:

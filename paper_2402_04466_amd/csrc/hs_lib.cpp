@@ -1125,6 +1125,41 @@ hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t byt
   return HS_OK;
 }
 
+hs_status hs_partition_copy(hs_app* app, void* d_dst, const void* d_src, size_t bytes,
+                            int repeats, double* seconds_per_copy) {
+  if (!app || !d_dst || !d_src || !seconds_per_copy || repeats < 1 || bytes == 0 ||
+      bytes % 16 != 0 || ((uintptr_t)d_dst & 15) || ((uintptr_t)d_src & 15)) {
+    set_error("hs_partition_copy: NULL, misaligned pointer, size not a multiple of 16 or repeats < 1");
+    return HS_E_INVAL;
+  }
+  if (frames_in_flight(app)) { set_error("hs_partition_copy: frames in flight"); return HS_E_STATE; }
+  HS_HIP(hipSetDevice(app->ctx->device));
+  hipStream_t st = app->s_overlay ? app->s_overlay : app->s_lane[0];
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  HS_HIP(hipEventCreate(&e0));
+  hipError_t e = hipEventCreate(&e1);
+  if (e == hipSuccess) {
+    launch_copy(d_dst, d_src, bytes, st);   // untimed: first touch of the buffers
+    e = hipEventRecord(e0, st);
+  }
+  for (int i = 0; i < repeats && e == hipSuccess; ++i) {
+    launch_copy(d_dst, d_src, bytes, st);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipEventRecord(e1, st);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (e != hipSuccess) {
+    set_error("hs_partition_copy: %s", hipGetErrorString(e));
+    return HS_E_DEVICE;
+  }
+  *seconds_per_copy = (double)ms * 1e-3 / repeats;
+  return HS_OK;
+}
+
 hs_status hs_query_workspace(const hs_app_desc* desc, size_t* bytes) {
   return guarded("hs_query_workspace", [&]() -> hs_status {
   if (!bytes) { set_error("hs_query_workspace: NULL bytes"); return HS_E_INVAL; }

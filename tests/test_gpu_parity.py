@@ -425,6 +425,34 @@ def test_device_copy_kernel(hs, ctx):
         hs.hs_device_copy(ctx, 256, 512, 24)          # not a multiple of 16
 
 
+def test_partition_copy_runs_under_the_application_mask(hs, ctx):
+    """The masked copy that gives a partition's bandwidth denominator: exact, and a 16-CU
+    partition moves the same bytes more slowly than the whole device."""
+    from paper_2402_04466_amd.harness import AppStream
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+    a = AppStream(ctx, net=hs.HS_NET_TINY4, frame_w=320, frame_h=240, net_w=128, net_h=128,
+                  blob=blob, palette=PAL, queue_depth=2)
+    try:
+        nbytes = 64 << 20
+        src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda:0")
+        dst = torch.zeros_like(src)
+        torch.cuda.synchronize()
+        t_all = hs.hs_partition_copy(a.app, dst.data_ptr(), src.data_ptr(), nbytes, 5)
+        assert torch.equal(dst, src) and t_all > 0
+        dst.zero_()
+        torch.cuda.synchronize()
+        hs.hs_set_partition(a.app, hs.cu_mask_words(range(16)), hs.cu_mask_words(range(16)))
+        t_16 = hs.hs_partition_copy(a.app, dst.data_ptr(), src.data_ptr(), nbytes, 5)
+        assert torch.equal(dst, src)
+        print(f"[partition copy] all CUs {2 * nbytes / t_all / 1e9:.0f} GB/s, "
+              f"16 CUs {2 * nbytes / t_16 / 1e9:.0f} GB/s", flush=True)
+        assert t_16 > 1.5 * t_all
+        with pytest.raises(hs.HsError):
+            hs.hs_partition_copy(a.app, dst.data_ptr(), src.data_ptr(), 24, 1)
+    finally:
+        a.close()
+
+
 def test_kernel_timing_reports_every_family(hs, ctx):
     from paper_2402_04466_amd.harness import AppStream
     frames = list(si.uniform_frames(1, 240, 320, 2))
