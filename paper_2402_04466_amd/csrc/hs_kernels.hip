@@ -22,6 +22,21 @@ __device__ __forceinline__ uint32_t udiv_est(uint32_t num, uint32_t d, float rcp
 // Stage 1: one workgroup per output row.  The two source rows the row needs are staged in
 // LDS with 16-byte loads; every output pixel is the exact integer 4-tap sum, rounded once.
 // =============================================================================================
+// a * b (+ c) on the low 24 bits of a and b, low 32 bits of the result: the full-rate integer
+// multiplier (the 32 x 32-bit one runs at a quarter of its rate).  Written as instructions
+// because the compiler turns __umul24 back into a 32-bit multiply when it knows one factor
+// to be small.
+__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_mul_u32_u24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t mad24(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
   extern __shared__ __align__(16) uint8_t lds[];
   __shared__ float s_lut32[256];
@@ -76,7 +91,11 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
     for (int c = 0; c < 3; ++c) {
       const uint32_t p00 = (uint32_t)(r0 >> (8 * c)) & 0xffu, p01 = (uint32_t)(r0 >> (8 * c + 24)) & 0xffu;
       const uint32_t p10 = (uint32_t)(r1 >> (8 * c)) & 0xffu, p11 = (uint32_t)(r1 >> (8 * c + 24)) & 0xffu;
-      const uint32_t acc = wy0 * (wx0 * p00 + wx1 * p01) + wy1 * (wx0 * p10 + wx1 * p11);
+      // every factor is below 2^24 (weights <= 2*wo, 2*ho <= 2^15; a row sum <= 2*wo*255 < 2^24) and
+      // the sum below 2^31: 24-bit multiplies are exact here and run at four times the rate of
+      // the 32-bit ones
+      const uint32_t acc = mad24(wy0, mad24(wx0, p00, mul24(wx1, p01)),
+                                 mul24(wy1, mad24(wx0, p10, mul24(wx1, p11))));
       // floor((acc + d/2) / d) by multiplication: exact for numerators below 2^31
       q[c] = __umulhi(acc + (d >> 1), p.d_magic) >> p.d_shift;
     }
@@ -1009,7 +1028,8 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
   // Most groups see one channel for all 16 pixels: nothing to draw, or one colour.  Then the
   // blend runs on two bytes per 32-bit operation: even and odd bytes of a word are 16-bit
   // fields, (256 - a) * byte + (a * colour + 128) never exceeds 65408, so no field carries into
-  // its neighbour.
+  // its neighbour.  The field pair is below 2^24 and the factor at most 256: 24-bit multiplies
+  // (full rate; the 32-bit ones run at a quarter of it) are exact.
   const int mx_last = (int)udiv_est((uint32_t)((X0 + 15) * L.wm), (uint32_t)p.wf, p.rcp_wf);
   const bool one_cell = mx_last == mx0 || (mx_last == mx0 + 1 && k1 == k0);
   if (one_cell) {
@@ -1017,14 +1037,14 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
       const uint32_t col = overlay_colour(L, k0);
       uint32_t t[3];
 #pragma unroll
-      for (int c = 0; c < 3; ++c) t[c] = (uint32_t)L.a * ((col >> (8 * c)) & 0xffu) + 128u;
+      for (int c = 0; c < 3; ++c) t[c] = mad24((uint32_t)L.a, (col >> (8 * c)) & 0xffu, 128u);
 #pragma unroll
       for (int j = 0; j < 12; ++j) {
         const uint32_t ce = t[j % 3] | (t[(j + 2) % 3] << 16);        // bytes 0 and 2
         const uint32_t co = t[(j + 1) % 3] | (t[(j + 3) % 3] << 16);  // bytes 1 and 3
         const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
-        w[j] = (((e * (uint32_t)ia + ce) >> 8) & 0x00ff00ffu) |
-               ((o * (uint32_t)ia + co) & 0xff00ff00u);
+        w[j] = ((mad24(e, (uint32_t)ia, ce) >> 8) & 0x00ff00ffu) |
+               (mad24(o, (uint32_t)ia, co) & 0xff00ff00u);
       }
     }
   } else if (mx_last == mx0 + 1) {
@@ -1038,8 +1058,8 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
     uint32_t t0[3], t1[3];
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
-      t0[c] = (uint32_t)L.a * ((c0 >> (8 * c)) & 0xffu) + 128u;
-      t1[c] = (uint32_t)L.a * ((c1 >> (8 * c)) & 0xffu) + 128u;
+      t0[c] = mad24((uint32_t)L.a, (c0 >> (8 * c)) & 0xffu, 128u);
+      t1[c] = mad24((uint32_t)L.a, (c1 >> (8 * c)) & 0xffu, 128u);
     }
 #pragma unroll
     for (int j = 0; j < 12; ++j) {
@@ -1048,8 +1068,8 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
       const uint32_t tb2 = 4 * j + 2 < s3 ? t0[(j + 2) % 3] : t1[(j + 2) % 3];
       const uint32_t tb3 = 4 * j + 3 < s3 ? t0[(j + 3) % 3] : t1[(j + 3) % 3];
       const uint32_t e = w[j] & 0x00ff00ffu, o = (w[j] >> 8) & 0x00ff00ffu;
-      const uint32_t blended = (((e * (uint32_t)ia + (tb0 | (tb2 << 16))) >> 8) & 0x00ff00ffu) |
-                               ((o * (uint32_t)ia + (tb1 | (tb3 << 16))) & 0xff00ff00u);
+      const uint32_t blended = ((mad24(e, (uint32_t)ia, tb0 | (tb2 << 16)) >> 8) & 0x00ff00ffu) |
+                               (mad24(o, (uint32_t)ia, tb1 | (tb3 << 16)) & 0xff00ff00u);
       const int nb = min(4, max(0, s3 - 4 * j));                    // leading bytes of cell 0
       const uint32_t low = nb == 4 ? 0xffffffffu : ((1u << (8 * nb)) - 1u);
       const uint32_t draw = (low & d0) | (~low & d1);
@@ -1068,7 +1088,7 @@ __device__ __forceinline__ void overlay_layer_group(const OverlayParams& p, cons
           const int byte = 3 * i + c;                 // literal after unrolling
           const uint32_t pc = (col >> (8 * c)) & 0xffu;
           const uint32_t old = (w[byte >> 2] >> (8 * (byte & 3))) & 0xffu;
-          const uint32_t nw = (L.a * pc + ia * old + 128u) >> 8;
+          const uint32_t nw = mad24((uint32_t)L.a, pc, mad24((uint32_t)ia, old, 128u)) >> 8;
           w[byte >> 2] = (w[byte >> 2] & ~(0xffu << (8 * (byte & 3)))) | (nw << (8 * (byte & 3)));
         }
       }
@@ -1150,7 +1170,7 @@ __device__ __forceinline__ void overlay_layer_pixel(const OverlayParams& p, cons
   for (int c = 0; c < 3; ++c) {
     if (k != 0xff) {
       const uint32_t pc = (overlay_colour(L, k) >> (8 * c)) & 0xffu;
-      x[c] = (L.a * pc + (256 - L.a) * x[c] + 128u) >> 8;
+      x[c] = mad24((uint32_t)L.a, pc, mad24((uint32_t)(256 - L.a), x[c], 128u)) >> 8;
     }
     if (paint >= 0) x[c] = (overlay_colour(L, (uint32_t)paint) >> (8 * c)) & 0xffu;
   }
