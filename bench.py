@@ -110,7 +110,7 @@ def equal_partitions(n_cus: int, n_streams: int, overlay_groups: int = 1, spare_
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (streams would "
+        print("bench.py measures one GPU: this library has no multi-GPU path (streams would "
               "shard one application per GPU with no communication); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
