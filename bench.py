@@ -72,6 +72,10 @@ def parse():
                     help="every application runs N networks side by side on each frame and draws "
                          "their layers in one overlay launch (the paper's multi-network "
                          "application, Section III-B); needs --batch 1")
+    ap.add_argument("--per-stream-submit", action="store_true",
+                    help="with --batch B > 1: every stream of a batch submits its own frame from "
+                         "its own thread (hs_mux); latency then counts from the stream's own "
+                         "arrival and includes the wait for the rest of the batch")
     ap.add_argument("--paced-frames", type=int, default=60)
     ap.add_argument("--repeats", type=int, default=1,
                     help="repeat the paced latency run this many times (state reset in between) "
@@ -265,6 +269,9 @@ def main():
                 hs.hs_set_cpu_affinity(a, cores[(2 * i + 1) % len(cores)])
     tiny_paced = [(f * ((args.paced_frames + len(f) - 1) // len(f)))[:args.paced_frames]
                   for f in tiny_frames]
+    muxes = None
+    if args.per_stream_submit and args.batch > 1 and not grouped:
+        muxes = [hs.hs_create_mux(s.app, args.batch) for s in streams]
     lat_ms, tl, dropped, results, kept, lateness_us = [], [], [], [], [], []
     for rep in range(max(1, args.repeats)):
         if rep:
@@ -273,7 +280,8 @@ def main():
                     hs.hs_reset_state(a)
         res_all, drop, late = run_paced(streams + tiny, paced + tiny_paced, args.fps,
                                         outs + tiny_outs, pin_cpus=pins,
-                                        n_frames=args.paced_frames, with_lateness=True)
+                                        n_frames=args.paced_frames, with_lateness=True,
+                                        muxes=muxes + [None] * len(tiny) if muxes else None)
         lateness_us.extend(v / 1e3 for per in late for v in per)
         dropped.extend(drop)
         tiny_results, results = res_all[len(streams):], res_all[:len(streams)]
@@ -291,6 +299,8 @@ def main():
     if tiny:
         tm = hs.hs_latency_metrics_compute(tl, trim=False)
         tiny_m = {k: (int(v) if k == "n" else round(v, 4)) for k, v in tm.items()}
+    for m in muxes or []:
+        hs.hs_destroy_mux(m)
     hog_stop.set()
     for t in hog_threads:
         t.join()
@@ -438,6 +448,7 @@ def main():
                                + (f"; {args.group_nets} such networks per stream, one overlay "
                                   "launch for their layers" if grouped else ""),
                    "streams": args.streams, "batch": args.batch, "group_nets": args.group_nets,
+                   "per_stream_submit": bool(muxes),
                    "partition": args.partition,
                    "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,

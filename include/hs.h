@@ -44,6 +44,7 @@ extern "C" {
 typedef struct hs_ctx hs_ctx; /* one per device, opaque */
 typedef struct hs_app hs_app; /* one per application stream, opaque */
 typedef struct hs_group hs_group; /* applications that share frames and one overlay, opaque */
+typedef struct hs_mux hs_mux;     /* per-stream front of a batched application, opaque */
 
 typedef enum {
   HS_OK = 0,
@@ -347,16 +348,38 @@ hs_status hs_get_kernel_times(hs_app* app, hs_kernel_time* entries, int max_entr
  * WRITE_SIZE) are scaled. */
 hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes);
 
+/* ---- batched application fed stream by stream ---------------------------------------- */
+
+/* A batched application (desc.batch = B) takes one frame of every stream per call of
+ * hs_submit_batch.  Independent sources do not arrive together: the mux lets stream j hand
+ * over its frame on its own (hs_mux_submit, from any thread; arrival is stamped then), submits
+ * the batch to the application when the last of the B frames has arrived, and lets every
+ * stream collect its own result (hs_mux_poll / hs_mux_wait: the hs_result of that stream, with
+ * t_submit_ns = the stream's own arrival and frame_id = the id the stream gave, so that
+ * t_overlay_done_ns - t_submit_ns includes the wait for the rest of the batch).
+ * A stream whose previous frame still waits for its batch gets HS_E_QUEUE_FULL, and so does the
+ * stream that would complete a batch while the application's queue is full (its frame is not
+ * taken, the others keep waiting).  While a mux exists the application is driven only through
+ * it.  The calls are thread-safe among themselves.  `batch` must equal the application's. */
+hs_status hs_create_mux(hs_app* app, int batch, hs_mux** out);
+hs_status hs_destroy_mux(hs_mux* mux);
+hs_status hs_mux_submit(hs_mux* mux, int stream, const uint8_t* d_frame, uint8_t* d_overlay_out,
+                        uint64_t frame_id);
+hs_status hs_mux_poll(hs_mux* mux, int stream, hs_result* out);
+hs_status hs_mux_wait(hs_mux* mux, int stream, hs_result* out, uint64_t timeout_ns);
+
 /* ---- native stream driver --------------------------------------------------------- */
 
-/* One source of frames: an application (batch >= 1) or a group, with the device buffers it
- * cycles through.  d_frames / d_outs are HOST arrays of n_frames * batch / n_outs * batch
- * device pointers; frame k submits entries (k % n_frames) * batch .. + batch - 1 as input and
+/* One source of frames: an application (batch >= 1), a group or one stream of a mux, with the
+ * device buffers it cycles through.  d_frames / d_outs are HOST arrays of n_frames * batch /
+ * n_outs * batch device pointers; frame k submits entries (k % n_frames) * batch .. + batch - 1 as input and
  * (k % n_outs) * batch .. as overlay output (n_outs >= queue_depth keeps an output untouched
  * until its result has been collected).  frame_id = k. */
 typedef struct {
-  hs_app* app;               /* ignored when group != NULL                                 */
+  hs_app* app;               /* ignored when group or mux is given                         */
   hs_group* group;           /* a multi-network application, batch must be 1               */
+  hs_mux* mux;               /* one stream (mux_stream) of a batched application behind a   */
+  int mux_stream;            /* mux; batch and results_per_frame must be 1                  */
   const uint8_t* const* d_frames;
   uint8_t* const* d_outs;
   int n_frames, n_outs, batch;

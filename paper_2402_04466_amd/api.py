@@ -21,7 +21,8 @@ __all__ = [
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
     "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch",
     "hs_create_group", "hs_destroy_group", "hs_submit_group", "hs_poll_group", "hs_wait_group",
-    "HS_MAX_GROUP", "hs_feed", "hs_run_feeds", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
+    "HS_MAX_GROUP", "hs_feed", "hs_run_feeds", "hs_create_mux", "hs_destroy_mux", "hs_mux_submit",
+    "hs_mux_poll", "hs_mux_wait", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
     "hs_get_kernel_times", "hs_device_copy", "hs_partition_copy", "hs_last_error", "hs_version", "make_desc", "cu_mask_words",
 ]
 
@@ -88,7 +89,8 @@ _lib = None
 
 
 class hs_feed(C.Structure):
-    _fields_ = [("app", C.c_void_p), ("group", C.c_void_p), ("d_frames", C.c_void_p),
+    _fields_ = [("app", C.c_void_p), ("group", C.c_void_p), ("mux", C.c_void_p),
+                ("mux_stream", C.c_int), ("d_frames", C.c_void_p),
                 ("d_outs", C.c_void_p), ("n_frames", C.c_int), ("n_outs", C.c_int),
                 ("batch", C.c_int), ("results_per_frame", C.c_int), ("cpu", C.c_int)]
 
@@ -138,6 +140,11 @@ def load() -> C.CDLL:
         "hs_submit_group": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
         "hs_poll_group": (C.c_int, [C.c_void_p, P(hs_result)]),
         "hs_wait_group": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
+        "hs_create_mux": (C.c_int, [C.c_void_p, C.c_int, P(C.c_void_p)]),
+        "hs_destroy_mux": (C.c_int, [C.c_void_p]),
+        "hs_mux_submit": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_uint64]),
+        "hs_mux_poll": (C.c_int, [C.c_void_p, C.c_int, P(hs_result)]),
+        "hs_mux_wait": (C.c_int, [C.c_void_p, C.c_int, P(hs_result), C.c_uint64]),
         "hs_run_feeds": (C.c_int, [P(hs_feed), C.c_int, C.c_double, C.c_int, C.c_void_p,
                                    P(C.c_int), C.c_void_p, P(C.c_double)]),
         "hs_latency_metrics_compute": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int,
@@ -366,8 +373,38 @@ def hs_wait_group(group: int, n_members: int, timeout_ns: int = 10_000_000_000):
     return list(r) if st == HS_OK else None
 
 
+def hs_create_mux(app: int, batch: int) -> int:
+    out = C.c_void_p()
+    _check(load().hs_create_mux(app, batch, C.byref(out)))
+    return out.value
+
+
+def hs_destroy_mux(mux: int) -> None:
+    _check(load().hs_destroy_mux(mux))
+
+
+def hs_mux_submit(mux: int, stream: int, d_frame: int, d_overlay_out: int, frame_id: int) -> int:
+    """Returns HS_OK or HS_E_QUEUE_FULL; raises on any other status."""
+    return _check(load().hs_mux_submit(mux, stream, d_frame, d_overlay_out, frame_id),
+                  soft=(HS_E_QUEUE_FULL,))
+
+
+def hs_mux_poll(mux: int, stream: int):
+    """Returns the stream's next hs_result, or None if none has finished."""
+    r = hs_result()
+    st = _check(load().hs_mux_poll(mux, stream, C.byref(r)), soft=(HS_E_NOT_READY,))
+    return r if st == HS_OK else None
+
+
+def hs_mux_wait(mux: int, stream: int, timeout_ns: int = 10_000_000_000):
+    """Returns the stream's next hs_result, or None on time-out."""
+    r = hs_result()
+    st = _check(load().hs_mux_wait(mux, stream, C.byref(r), timeout_ns), soft=(HS_E_NOT_READY,))
+    return r if st == HS_OK else None
+
+
 def hs_run_feeds(feeds, fps: float, n_frames: int):
-    """feeds: dicts with app (int) or group (int), frames and outs (lists, one entry per distinct
+    """feeds: dicts with app (int), group (int) or mux (int) + mux_stream, frames and outs (lists, one entry per distinct
     frame / output, each a sequence of `batch` device pointers), results_per_frame, cpu (-1: no
     pin).  Returns (results, dropped, lateness_ns, elapsed_s): per feed the list of collected frames, each a
     list of results_per_frame hs_result; the number of dropped frames; the submit lateness of
@@ -383,6 +420,8 @@ def hs_run_feeds(feeds, fps: float, n_frames: int):
         keep += [fr, ou]
         arr[i].app = f.get("app") or None
         arr[i].group = f.get("group") or None
+        arr[i].mux = f.get("mux") or None
+        arr[i].mux_stream = int(f.get("mux_stream", 0))
         arr[i].d_frames = C.cast(fr, C.c_void_p)
         arr[i].d_outs = C.cast(ou, C.c_void_p)
         arr[i].n_frames, arr[i].n_outs, arr[i].batch = len(f["frames"]), len(f["outs"]), batch

@@ -188,9 +188,23 @@ class GroupStream:
         self._held.clear()
 
 
-def _feeds(streams, frames, outputs, pin_cpus):
-    feeds = []
+def _feeds(streams, frames, outputs, pin_cpus, muxes=None):
+    """One feed per application, or, for an application behind a mux (muxes[i] not None), one
+    feed per stream of its batch.  Returns the feeds and, per application, the indices of its
+    feeds."""
+    feeds, owner = [], []
     for i, s in enumerate(streams):
+        if muxes is not None and muxes[i] is not None:
+            idx = []
+            for j in range(s.batch):
+                idx.append(len(feeds))
+                feeds.append({"mux": muxes[i], "mux_stream": j, "results_per_frame": 1,
+                              "frames": [[row[j].data_ptr()] for row in frames[i]],
+                              "outs": [[row[j].data_ptr()] for row in outputs[i]],
+                              "cpu": -1 if pin_cpus is None else pin_cpus[i]})
+            owner.append(idx)
+            continue
+        owner.append([len(feeds)])
         f = {"frames": [[t.data_ptr() for t in row] for row in frames[i]],
              "outs": [[t.data_ptr() for t in row] for row in outputs[i]],
              "cpu": -1 if pin_cpus is None else pin_cpus[i]}
@@ -199,11 +213,24 @@ def _feeds(streams, frames, outputs, pin_cpus):
         else:
             f["app"], f["results_per_frame"] = s.app, s.batch
         feeds.append(f)
-    return feeds
+    return feeds, owner
+
+
+def _regroup(per_feed, owner):
+    """Per application: per frame, the results of all its streams (a muxed application's feeds
+    are merged frame by frame; frames that some stream dropped are left out)."""
+    out = []
+    for idx in owner:
+        if len(idx) == 1:
+            out.append(per_feed[idx[0]])
+        else:
+            n = min(len(per_feed[j]) for j in idx)
+            out.append([[per_feed[j][k][0] for j in idx] for k in range(n)])
+    return out
 
 
 def run_paced(streams, frames, fps: float, outputs, pin_cpus=None, n_frames=None,
-              with_lateness: bool = False):
+              with_lateness: bool = False, muxes=None):
     """Frame k of every application is submitted at t0 + k/fps by the library's native driver
     (one submitting thread per application, absolute deadlines: `hs_run_feeds`), the way the
     paper runs one process per application instance (Section V-B).  ``frames[i][k]`` /
@@ -212,9 +239,14 @@ def run_paced(streams, frames, fps: float, outputs, pin_cpus=None, n_frames=None
     ``outputs[i][k % len]``.  Returns, per application, the list of per-frame result lists (one
     hs_result per stream, or per member of a group), plus the number of frames dropped because
     the queue was full.  ``pin_cpus[i]``: CPU core the submitting thread of application i pins
-    itself to."""
+    itself to.  ``muxes[i]``: a mux handle when the streams of batched application i submit on their
+    own, one thread per stream (their results are merged per frame again)."""
     n = n_frames if n_frames is not None else max(len(f) for f in frames)
-    results, dropped, late, _ = api.hs_run_feeds(_feeds(streams, frames, outputs, pin_cpus), fps, n)
+    feeds, owner = _feeds(streams, frames, outputs, pin_cpus, muxes)
+    results, dropped, late, _ = api.hs_run_feeds(feeds, fps, n)
+    results = _regroup(results, owner)
+    dropped = [sum(dropped[j] for j in idx) for idx in owner]
+    late = [[v for j in idx for v in late[j]] for idx in owner]
     return (results, dropped, late) if with_lateness else (results, dropped)
 
 
@@ -223,5 +255,6 @@ def run_back_to_back(streams, frames, outputs, n_frames: int):
     one thread each).  Returns the per-application results as run_paced does and the wall time
     of the run in seconds, measured inside the library from the start of the submitting threads
     to the collection of the last result (all GPU work of the run is complete then)."""
-    results, _, _, elapsed = api.hs_run_feeds(_feeds(streams, frames, outputs, None), 0.0, n_frames)
-    return results, elapsed
+    feeds, owner = _feeds(streams, frames, outputs, None)
+    results, _, _, elapsed = api.hs_run_feeds(feeds, 0.0, n_frames)
+    return _regroup(results, owner), elapsed

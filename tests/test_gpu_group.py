@@ -140,3 +140,80 @@ def test_group_equals_members_run_alone_and_calls_are_guarded(hs, ctx, mode):
     finally:
         grp.close()
         solo.close()
+
+
+def test_mux_feeds_a_batched_application_stream_by_stream(hs, ctx):
+    """Three streams of a batch-3 application hand over their frames on their own (here from
+    three threads, out of order and with delays); every stream gets its own result with its own
+    arrival stamp, and the outputs equal those of the same frames submitted as whole batches."""
+    import threading
+    import time
+    from paper_2402_04466_amd import api
+    from paper_2402_04466_amd.harness import AppStream
+    B, T, fw, fh = 3, 4, 320, 240
+    blob = si.he_normal_blob(TINY, 0)
+    kw = dict(net=hs.HS_NET_TINY4, frame_w=fw, frame_h=fh, net_w=128, net_h=128, blob=blob,
+              palette=PAL_A, queue_depth=T, batch=B)   # a slot per batch: buffers stay readable
+    a, ref_app = AppStream(ctx, **kw), AppStream(ctx, **kw)
+    mux = api.hs_create_mux(a.app, B)
+    try:
+        frames = [list(si.uniform_frames(T, fh, fw, 70 + j)) for j in range(B)]
+        d_in = [[a.upload_frame(f) for f in frames[j]] for j in range(B)]
+        d_out = [[a.new_output() for _ in range(T)] for j in range(B)]
+        ref_out = [[a.new_output() for _ in range(T)] for j in range(B)]
+        ref = []
+        for t in range(T):
+            assert ref_app.submit_batch([d_in[j][t] for j in range(B)],
+                                        [ref_out[j][t] for j in range(B)], t) == hs.HS_OK
+            rs = ref_app.wait_batch()
+            ref.append([ref_app.fetch(rs[j], ref_out[j][t]) for j in range(B)])
+        # a stream cannot run ahead of its batch
+        assert api.hs_mux_submit(mux, 1, d_in[1][0].data_ptr(), d_out[1][0].data_ptr(), 100) == hs.HS_OK
+        assert api.hs_mux_submit(mux, 1, d_in[1][1].data_ptr(), d_out[1][1].data_ptr(), 101) \
+            == hs.HS_E_QUEUE_FULL
+        assert api.hs_mux_poll(mux, 1) is None
+        got = [[None] * T for _ in range(B)]
+        errors = []
+
+        def stream_thread(j):
+            try:
+                for t in range(T):
+                    if not (j == 1 and t == 0):          # stream 1's first frame is already in
+                        time.sleep(0.002 * ((j + t) % 3))
+                        assert api.hs_mux_submit(mux, j, d_in[j][t].data_ptr(),
+                                                 d_out[j][t].data_ptr(), 100 + t) == hs.HS_OK
+                    r = api.hs_mux_wait(mux, j, 5_000_000_000)
+                    assert r is not None and r.frame_id == 100 + t
+                    got[j][t] = r
+            except BaseException as e:      # noqa: BLE001 - reported by the main thread
+                errors.append((j, repr(e)))
+
+        print("[mux] 3 streams x 4 frames from 3 threads", flush=True)
+        th = [threading.Thread(target=stream_thread, args=(j,)) for j in range(B)]
+        for t_ in th:
+            t_.start()
+        for t_ in th:
+            t_.join()
+        assert not errors, errors
+        for t in range(T):
+            stamps = [got[j][t].t_submit_ns for j in range(B)]
+            assert len(set(stamps)) == B                       # every stream its own arrival
+            done = {got[j][t].t_overlay_done_ns for j in range(B)}
+            assert len(done) == 1 and max(stamps) <= done.pop()  # one batch, one departure
+            for j in range(B):
+                g = a.fetch(got[j][t], d_out[j][t])
+                for key in ("net_input", "logits", "mask", "argmax_idx", "present", "overlay"):
+                    assert np.array_equal(g[key], ref[t][j][key]), (t, j, key)
+        # the native driver over the same mux: one feed per stream, paced
+        feeds = [{"mux": mux, "mux_stream": j, "results_per_frame": 1,
+                  "frames": [[x.data_ptr()] for x in d_in[j]],
+                  "outs": [[x.data_ptr()] for x in d_out[j]]} for j in range(B)]
+        results, dropped, late, _ = api.hs_run_feeds(feeds, 500.0, 8)
+        assert dropped == [0] * B and all(len(r) == 8 for r in results)
+        for j in range(B):
+            assert [r[0].frame_id for r in results[j]] == list(range(8))
+            assert all(r[0].t_overlay_done_ns > r[0].t_submit_ns for r in results[j])
+    finally:
+        api.hs_destroy_mux(mux)
+        a.close()
+        ref_app.close()
