@@ -414,6 +414,11 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
   const int cc_begin = split * p.chunks_per_split;
   const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
   const bool has_proj = STRIDE == 2 && p.wt2 != nullptr;
+  // A layer with a single Cin chunk uses the same nine weight tiles for every tile a workgroup
+  // walks: with all nine held in the register stages they are fetched once per workgroup
+  // instead of once per tile (at 12 frames per launch the stage-1 layers otherwise pull four
+  // times more weight bytes than activation bytes from L2).
+  const bool keep_w = PERSIST && WS == 9 && p.chunks_per_tap == 1;
 
   // loop-invariant loader state
   const f16* l_wbase[WL];
@@ -507,7 +512,7 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
           *reinterpret_cast<u32x4*>(&s_patch[pb][l_plds[i]]) = l_poff[i] >= 0 ? st_p[i] : zero_; \
     }                                                                                          \
     __syncthreads();                                                                           \
-    if (!(LAST_) || (TAP_) + WS < 9)                                                           \
+    if ((!(LAST_) || (TAP_) + WS < 9) && !keep_w)                                              \
       HS_LOAD_W((TAP_) % WS, ((TAP_) + WS >= 9 ? (CCN_) : cc), ((TAP_) + WS) % 9)              \
     if (!(LAST_)) {                                                                            \
       _Pragma("unroll") for (int i = PT * (TAP_); i < PT * (TAP_) + PT; ++i)                   \
@@ -651,6 +656,8 @@ KernelDesc describe(const ConvParams& p) {
   const bool walk = p.tiles_per_wg > 1;
   if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1, false, 1>, grid, dim3(256), 0};
+  if (p.variant == 3 && walk && p.chunks_per_tap == 1)
+    return KernelDesc{(const void*)k_conv3x3_halo<2, 1, 9, 1, true, OCC3>, grid, dim3(256), 0};
   if (p.variant == 3)
     return KernelDesc{walk ? (const void*)k_conv3x3_halo<2, 1, 3, 1, true, OCC3>
                            : (const void*)k_conv3x3_halo<2, 1, 3, 1, false, 1>, grid, dim3(256), 0};
