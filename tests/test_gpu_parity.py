@@ -112,6 +112,8 @@ def test_config2_full_size_three_frames(hs, ctx):
     (128, 128, 128, 128, 0.5, 0.0),      # identity resize, alpha 0 => overlay == input
     (322, 241, 96, 72, 0.75, 1.0),       # odd frame size (pitch padding), upscale-free, opaque
     (64, 48, 160, 120, 0.3, 0.37),       # upscaling resize, odd alpha
+    (48, 8, 16384, 8, 0.5, 0.5),         # widest network input: interpolation weights up to 2^15
+    (10922, 9, 128, 16, 0.5, 0.5),       # widest frame (32768-byte rows), 85x decimation
 ])
 def test_tiny_net_edge_shapes(hs, ctx, fw, fh, nw, nh, thr, alpha):
     frames = list(si.uniform_frames(2, fh, fw, 5))
