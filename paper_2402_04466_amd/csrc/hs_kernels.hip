@@ -37,11 +37,13 @@ __device__ __forceinline__ uint32_t mad24(uint32_t a, uint32_t b, uint32_t c) {
   return r;
 }
 
-__global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
+// Block size: 256..512 threads, chosen by the host so that the passes over the output row are as
+// full as possible (854 pixels: two passes of 448 threads instead of four of 256).
+__global__ __launch_bounds__(512) void k_resize_norm(ResizeParams p) {
   extern __shared__ __align__(16) uint8_t lds[];
   __shared__ float s_lut32[256];
   __shared__ f16 s_lut16[256];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, T = blockDim.x;
   const int Y = blockIdx.x;
   const uint8_t* const src = p.src[blockIdx.y];          // stream blockIdx.y of the batch
   f16* const dst = p.dst + blockIdx.y * p.dst_img_stride;
@@ -58,19 +60,21 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
   const uint4* r1 = reinterpret_cast<const uint4*>(src + (size_t)y1 * p.src_pitch);
   uint4* l0 = reinterpret_cast<uint4*>(lds);
   uint4* l1 = l0 + row_vecs;
-  for (int v = tid; v < row_vecs; v += 256) {
+  for (int v = tid; v < row_vecs; v += T) {
     l0[v] = r0[v];
     l1[v] = r1[v];
   }
-  s_lut32[tid] = p.lut32[tid];
-  s_lut16[tid] = p.lut16[tid];
+  if (tid < 256) {
+    s_lut32[tid] = p.lut32[tid];
+    s_lut16[tid] = p.lut16[tid];
+  }
   __syncthreads();
 
   const uint32_t* p0 = reinterpret_cast<const uint32_t*>(lds);
   const uint32_t* p1 = reinterpret_cast<const uint32_t*>(lds + (size_t)row_vecs * 16);
   const uint32_t d = dx * dy;
   const uint32_t wy1 = fy, wy0 = dy - fy;
-  for (int X = tid; X < p.wo; X += 256) {
+  for (int X = tid; X < p.wo; X += T) {
     int nx = (2 * X + 1) * p.wi - p.wo;
     nx = max(0, min(nx, (p.wi - 1) * (int)dx));
     const uint32_t x0 = udiv_est((uint32_t)nx, dx, p.rcp_dx);
@@ -117,7 +121,10 @@ __global__ __launch_bounds__(256) void k_resize_norm(ResizeParams p) {
 
 KernelDesc describe(const ResizeParams& p) {
   const unsigned lds = (unsigned)((3 * p.wi + 15) >> 4) * 16 * 2 + 16;   // + padding read at the edge
-  return KernelDesc{(const void*)k_resize_norm, dim3(p.ho, p.batch), dim3(256), lds};
+  unsigned best = 256;
+  for (unsigned t = 320; t <= 512; t += 64)
+    if ((p.wo + t - 1) / t * t < (p.wo + best - 1) / best * best) best = t;
+  return KernelDesc{(const void*)k_resize_norm, dim3(p.ho, p.batch), dim3(best), lds};
 }
 
 // =============================================================================================
