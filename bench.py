@@ -77,7 +77,7 @@ def parse():
                          "its own thread (hs_mux); latency then counts from the stream's own "
                          "arrival and includes the wait for the rest of the batch")
     ap.add_argument("--paced-frames", type=int, default=60)
-    ap.add_argument("--repeats", type=int, default=1,
+    ap.add_argument("--repeats", type=int, default=3,
                     help="repeat the paced latency run this many times (state reset in between) "
                          "and pool the trimmed latencies, as the paper pools its repeated runs")
     ap.add_argument("--distinct-frames", type=int, default=8)
