@@ -144,8 +144,9 @@ KernelDesc describe(const ResizeParams& p) {
 __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
 // residual add, ReLU and store of 4 consecutive output channels n..n+3 of pixel m
+template <bool LOAD_RES = true>
 __device__ __forceinline__ void store_quad(const ConvParams& p, int m, int n, float v[4]) {
-  if (p.res) {
+  if (LOAD_RES && p.res) {
     const half4 r = *reinterpret_cast<const half4*>(p.res + (size_t)m * p.res_pitch + n);
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] += (float)r[j];
@@ -561,6 +562,21 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
 
   const int wm_rows = 4 * wm + (r >> 3);
   const int n_base = n0 + wn * 32 + h * 4;
+  // The residual of a block's second convolution is fetched while the tile's last chunk is
+  // still being computed, not between the last MFMA and the store (one full memory latency
+  // at the end of every such launch otherwise).  Loads are unconditional, from clamped addresses.
+  const bool res_here = p.res != nullptr && !p.use_partial;
+  half4 res_pre[MT][4];
+#define HS_RES_PREFETCH()                                                                      \
+  if (res_here) {                                                                              \
+    const int oy_ = min(y0 + wm_rows, p.hout - 1);                                             \
+    _Pragma("unroll") for (int g = 0; g < MT; ++g) {                                           \
+      const int ox_ = min(x0 + 8 * g + (r & 7), p.wout - 1);                                   \
+      const f16* rp_ = p.res + (size_t)(img * p.img_m + oy_ * p.wout + ox_) * p.res_pitch;     \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                            \
+        res_pre[g][i] = *reinterpret_cast<const half4*>(rp_ + min(n_base + 8 * i, p.cout - 4)); \
+    }                                                                                          \
+  }
   // Stores the finished tile (image img, origin y0, x0) and clears the accumulators.
   // Accumulator quad i of group g: channels n_base + 8*i .. +3 of pixel (oy, ox_g).
 #define HS_STORE_TILE()                                                                        \
@@ -581,7 +597,10 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
             if (n < p.cout) {                                                                  \
               float v[4] = {acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2],               \
                             acc[g][4 * i + 3]};                                                \
-              store_quad(p, m, n, v);                                                          \
+              if (res_here) {                                                                  \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j) v[j] += (float)res_pre[g][i][j]; \
+              }                                                                                \
+              store_quad<false>(p, m, n, v);                                                   \
             }                                                                                  \
           }                                                                                    \
         }                                                                                      \
@@ -631,7 +650,10 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
   for (int item = 0; item + 1 < n_items; ++item) {
     const bool cross = PERSIST && cc + 1 == cc_end;    // the next item starts a new tile
     const int cc_nx = cross ? cc_begin : cc + 1;
-    if (cross) { HS_TILE_SETUP(tm + 1, l_poff_n, img_n, y0_n, x0_n) }
+    if (cross) {
+      HS_TILE_SETUP(tm + 1, l_poff_n, img_n, y0_n, x0_n)
+      HS_RES_PREFETCH()
+    }
     HS_CHUNK(false, cc_nx, l_poff_n)
     if (PB == 2) pb ^= 1;
     if (cross) {
@@ -643,8 +665,10 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
     }
     cc = cc_nx;
   }
+  HS_RES_PREFETCH()
   HS_CHUNK(true, cc, l_poff)
   HS_STORE_TILE()
+#undef HS_RES_PREFETCH
 #undef HS_STORE_TILE
 #undef HS_CHUNK
 #undef HS_PROJ
