@@ -535,3 +535,40 @@ def test_concurrent_paced_streams_match_solo_runs(hs, ctx, partition):
     finally:
         for a in apps:
             a.close()
+
+
+def test_create_destroy_cycles_release_everything(hs, ctx):
+    """Applications (partitioned or not, grouped, behind a mux) can be created and destroyed
+    many times over: streams, events, threads and CU claims are all returned."""
+    from paper_2402_04466_amd import api
+    from paper_2402_04466_amd.harness import AppStream, GroupStream
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+    frame = si.uniform_frames(1, 240, 320, 3)[0]
+    n_cus = hs.hs_device_cus(ctx)
+    ref = None
+    for cycle in range(24):
+        kw = dict(net=hs.HS_NET_TINY4, frame_w=320, frame_h=240, net_w=128, net_h=128, blob=blob,
+                  palette=PAL, queue_depth=2 + cycle % 3)
+        a, b = AppStream(ctx, **kw), AppStream(ctx, **kw)
+        if cycle % 2:
+            hs.hs_set_partition(a.app, hs.cu_mask_words(range(0, n_cus // 2)),
+                                hs.cu_mask_words(range(0, n_cus // 2)))
+            hs.hs_set_partition(b.app, hs.cu_mask_words(range(n_cus // 2, n_cus - 8)),
+                                hs.cu_mask_words(range(n_cus - 8, n_cus)))
+        d_in, d_out = a.upload_frame(frame), a.new_output()
+        if cycle % 3 == 0:
+            g = GroupStream(ctx, [a, b])
+            assert g.submit(d_in, d_out, cycle) == hs.HS_OK
+            rs = g.wait_batch()
+            got = a.fetch(rs[0])["logits"]
+            g.close()
+        else:
+            mux = api.hs_create_mux(a.app, 1)
+            assert api.hs_mux_submit(mux, 0, d_in.data_ptr(), d_out.data_ptr(), cycle) == hs.HS_OK
+            r = api.hs_mux_wait(mux, 0)
+            got = a.fetch(r)["logits"]
+            api.hs_destroy_mux(mux)
+            a.close()
+            b.close()
+        ref = got if ref is None else ref
+        assert np.array_equal(got, ref), cycle
