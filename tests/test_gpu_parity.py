@@ -572,3 +572,53 @@ def test_create_destroy_cycles_release_everything(hs, ctx):
             b.close()
         ref = got if ref is None else ref
         assert np.array_equal(got, ref), cycle
+
+
+def test_long_concurrent_back_to_back_runs_are_deterministic(hs, ctx):
+    """Five applications of different kinds, sizes and queue depths push 400 frames each through
+    the device at the same time, as fast as their queues take them (native driver, one thread
+    each, frames of one application overlapping in two lanes where its depth is even).  Twice
+    over the final outputs -- which depend on every earlier frame through the recurrent state --
+    must be identical, and identical to what each application reaches when it runs alone."""
+    from paper_2402_04466_amd.harness import AppStream, run_back_to_back
+    fw, fh, n = 640, 360, 400
+    specs = [(hs.HS_NET_RESNET18_CONVLSTM, si.RESNET18_CONVLSTM_LAYERS, 224, 128, 4),
+             (hs.HS_NET_TINY4, si.TINY4_LAYERS, 128, 128, 4),
+             (hs.HS_NET_RESNET18_CONVLSTM, si.RESNET18_CONVLSTM_LAYERS, 288, 160, 2),
+             (hs.HS_NET_RESNET18_CONVLSTM, si.RESNET18_CONVLSTM_LAYERS, 160, 96, 3),
+             (hs.HS_NET_TINY4, si.TINY4_LAYERS, 96, 64, 6)]
+    apps, frames, outs = [], [], []
+    try:
+        for i, (net, layers, nw, nh, depth) in enumerate(specs):
+            a = AppStream(ctx, net=net, frame_w=fw, frame_h=fh, net_w=nw, net_h=nh,
+                          blob=si.he_normal_blob(layers, 20 + i), palette=PAL, queue_depth=depth)
+            apps.append(a)
+            frames.append([[a.upload_frame(f)] for f in si.tool_scene_frames(7, fh, fw, 80 + i)])
+            outs.append([[a.new_output()] for _ in range(depth)])
+
+        def last_outputs(results):
+            got = []
+            for a, rs in zip(apps, results):
+                assert [r[0].frame_id for r in rs] == list(range(n))
+                g = a.fetch(rs[-1][0])
+                got.append((g["logits"].copy(), g["mask"].copy()))
+            return got
+
+        runs = []
+        for rep in range(2):
+            for a in apps:
+                hs.hs_reset_state(a.app)
+            print(f"[long concurrent] pass {rep}: {len(apps)} applications x {n} frames", flush=True)
+            results, _ = run_back_to_back(apps, frames, outs, n)
+            runs.append(last_outputs(results))
+        for i in range(len(apps)):
+            assert np.array_equal(runs[0][i][0], runs[1][i][0]), f"application {i}: passes differ"
+            assert np.array_equal(runs[0][i][1], runs[1][i][1]), f"application {i}: passes differ"
+        for i, a in enumerate(apps):
+            hs.hs_reset_state(a.app)
+            results, _ = run_back_to_back([a], [frames[i]], [outs[i]], n)
+            g = a.fetch(results[0][-1][0])
+            assert np.array_equal(g["logits"], runs[0][i][0]), f"application {i}: differs from solo"
+    finally:
+        for a in apps:
+            a.close()
