@@ -255,6 +255,14 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
                           uint8_t* const* d_overlay_outs, uint64_t frame_id);
 hs_status hs_poll_batch(hs_app* app, hs_result* out);
 hs_status hs_wait_batch(hs_app* app, hs_result* out, uint64_t timeout_ns);
+/* As hs_submit_batch (also for batch = 1) when the frames are still being produced on one of the
+ * caller's own HIP streams: hip_event_frames_ready is a hipEvent_t the caller recorded on that
+ * stream after the last write to the frames; stage 1 is ordered behind it on the GPU, the call
+ * itself does not wait.  NULL: no dependency.  The stage-4 read of the frames is ordered behind
+ * stage 1 anyway.  t_submit_ns is still the time of the call. */
+hs_status hs_submit_batch_after(hs_app* app, const uint8_t* const* d_frames,
+                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
+                                void* hip_event_frames_ready);
 
 /* ---- multi-network applications (Section III-B) ------------------------------------- */
 

@@ -19,7 +19,8 @@ __all__ = [
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
-    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_poll_batch", "hs_wait_batch",
+    "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_submit_batch_after", "hs_poll_batch",
+    "hs_wait_batch",
     "hs_create_group", "hs_destroy_group", "hs_submit_group", "hs_poll_group", "hs_wait_group",
     "HS_MAX_GROUP", "hs_feed", "hs_run_feeds", "hs_create_mux", "hs_destroy_mux", "hs_mux_submit",
     "hs_mux_poll", "hs_mux_wait", "hs_latency_metrics_compute", "hs_mann_whitney_u", "hs_set_cpu_affinity", "hs_set_kernel_timing", "hs_set_launch_mode", "HS_LAUNCH_GRAPH", "HS_LAUNCH_EAGER",
@@ -128,6 +129,8 @@ def load() -> C.CDLL:
         "hs_get_state": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
         "hs_get_features": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
         "hs_submit_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
+        "hs_submit_batch_after": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                            C.c_void_p]),
         "hs_poll_batch": (C.c_int, [C.c_void_p, P(hs_result)]),
         "hs_wait_batch": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
         "hs_set_partition": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
@@ -324,6 +327,16 @@ def hs_submit_batch(app: int, d_frames, d_overlay_outs, frame_id: int) -> int:
     fr = (C.c_void_p * n)(*[int(x) for x in d_frames])
     ou = (C.c_void_p * n)(*[int(x) for x in d_overlay_outs])
     return _check(load().hs_submit_batch(app, fr, ou, frame_id), soft=(HS_E_QUEUE_FULL,))
+
+
+def hs_submit_batch_after(app: int, d_frames, d_overlay_outs, frame_id: int, hip_event: int) -> int:
+    """As hs_submit_batch, with stage 1 ordered behind a HIP event (its handle as an integer, e.g.
+    ``torch.cuda.Event.cuda_event``) that the caller recorded after producing the frames."""
+    n = len(d_frames)
+    fr = (C.c_void_p * n)(*[int(x) for x in d_frames])
+    ou = (C.c_void_p * n)(*[int(x) for x in d_overlay_outs])
+    return _check(load().hs_submit_batch_after(app, fr, ou, frame_id, hip_event),
+                  soft=(HS_E_QUEUE_FULL,))
 
 
 def hs_poll_batch(app: int, batch: int):

@@ -1393,7 +1393,7 @@ static void finish_submit(hs_app* app, Slot* s) {
 static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
                                uint64_t t_submit, bool own_overlay, Slot** slot_out,
-                               hipStream_t* stream_out) {
+                               hipStream_t* stream_out, hipEvent_t frames_ready = nullptr) {
   if (!app || !d_frames || !d_overlay_outs) { set_error("hs_submit_batch: NULL argument"); return HS_E_INVAL; }
   const int B = app->batch;
   for (int j = 0; j < B; ++j) {
@@ -1455,6 +1455,8 @@ static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
     HS_HIP(hipStreamWaitEvent(lane_stream, same_lane.ev_post, 0));
   }
   app->lane_last_stream[s->lane] = lane_stream;
+  // the caller's producer (another stream) may still be writing the frames
+  if (frames_ready) HS_HIP(hipStreamWaitEvent(lane_stream, frames_ready, 0));
   if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
     void* args[1];
     hipKernelNodeParams kp = node_params(s->pre[0], args);
@@ -1510,6 +1512,15 @@ hs_status hs_submit_batch(hs_app* app, const uint8_t* const* d_frames,
   const uint64_t t_submit = now_ns();
   if (refuse_grouped(app, "hs_submit_batch") != HS_OK) return HS_E_STATE;
   return submit_stages(app, d_frames, d_overlay_outs, frame_id, t_submit, true, nullptr, nullptr);
+}
+
+hs_status hs_submit_batch_after(hs_app* app, const uint8_t* const* d_frames,
+                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
+                                void* hip_event_frames_ready) {
+  const uint64_t t_submit = now_ns();
+  if (refuse_grouped(app, "hs_submit_batch_after") != HS_OK) return HS_E_STATE;
+  return submit_stages(app, d_frames, d_overlay_outs, frame_id, t_submit, true, nullptr, nullptr,
+                       (hipEvent_t)hip_event_frames_ready);
 }
 
 hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,

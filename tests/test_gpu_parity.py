@@ -622,3 +622,39 @@ def test_long_concurrent_back_to_back_runs_are_deterministic(hs, ctx):
     finally:
         for a in apps:
             a.close()
+
+
+def test_submit_behind_a_producer_event(hs, ctx):
+    """A frame still being written on the caller's own stream: with the producer's event handed
+    to the submit, stage 1 waits for it on the GPU and sees the finished frame."""
+    from paper_2402_04466_amd import api
+    from paper_2402_04466_amd.harness import AppStream
+    fw, fh = 640, 360
+    frame = list(si.tool_scene_frames(1, fh, fw, 33))[0]
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 5)
+    a = AppStream(ctx, net=hs.HS_NET_TINY4, frame_w=fw, frame_h=fh, net_w=128, net_h=128, blob=blob,
+                  palette=PAL, queue_depth=2)
+    try:
+        ready = a.upload_frame(frame)
+        d_out = a.new_output()
+        assert a.submit(ready, d_out, 0) == hs.HS_OK
+        ref = a.fetch(a.wait(), d_out)
+        # the producer: a long spin, then the copy of the real frame over a zeroed buffer
+        late = torch.zeros_like(ready)
+        d_out2 = a.new_output()
+        side = torch.cuda.Stream()
+        ev = torch.cuda.Event()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            torch.cuda._sleep(200_000_000)             # ~0.1 s of GPU time on the side stream
+            late.copy_(ready)
+            ev.record(side)
+        assert api.hs_submit_batch_after(a.app, [late.data_ptr()], [d_out2.data_ptr()], 1,
+                                         ev.cuda_event) == hs.HS_OK
+        r = a.wait()
+        got = a.fetch(r, d_out2)
+        for key in ("net_input", "logits", "mask", "overlay"):
+            assert np.array_equal(got[key], ref[key]), key
+        assert (r.t_overlay_done_ns - r.t_submit_ns) > 20_000_000   # it did wait for the producer
+    finally:
+        a.close()
