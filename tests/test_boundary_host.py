@@ -60,6 +60,15 @@ def test_stream_driver_and_group_calls_reject_bad_arguments_without_a_gpu():
     assert lib.hs_submit_group(None, None, None, 0) == hs.HS_E_INVAL
     assert lib.hs_poll_group(None, None) == hs.HS_E_INVAL
     assert lib.hs_wait_group(None, None, 0) == hs.HS_E_INVAL
+    mux = ctypes.c_void_p()
+    assert lib.hs_create_mux(None, 3, ctypes.byref(mux)) == hs.HS_E_INVAL
+    assert lib.hs_destroy_mux(None) == hs.HS_E_INVAL
+    assert lib.hs_mux_submit(None, 0, None, None, 0) == hs.HS_E_INVAL
+    assert lib.hs_mux_poll(None, 0, None) == hs.HS_E_INVAL
+    assert lib.hs_mux_wait(None, 0, None, 0) == hs.HS_E_INVAL
+    assert lib.hs_submit_batch_after(None, None, None, 0, None) == hs.HS_E_INVAL
+    sec = ctypes.c_double()
+    assert lib.hs_partition_copy(None, None, None, 16, 1, ctypes.byref(sec)) == hs.HS_E_INVAL
 
 
 # ---- admission control ---------------------------------------------------------------------
