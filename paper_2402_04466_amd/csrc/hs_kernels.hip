@@ -2,6 +2,8 @@
 // paper Section III-A stages format conversion -> inference -> postprocess -> overlay.
 #include "hs_kernels.h"
 
+#include <algorithm>
+
 namespace hs {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -38,7 +40,11 @@ __device__ __forceinline__ uint32_t mad24(uint32_t a, uint32_t b, uint32_t c) {
 }
 
 // Block size: 256..512 threads, chosen by the host so that the passes over the output row are as
-// full as possible (854 pixels: two passes of 448 threads instead of four of 256).
+// full as possible (854 pixels: two passes of 448 threads instead of four of 256) and that a
+// source row is at most kResizeVecs 16-byte vectors per thread.  The row loads are the first
+// thing a workgroup issues: the lookup tables and the row arithmetic are set up behind them.
+constexpr int kResizeVecs = 4;
+template <int NV>   // 16-byte vectors per thread and source row: 1, 2 or 4
 __global__ __launch_bounds__(512) void k_resize_norm(ResizeParams p) {
   extern __shared__ __align__(16) uint8_t lds[];
   __shared__ float s_lut32[256];
@@ -55,24 +61,38 @@ __global__ __launch_bounds__(512) void k_resize_norm(ResizeParams p) {
   const uint32_t fy = (uint32_t)ny - y0 * dy;
   const uint32_t y1 = min(y0 + 1u, (uint32_t)(p.hi - 1));
 
+  // the two source rows: 16-byte loads into named registers (as arrays they end up in scratch
+  // memory), addresses clamped to the row so that every load is unconditional
   const int row_vecs = (3 * p.wi + 15) >> 4;          // 16-byte vectors per source row
-  const uint4* r0 = reinterpret_cast<const uint4*>(src + (size_t)y0 * p.src_pitch);
-  const uint4* r1 = reinterpret_cast<const uint4*>(src + (size_t)y1 * p.src_pitch);
-  uint4* l0 = reinterpret_cast<uint4*>(lds);
-  uint4* l1 = l0 + row_vecs;
-  for (int v = tid; v < row_vecs; v += T) {
-    l0[v] = r0[v];
-    l1[v] = r1[v];
+  const uint4* const row0 = reinterpret_cast<const uint4*>(src + (size_t)y0 * p.src_pitch);
+  const uint4* const row1 = reinterpret_cast<const uint4*>(src + (size_t)y1 * p.src_pitch);
+  uint4 st0_0, st0_1, st0_2, st0_3, st1_0, st1_1, st1_2, st1_3;
+#define HS_FETCH_VEC(I_)                                                                       \
+  if constexpr (NV > I_) {                                                                     \
+    const int v_ = min(tid + I_ * T, row_vecs - 1);                                            \
+    st0_##I_ = row0[v_];                                                                       \
+    st1_##I_ = row1[v_];                                                                       \
   }
+#define HS_HAND_VEC(I_)                                                                        \
+  if constexpr (NV > I_) {                                                                     \
+    if (tid + I_ * T < row_vecs) {                                                             \
+      l0[tid + I_ * T] = st0_##I_;                                                             \
+      l1[tid + I_ * T] = st1_##I_;                                                             \
+    }                                                                                          \
+  }
+  HS_FETCH_VEC(0) HS_FETCH_VEC(1) HS_FETCH_VEC(2) HS_FETCH_VEC(3)
   if (tid < 256) {
     s_lut32[tid] = p.lut32[tid];
     s_lut16[tid] = p.lut16[tid];
   }
-  __syncthreads();
-
-  const uint32_t* p0 = reinterpret_cast<const uint32_t*>(lds);
-  const uint32_t* p1 = reinterpret_cast<const uint32_t*>(lds + (size_t)row_vecs * 16);
+  uint4* const l0 = reinterpret_cast<uint4*>(lds);
+  uint4* const l1 = l0 + row_vecs;
+  const uint32_t* const p0 = reinterpret_cast<const uint32_t*>(lds);
+  const uint32_t* const p1 = reinterpret_cast<const uint32_t*>(lds + (size_t)row_vecs * 16);
   const uint32_t d = dx * dy;
+
+  HS_HAND_VEC(0) HS_HAND_VEC(1) HS_HAND_VEC(2) HS_HAND_VEC(3)
+  __syncthreads();
   const uint32_t wy1 = fy, wy0 = dy - fy;
   for (int X = tid; X < p.wo; X += T) {
     int nx = (2 * X + 1) * p.wi - p.wo;
@@ -117,14 +137,29 @@ __global__ __launch_bounds__(512) void k_resize_norm(ResizeParams p) {
       o[2 * plane] = s_lut32[q[2]];
     }
   }
+#undef HS_HAND_VEC
+#undef HS_FETCH_VEC
+}
+
+static unsigned resize_block(const ResizeParams& p) {
+  const unsigned row_vecs = (unsigned)((3 * p.wi + 15) >> 4);
+  const unsigned t_min = std::max(256u, (row_vecs + kResizeVecs - 1) / kResizeVecs);
+  unsigned best = 0;
+  for (unsigned t = 256; t <= 512; t += 64) {
+    if (t < t_min) continue;
+    if (!best || (p.wo + t - 1) / t * t < (p.wo + best - 1) / best * best) best = t;
+  }
+  return best ? best : 512;
 }
 
 KernelDesc describe(const ResizeParams& p) {
   const unsigned lds = (unsigned)((3 * p.wi + 15) >> 4) * 16 * 2 + 16;   // + padding read at the edge
-  unsigned best = 256;
-  for (unsigned t = 320; t <= 512; t += 64)
-    if ((p.wo + t - 1) / t * t < (p.wo + best - 1) / best * best) best = t;
-  return KernelDesc{(const void*)k_resize_norm, dim3(p.ho, p.batch), dim3(best), lds};
+  const unsigned t = resize_block(p);
+  const unsigned nv = ((unsigned)((3 * p.wi + 15) >> 4) + t - 1) / t;
+  const void* f = nv <= 1   ? (const void*)k_resize_norm<1>
+                  : nv == 2 ? (const void*)k_resize_norm<2>
+                            : (const void*)k_resize_norm<kResizeVecs>;
+  return KernelDesc{f, dim3(p.ho, p.batch), dim3(t), lds};
 }
 
 // =============================================================================================
