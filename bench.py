@@ -89,7 +89,8 @@ def parse():
                     help="first run the library's plain copy kernel 4 times over this many MiB "
                          "(reference dispatches for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=6)
+    ap.add_argument("--cpu-frames", type=int, default=21,
+                    help="frames of the CPU oracle sample (the first is untimed): about 12 s of CPU work")
     return ap.parse_args()
 
 
@@ -282,6 +283,8 @@ def main():
                                         outs + tiny_outs, pin_cpus=pins,
                                         n_frames=args.paced_frames, with_lateness=True,
                                         muxes=muxes + [None] * len(tiny) if muxes else None)
+        print(f"[bench] paced run {rep + 1} of {max(1, args.repeats)} done", file=sys.stderr,
+              flush=True)
         lateness_us.extend(v / 1e3 for per in late for v in per)
         dropped.extend(drop)
         tiny_results, results = res_all[len(streams):], res_all[:len(streams)]
@@ -455,6 +458,8 @@ def main():
                    "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "tiny_groups": args.tiny_groups, "annotate": bool(args.annotate), "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]), "repeats": max(1, args.repeats),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
+                       "p999": round(float(np.percentile(lat_ms, 99.9)), 4),
+                       "above_2x_p50": int(np.sum(np.asarray(lat_ms) > 2.0 * m["p50"])),
                        "max": round(m["max"], 4), "mean": round(m["mean"], 4),
                        "std": round(m["std"], 4), "tail": round(m["tail"], 4),
                        "flatness": round(m["flatness"], 4), "dropped": int(sum(dropped)),
