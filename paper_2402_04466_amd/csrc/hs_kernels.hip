@@ -448,9 +448,13 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
   // last chunk of the current one, so the cold start is paid once per workgroup.
   const int groups_m = (p.tiles_m + p.tiles_per_wg - 1) / p.tiles_per_wg;
   if (tile >= groups_m * p.tiles_n * p.nsplit) return;
-  const int tm_begin = (tile % groups_m) * p.tiles_per_wg;
+  // Tile order inside an XCD's run: spatial tile fastest (the workgroups of one L2 share a
+  // weight slice), or channel tile fastest (they share input patches, and the layer's input is
+  // fetched into one L2 only); the host picks whichever fetches fewer bytes.
+  const int tm_begin =
+      (p.n_fastest ? (tile / p.tiles_n) % groups_m : tile % groups_m) * p.tiles_per_wg;
   const int tm_end = PERSIST ? min(p.tiles_m, tm_begin + p.tiles_per_wg) : tm_begin + 1;
-  const int tile_n = (tile / groups_m) % p.tiles_n;
+  const int tile_n = p.n_fastest ? tile % p.tiles_n : (tile / groups_m) % p.tiles_n;
   const int split = tile / (groups_m * p.tiles_n);
   const int tiles_img = p.tiles_m / p.batch;            // spatial tiles per image
   const int n0 = tile_n * BN;

@@ -349,6 +349,19 @@ struct Builder {
     }
     const int groups_m = (c.tiles_m + c.tiles_per_wg - 1) / c.tiles_per_wg;
     c.tiles_per_xcd = (groups_m * c.tiles_n * c.nsplit + 7) / 8;
+    // Tile order: every XCD (own L2) takes a run of consecutive tiles.  Spatial tile fastest:
+    // an XCD sees few channel tiles but min(8, tiles_n * nsplit) XCDs fetch the same input;
+    // channel tile fastest: the input goes to one L2 only, the weights to all eight.
+    c.n_fastest = 0;
+    if (c.variant >= 1 && c.variant <= 4 && c.tiles_n > 1) {
+      const double in_b = 2.0 * c.batch * c.hin * c.win * (c.chunks_per_tap * 64.0);
+      const double w_b = 2.0 * c.cout_pad * c.ktot;
+      const double pairs = (double)c.tiles_n * c.nsplit;        // (channel tile, K split) pairs
+      const double m_fast = in_b / c.nsplit * std::min(8.0, pairs) + w_b * std::max(1.0, 8.0 / pairs);
+      const double n_fast =
+          in_b + w_b * std::max(1.0, std::min(8.0, (double)groups_m * c.nsplit) / c.nsplit);
+      c.n_fastest = n_fast < 0.8 * m_fast ? 1 : 0;
+    }
   }
 
   // Appends the convolution and, when it is split along K, its reduction kernel.
