@@ -72,7 +72,8 @@ struct ConvParams {
   int tiles_per_wg;     // variant 1..4: consecutive spatial tiles one workgroup walks (>= 1);
                         // workgroups = ceil(tiles_m / tiles_per_wg) * tiles_n * nsplit
   int tiles_per_xcd;    // ceil(workgroups / 8)
-  int n_fastest;        // variant 1..4: channel tiles vary fastest in the tile order (else spatial)
+  int n_block;          // variant 1..4: channel tiles per block of the tile order (divides tiles_n;
+                        // 1: spatial tile fastest, tiles_n: channel tile fastest)
   int use_partial;      // 1: store fp32 partial sums for a reduction kernel, no epilogue here
   float* partial;       // [nsplit][m][cout_pad] fp32
   // fused epilogue (use_partial == 0)

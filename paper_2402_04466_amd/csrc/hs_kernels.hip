@@ -448,13 +448,16 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
   // last chunk of the current one, so the cold start is paid once per workgroup.
   const int groups_m = (p.tiles_m + p.tiles_per_wg - 1) / p.tiles_per_wg;
   if (tile >= groups_m * p.tiles_n * p.nsplit) return;
-  // Tile order inside an XCD's run: spatial tile fastest (the workgroups of one L2 share a
-  // weight slice), or channel tile fastest (they share input patches, and the layer's input is
-  // fetched into one L2 only); the host picks whichever fetches fewer bytes.
-  const int tm_begin =
-      (p.n_fastest ? (tile / p.tiles_n) % groups_m : tile % groups_m) * p.tiles_per_wg;
+  // Tile order inside a K split: blocks of n_block channel tiles; inside a block the channel
+  // tile varies fastest, then the spatial tile.  n_block == 1: the workgroups of one L2 share
+  // a weight slice and every L2 that holds a channel tile fetches the input; n_block ==
+  // tiles_n: they share input patches and every L2 fetches all the weights.  The host picks
+  // the block size that brings the fewest bytes into the eight L2s.
+  const int within = tile % (groups_m * p.tiles_n);
+  const int blk = groups_m * p.n_block, in_blk = within % blk;
+  const int tm_begin = (in_blk / p.n_block) * p.tiles_per_wg;
   const int tm_end = PERSIST ? min(p.tiles_m, tm_begin + p.tiles_per_wg) : tm_begin + 1;
-  const int tile_n = p.n_fastest ? tile % p.tiles_n : (tile / groups_m) % p.tiles_n;
+  const int tile_n = (within / blk) * p.n_block + in_blk % p.n_block;
   const int split = tile / (groups_m * p.tiles_n);
   const int tiles_img = p.tiles_m / p.batch;            // spatial tiles per image
   const int n0 = tile_n * BN;

@@ -349,18 +349,35 @@ struct Builder {
     }
     const int groups_m = (c.tiles_m + c.tiles_per_wg - 1) / c.tiles_per_wg;
     c.tiles_per_xcd = (groups_m * c.tiles_n * c.nsplit + 7) / 8;
-    // Tile order: every XCD (own L2) takes a run of consecutive tiles.  Spatial tile fastest:
-    // an XCD sees few channel tiles but min(8, tiles_n * nsplit) XCDs fetch the same input;
-    // channel tile fastest: the input goes to one L2 only, the weights to all eight.
-    c.n_fastest = 0;
+    // Tile order: every XCD (own L2) takes a run of tiles_per_xcd consecutive tiles.  For every
+    // block size, count what the eight L2s fetch (each its own spatial groups' input slices and
+    // its own channel tiles' weight slices, once) and keep the cheapest.
+    c.n_block = 1;
     if (c.variant >= 1 && c.variant <= 4 && c.tiles_n > 1) {
-      const double in_b = 2.0 * c.batch * c.hin * c.win * (c.chunks_per_tap * 64.0);
-      const double w_b = 2.0 * c.cout_pad * c.ktot;
-      const double pairs = (double)c.tiles_n * c.nsplit;        // (channel tile, K split) pairs
-      const double m_fast = in_b / c.nsplit * std::min(8.0, pairs) + w_b * std::max(1.0, 8.0 / pairs);
-      const double n_fast =
-          in_b + w_b * std::max(1.0, std::min(8.0, (double)groups_m * c.nsplit) / c.nsplit);
-      c.n_fastest = n_fast < 0.8 * m_fast ? 1 : 0;
+      const double in_unit = 2.0 * c.batch * c.hin * c.win * (c.chunks_per_tap * 64.0) /
+                             ((double)groups_m * c.nsplit);
+      const double w_unit = 2.0 * c.cout_pad * c.ktot / ((double)c.tiles_n * c.nsplit);
+      const int per_split = groups_m * c.tiles_n, total = per_split * c.nsplit;
+      double best = 0;
+      for (int nb = 1; nb <= c.tiles_n; nb *= 2) {
+        if (c.tiles_n % nb) continue;
+        double bytes = 0;
+        std::vector<char> seen_in((size_t)groups_m * c.nsplit), seen_w((size_t)c.tiles_n * c.nsplit);
+        for (int x = 0; x < 8; ++x) {
+          std::fill(seen_in.begin(), seen_in.end(), 0);
+          std::fill(seen_w.begin(), seen_w.end(), 0);
+          for (int t = x * c.tiles_per_xcd; t < std::min(total, (x + 1) * c.tiles_per_xcd); ++t) {
+            const int split = t / per_split, within = t % per_split;
+            const int blk = groups_m * nb, in_blk = within % blk;
+            const int gm = in_blk / nb, tn = (within / blk) * nb + in_blk % nb;
+            char& si = seen_in[(size_t)split * groups_m + gm];
+            char& sw = seen_w[(size_t)split * c.tiles_n + tn];
+            if (!si) { si = 1; bytes += in_unit; }
+            if (!sw) { sw = 1; bytes += w_unit; }
+          }
+        }
+        if (nb == 1 || bytes < 0.9 * best) { best = bytes; c.n_block = nb; }
+      }
     }
   }
 
