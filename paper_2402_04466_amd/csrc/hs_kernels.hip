@@ -203,6 +203,53 @@ __device__ __forceinline__ void store_quad(const ConvParams& p, int m, int n, fl
   }
 }
 
+// Epilogue of the 32 channels of one pixel that a lane pair (r, r + 32) holds as accumulator
+// quads: lane half h has channels cbase + 4h + 8i .. +3 in acc[4i .. 4i+3], i = 0..3.  Residual,
+// ReLU and rounding to fp16 as in store_quad; then the two lanes swap one quad of every pair
+// (v_permlane32_swap: lanes 32..63 of the first operand <-> lanes 0..31 of the second), so that
+// each holds 8 consecutive channels per pair and stores 16 bytes at a time instead of 8.
+// For fp16 outputs whose channel count is a multiple of 32.  Every lane of the wavefront must
+// call it (the swap needs both lanes of a pair); `valid` gates the store.
+__device__ __forceinline__ void store_octets(const ConvParams& p, bool valid, int m, int cbase,
+                                             int h, const floatx16& acc, const half4 (&res)[4],
+                                             bool has_res) {
+  uint32_t q[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float v[4] = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
+    if (has_res) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] += (float)res[i][j];
+    }
+    if (p.relu) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.0f);
+    }
+    half4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = (f16)v[j];
+    const uint2 w = __builtin_bit_cast(uint2, o);
+    q[i][0] = w.x;
+    q[i][1] = w.y;
+  }
+#pragma unroll
+  for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      const auto sw = __builtin_amdgcn_permlane32_swap(q[2 * pr][w], q[2 * pr + 1][w], false, false);
+      q[2 * pr][w] = sw[0];
+      q[2 * pr + 1][w] = sw[1];
+    }
+  if (valid) {
+    f16* dst = p.out + (size_t)m * p.out_pitch + cbase + h * 8;
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      const u32x4 o = {q[2 * pr][0], q[2 * pr][1], q[2 * pr + 1][0], q[2 * pr + 1][1]};
+      *reinterpret_cast<u32x4*>(dst + 16 * pr) = o;
+    }
+  }
+}
+
 template <int KC, int DEPTH>
 __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
   constexpr int BM = 64, BN = 64;
@@ -608,6 +655,10 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
   // still being computed, not between the last MFMA and the store (one full memory latency
   // at the end of every such launch otherwise).  Loads are unconditional, from clamped addresses.
   const bool res_here = p.res != nullptr && !p.use_partial;
+  // fp16 output with whole 64-channel tiles: 16-byte stores after a lane exchange (store_octets);
+  // not in the tile-walking stride-2 instantiation, which has no registers to spare for it
+  const bool wide_out =
+      !(STRIDE == 2 && PERSIST) && !p.use_partial && p.out_f32 == nullptr && (p.cout & 63) == 0;
   half4 res_pre[MT][4];
 #define HS_RES_PREFETCH()                                                                      \
   if (res_here) {                                                                              \
@@ -633,7 +684,7 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
           _Pragma("unroll") for (int i = 0; i < 4; ++i)                                        \
             *reinterpret_cast<float4*>(dst + 8 * i) = make_float4(                             \
                 acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]);       \
-        } else {                                                                               \
+        } else if (!wide_out) {                                                                \
           _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
             const int n = n_base + 8 * i;                                                      \
             if (n < p.cout) {                                                                  \
@@ -647,6 +698,9 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
           }                                                                                    \
         }                                                                                      \
       }                                                                                        \
+      if (wide_out)   /* every lane takes part in the exchange */                              \
+        store_octets(p, oy < p.hout && ox < p.wout, img * p.img_m + oy * p.wout + ox,          \
+                     n0 + wn * 32, h, acc[g], res_pre[g], res_here);                           \
       acc[g] = zero16;                                                                         \
     }                                                                                          \
     if (has_proj) { /* projection output: no residual, no ReLU */                              \
@@ -722,6 +776,162 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
 #undef HS_TILE_SETUP
 }
 
+// =============================================================================================
+// 3x3 stride-1 layers with 64 input channels (one Cin chunk) on grids several times the device:
+// the nine weight tiles of a workgroup's channel tile never change while it walks its spatial
+// tiles, so they are made resident once -- taps 0..4 in LDS, taps 5..8 as MFMA fragments in
+// registers (all nine in LDS would leave one workgroup per CU, all nine in registers none of
+// the registers).  A tile then costs one patch hand-over (two barriers) and 72 MFMAs per
+// wavefront with no weight traffic and no barrier between the taps.  Same tile, wavefront
+// layout and accumulation order (tap-major, four K-steps of 16 per tap) as
+// k_conv3x3_halo<2, 1, 9, 1, true, *>: results are bit-identical.
+// =============================================================================================
+__global__ __launch_bounds__(256, 2) void k_conv3x3_c64_walk(ConvParams p) {
+  constexpr int TH = 8, TW = 16, IPH = TH + 2, IPW = TW + 2, NPIX = IPH * IPW;
+  constexpr int PITCH = 64 + 8;
+  constexpr int RP = (IPW * PITCH * 2 + ((128 - (IPW * PITCH * 2) % 256 + 256) % 256)) / 2;
+  static_assert((RP * 2) % 256 == 128, "plane row pitch must be 128 mod 256 bytes");
+  constexpr int PV = NPIX * 8, PL = (PV + 255) / 256;
+  constexpr int LT = 5;                       // taps whose weights stay in LDS (the rest: registers)
+  constexpr int WT = 64 * PITCH;              // halves of one weight tile in LDS
+  static_assert(IPH * RP >= 2 * WT, "the patch buffer stages two weight tiles in the prologue");
+  __shared__ __align__(16) f16 s_patch[IPH * RP];
+  __shared__ __align__(16) f16 s_wk[LT * WT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  const int groups_m = (p.tiles_m + p.tiles_per_wg - 1) / p.tiles_per_wg;
+  if (tile >= groups_m * p.tiles_n) return;
+  const int blk = groups_m * p.n_block, in_blk = tile % blk;       // tile order: see k_conv3x3_halo
+  const int tm_begin = (in_blk / p.n_block) * p.tiles_per_wg;
+  const int tm_end = min(p.tiles_m, tm_begin + p.tiles_per_wg);
+  const int n0 = ((tile / blk) * p.n_block + in_blk % p.n_block) * 64;
+  const int tiles_img = p.tiles_m / p.batch;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int fw_off = (wn * 32 + r) * PITCH + h * 8;
+  const int fp_off = (4 * wm + (r >> 3)) * RP + (r & 7) * PITCH + h * 8;
+
+  // ---- patch loader: LDS slot and pixel of every vector are fixed, the source depends on the tile
+  int l_plds[PL], l_pyx[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) {
+    const int v = tid + 256 * i;
+    const int pix = min(v >> 3, NPIX - 1), py = pix / IPW, px = pix - py * IPW;
+    l_pyx[i] = py | (px << 8);
+    l_plds[i] = v >= PV ? -1 : py * RP + px * PITCH + (v & 7) * 8;
+  }
+  u32x4 st_p[PL];
+  uint32_t st_inb = 0;          // bit i: vector i of the fetched patch lies inside the image
+  int f_img = 0, f_y0 = 0, f_x0 = 0;   // image and origin of the tile whose patch is in st_p
+#define HS_FETCH_PATCH(TM_)                                                                    \
+  {                                                                                            \
+    f_img = (TM_) / tiles_img;                                                                 \
+    const int ts_ = (TM_) - f_img * tiles_img, ty_ = ts_ / p.tiles_x;                          \
+    f_y0 = ty_ * TH;                                                                           \
+    f_x0 = (ts_ - ty_ * p.tiles_x) * TW;                                                       \
+    st_inb = 0;                                                                                \
+    _Pragma("unroll") for (int i = 0; i < PL; ++i) {                                           \
+      const int iy_ = f_y0 + (l_pyx[i] & 0xff) - 1, ix_ = f_x0 + (l_pyx[i] >> 8) - 1;          \
+      const bool in_ = l_plds[i] >= 0 && iy_ >= 0 && iy_ < p.hin && ix_ >= 0 && ix_ < p.win;   \
+      st_inb |= (in_ ? 1u : 0u) << i;                                                          \
+      const int off_ = in_ ? ((f_img * p.hin + iy_) * p.win + ix_) * p.cin_pitch + (tid & 7) * 8 : 0; \
+      st_p[i] = *reinterpret_cast<const u32x4*>(p.in + off_);                                  \
+    }                                                                                          \
+  }
+  HS_FETCH_PATCH(tm_begin)
+
+  // ---- weights: taps 0..4 into their LDS tiles; taps 5..8, two at a time, through the (still
+  // unused) patch buffer into fragment registers
+  half8 a_keep[9 - LT][4];
+  {
+    const int row0 = tid >> 3, kv = tid & 7;        // this thread's vectors: rows row0, row0 + 32
+    const f16* w0 = p.wt + (size_t)(n0 + row0) * p.ktot + kv * 8;
+    const f16* w1 = w0 + (size_t)32 * p.ktot;
+    const int l0 = row0 * PITCH + kv * 8, l1 = l0 + 32 * PITCH;
+    u32x4 sw[9][2];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      sw[t][0] = *reinterpret_cast<const u32x4*>(w0 + t * 64);
+      sw[t][1] = *reinterpret_cast<const u32x4*>(w1 + t * 64);
+    }
+#pragma unroll
+    for (int t = 0; t < LT; ++t) {
+      *reinterpret_cast<u32x4*>(&s_wk[t * WT + l0]) = sw[t][0];
+      *reinterpret_cast<u32x4*>(&s_wk[t * WT + l1]) = sw[t][1];
+    }
+#pragma unroll
+    for (int pair = 0; pair < (9 - LT) / 2; ++pair) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        *reinterpret_cast<u32x4*>(&s_patch[j * WT + l0]) = sw[LT + 2 * pair + j][0];
+        *reinterpret_cast<u32x4*>(&s_patch[j * WT + l1]) = sw[LT + 2 * pair + j][1];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          a_keep[2 * pair + j][ks] =
+              *reinterpret_cast<const half8*>(&s_patch[j * WT + fw_off + ks * 16]);
+      __syncthreads();
+    }
+  }
+
+  const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int n_base = n0 + wn * 32 + h * 4;
+  for (int tm = tm_begin; tm < tm_end; ++tm) {
+    const int img = f_img, y0 = f_y0, x0 = f_x0;
+    if (tm != tm_begin) __syncthreads();      // every wavefront is done with the previous patch
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      if (l_plds[i] >= 0)
+        *reinterpret_cast<u32x4*>(&s_patch[l_plds[i]]) = ((st_inb >> i) & 1u) ? st_p[i] : zero;
+    }
+    __syncthreads();
+    if (tm + 1 < tm_end) HS_FETCH_PATCH(tm + 1)
+    // residual of this tile: fetched now, used after the MFMAs (clamped addresses, unconditional)
+    const int oy = y0 + 4 * wm + (r >> 3);
+    half4 res_pre[2][4];
+    if (p.res) {
+      const int oy_c = min(oy, p.hout - 1);
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int ox_c = min(x0 + 8 * g + (r & 7), p.wout - 1);
+        const f16* rp = p.res + (size_t)(img * p.img_m + oy_c * p.wout + ox_c) * p.res_pitch;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          res_pre[g][i] = *reinterpret_cast<const half4*>(rp + min(n_base + 8 * i, p.cout - 4));
+      }
+    }
+
+    floatx16 acc[2] = {zero16, zero16};
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const f16* fp = &s_patch[fp_off + (tap / 3) * RP + (tap % 3) * PITCH];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const half8 a = tap < LT ? *reinterpret_cast<const half8*>(&s_wk[tap * WT + fw_off + ks * 16])
+                                 : a_keep[tap < LT ? 0 : tap - LT][ks];
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          const half8 b = *reinterpret_cast<const half8*>(fp + g * 8 * PITCH + ks * 16);
+          acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[g], 0, 0, 0);
+        }
+      }
+    }
+
+    // fp16 output with a multiple of 64 channels (the host selects this kernel only then)
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int ox = x0 + 8 * g + (r & 7);
+      store_octets(p, oy < p.hout && ox < p.wout, img * p.img_m + oy * p.wout + ox, n0 + wn * 32, h,
+                   acc[g], res_pre[g], p.res != nullptr);
+    }
+  }
+#undef HS_FETCH_PATCH
+}
+
 constexpr int OCC3 = 2, OCC4 = 2;   // waves per SIMD the tile-walking instantiations are built for
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
@@ -729,6 +939,9 @@ KernelDesc describe(const ConvParams& p) {
   const bool walk = p.tiles_per_wg > 1;
   if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1, false, 1>, grid, dim3(256), 0};
+  if (p.variant == 3 && walk && p.chunks_per_tap == 1 && !p.use_partial && p.nsplit == 1 &&
+      !p.out_f32 && p.cout % 64 == 0)
+    return KernelDesc{(const void*)k_conv3x3_c64_walk, grid, dim3(256), 0};
   if (p.variant == 3 && walk && p.chunks_per_tap == 1)
     return KernelDesc{(const void*)k_conv3x3_halo<2, 1, 9, 1, true, OCC3>, grid, dim3(256), 0};
   if (p.variant == 3)
