@@ -63,7 +63,10 @@ struct ConvParams {
                         // 4: 3x3/2 pad-1 layers the same way (8 x 8 tile, patch stored as four
                         //    parity planes), optionally with the block's 1x1/2 projection of
                         //    the same input fused in (wt2 != NULL)
-  int tiles_x;          // variant 1..4: spatial tiles per output row
+                        // 5: a whole 64 -> 64 -> 64 channel block (two 3x3/1 convolutions, ReLU
+                        //    between, shortcut from the input, ReLU) in one launch
+                        //    (k_block64_fused): wt = first, wt2 = second convolution, res = in
+  int tiles_x;          // variant 1..5: spatial tiles per output row
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;
   // split-K: blockIdx.z handles chunks [z*chunks_per_split, ...)

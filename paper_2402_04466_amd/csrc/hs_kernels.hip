@@ -932,11 +932,181 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_c64_walk(ConvParams p) {
 #undef HS_FETCH_PATCH
 }
 
+// =============================================================================================
+// A whole 64-channel BasicBlock in one launch: out = ReLU(conv_b(ReLU(conv_a(x))) + x), both
+// convolutions 3x3 stride 1 pad 1, 64 -> 64 channels (one workgroup owns every channel of its
+// tile, so the intermediate tensor need not leave the CU).  For small grids (one frame, a few
+// frames): there a layer is a kernel boundary, a cold start and nine dependent steps, and the
+// block costs one of each of the first two instead of two.
+//
+// Output tile 8 x 16.  conv_b needs the intermediate on 10 x 18 pixels, conv_a therefore the
+// input on 12 x 20.  Phase A: the 180 intermediate pixels in row-major order form six groups of
+// 32 (the last 12 lanes idle); wavefront (wm, wn) computes groups wm, wm + 2, wm + 4 for
+// channels 32*wn .. +31 and writes them -- ReLU, rounded to fp16 exactly as the unfused layer
+// stores them, zero outside the image (conv_b's padding) -- into LDS over the input patch.
+// Phase B is the tile loop body of k_conv3x3_c64_walk on that patch.  The 18 weight tiles
+// stream through nine register stages and a double-buffered LDS tile, one barrier per tap;
+// every output accumulates tap-major with four K-steps of 16 per tap, as in the unfused
+// kernels: results are bit-identical to two k_conv3x3_halo launches.
+// p.wt / p.wt2: packed weights of conv_a / conv_b; p.res = p.in (the shortcut).
+// =============================================================================================
+__global__ __launch_bounds__(256, 2) void k_block64_fused(ConvParams p) {
+  constexpr int TH = 8, TW = 16, YH = TH + 2, YW = TW + 2, XH = TH + 4, XW = TW + 4;
+  constexpr int PITCH = 64 + 8;
+  constexpr int RPY = (YW * PITCH * 2 + ((128 - (YW * PITCH * 2) % 256 + 256) % 256)) / 2;
+  constexpr int RPX = (XW * PITCH * 2 + ((128 - (XW * PITCH * 2) % 256 + 256) % 256)) / 2;
+  static_assert((RPY * 2) % 256 == 128 && (RPX * 2) % 256 == 128, "row pitch must be 128 mod 256 bytes");
+  static_assert(XH * RPX >= YH * RPY, "the intermediate patch is written over the input patch");
+  constexpr int NPY = YH * YW;                         // 180 intermediate pixels
+  constexpr int XV = XH * XW * 8, XL = (XV + 255) / 256;   // input patch vectors, per thread
+  constexpr int WT = 64 * PITCH;
+  __shared__ __align__(16) f16 s_xy[XH * RPX];
+  __shared__ __align__(16) f16 s_w[2 * WT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tm = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if (tm >= p.tiles_m) return;
+  const int tiles_img = p.tiles_m / p.batch;
+  const int img = tm / tiles_img, ts = tm - img * tiles_img, ty = ts / p.tiles_x;
+  const int y0 = ty * TH, x0 = (ts - ty * p.tiles_x) * TW;
+  const int wm = wave & 1, wn = wave >> 1;
+
+  // ---- input patch: pixel (y0 - 2 + py, x0 - 2 + px), zeros outside the image
+  u32x4 st_x[XL];
+  uint32_t x_inb = 0;
+#pragma unroll
+  for (int i = 0; i < XL; ++i) {
+    const int v = tid + 256 * i;
+    const int pix = min(v >> 3, XH * XW - 1), py = pix / XW, px = pix - py * XW;
+    const int iy = y0 - 2 + py, ix = x0 - 2 + px;
+    const bool in = v < XV && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+    x_inb |= (in ? 1u : 0u) << i;
+    const int off = in ? ((img * p.hin + iy) * p.win + ix) * p.cin_pitch + (tid & 7) * 8 : 0;
+    st_x[i] = *reinterpret_cast<const u32x4*>(p.in + off);
+  }
+  // ---- weights: stage t holds tap t of conv_a, later tap t of conv_b
+  const int w_row = tid >> 3, w_kv = tid & 7;
+  const f16* wa0 = p.wt + (size_t)w_row * p.ktot + w_kv * 8;
+  const f16* wa1 = wa0 + (size_t)32 * p.ktot;
+  const f16* wb0 = p.wt2 + (size_t)w_row * p.ktot + w_kv * 8;
+  const f16* wb1 = wb0 + (size_t)32 * p.ktot;
+  const int wl0 = w_row * PITCH + w_kv * 8, wl1 = wl0 + 32 * PITCH;
+  u32x4 st_w[9][2];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    st_w[t][0] = *reinterpret_cast<const u32x4*>(wa0 + t * 64);
+    st_w[t][1] = *reinterpret_cast<const u32x4*>(wa1 + t * 64);
+  }
+#pragma unroll
+  for (int i = 0; i < XL; ++i) {
+    const int v = tid + 256 * i;
+    if (v < XV) {
+      const int pix = v >> 3, py = pix / XW, px = pix - py * XW;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(&s_xy[py * RPX + px * PITCH + (v & 7) * 8]) =
+          ((x_inb >> i) & 1u) ? st_x[i] : zero;
+    }
+  }
+
+  const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int fw_off = (wn * 32 + r) * PITCH + h * 8;
+
+  // ---- phase A: intermediate pixel q = 32*(wm + 2k) + r of the 10 x 18 patch, k = 0..2
+  int a_py[3], a_px[3], a_off[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int q = min(32 * (wm + 2 * k) + r, NPY - 1);
+    a_py[k] = q / YW;
+    a_px[k] = q - a_py[k] * YW;
+    a_off[k] = a_py[k] * RPX + a_px[k] * PITCH + h * 8;
+  }
+  floatx16 acc_a[3] = {zero16, zero16, zero16};
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap) {
+    f16* sw = &s_w[(tap & 1) * WT];
+    *reinterpret_cast<u32x4*>(&sw[wl0]) = st_w[tap][0];
+    *reinterpret_cast<u32x4*>(&sw[wl1]) = st_w[tap][1];
+    __syncthreads();
+    st_w[tap][0] = *reinterpret_cast<const u32x4*>(wb0 + tap * 64);
+    st_w[tap][1] = *reinterpret_cast<const u32x4*>(wb1 + tap * 64);
+    const int toff = (tap / 3) * RPX + (tap % 3) * PITCH;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const half8 a = *reinterpret_cast<const half8*>(&sw[fw_off + ks * 16]);
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const half8 b = *reinterpret_cast<const half8*>(&s_xy[a_off[k] + toff + ks * 16]);
+        acc_a[k] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc_a[k], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();          // every wavefront is done with the input patch
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int q = 32 * (wm + 2 * k) + r;
+    const int iy = y0 - 1 + a_py[k], ix = x0 - 1 + a_px[k];
+    const bool inside = iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+    if (q < NPY) {
+      f16* dst = &s_xy[a_py[k] * RPY + a_px[k] * PITCH + wn * 32 + h * 4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        half4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = inside ? (f16)fmaxf(acc_a[k][4 * i + j], 0.0f) : (f16)0.0f;
+        *reinterpret_cast<half4*>(dst + 8 * i) = o;
+      }
+    }
+  }
+
+  // ---- residual of this tile (the block's input), fetched now, used after phase B
+  const int oy = y0 + 4 * wm + (r >> 3);
+  const int n_base = wn * 32 + h * 4;
+  half4 res_pre[2][4];
+  {
+    const int oy_c = min(oy, p.hout - 1);
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int ox_c = min(x0 + 8 * g + (r & 7), p.wout - 1);
+      const f16* rp = p.res + (size_t)(img * p.img_m + oy_c * p.wout + ox_c) * p.res_pitch;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) res_pre[g][i] = *reinterpret_cast<const half4*>(rp + n_base + 8 * i);
+    }
+  }
+
+  // ---- phase B: conv_b on the intermediate patch (the first barrier below also publishes it)
+  const int fp_off = (4 * wm + (r >> 3)) * RPY + (r & 7) * PITCH + h * 8;
+  floatx16 acc_b[2] = {zero16, zero16};
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap) {
+    f16* sw = &s_w[((tap + 1) & 1) * WT];       // continues the alternation of phase A (taps 9..17)
+    *reinterpret_cast<u32x4*>(&sw[wl0]) = st_w[tap][0];
+    *reinterpret_cast<u32x4*>(&sw[wl1]) = st_w[tap][1];
+    __syncthreads();
+    const f16* fp = &s_xy[fp_off + (tap / 3) * RPY + (tap % 3) * PITCH];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const half8 a = *reinterpret_cast<const half8*>(&sw[fw_off + ks * 16]);
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const half8 b = *reinterpret_cast<const half8*>(fp + g * 8 * PITCH + ks * 16);
+        acc_b[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc_b[g], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const int ox = x0 + 8 * g + (r & 7);
+    store_octets(p, oy < p.hout && ox < p.wout, img * p.img_m + oy * p.wout + ox, wn * 32, h,
+                 acc_b[g], res_pre[g], true);
+  }
+}
+
 constexpr int OCC3 = 2, OCC4 = 2;   // waves per SIMD the tile-walking instantiations are built for
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
   const dim3 grid(8u * (unsigned)p.tiles_per_xcd);
   const bool walk = p.tiles_per_wg > 1;
+  if (p.variant == 5) return KernelDesc{(const void*)k_block64_fused, grid, dim3(256), 0};
   if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 3 && walk && p.chunks_per_tap == 1 && !p.use_partial && p.nsplit == 1 &&
