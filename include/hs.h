@@ -223,7 +223,9 @@ hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
                            const uint32_t* cu_mask_overlay, int n_words);
 /* The admission predicate alone, on host data (no GPU needed): would a request for
  * req_infer | req_overlay be admitted given the CUs already claimed by others?
- * Returns HS_OK or HS_E_OVERSUBSCRIBED / HS_E_INVAL exactly as hs_set_partition would. */
+ * Returns HS_OK or HS_E_OVERSUBSCRIBED / HS_E_INVAL exactly as hs_set_partition would (it is
+ * the same function): HS_E_OVERSUBSCRIBED for an empty mask, a CU >= device_cus or a claimed
+ * CU; HS_E_INVAL for bad arguments or a mask without a CU on each of the device_cus / 32 XCDs. */
 hs_status hs_admission_check(const uint32_t* claimed_by_others, const uint32_t* req_infer,
                              const uint32_t* req_overlay, int n_words, int device_cus);
 
@@ -236,7 +238,11 @@ hs_status hs_admission_check(const uint32_t* claimed_by_others, const uint32_t* 
  *                 alias d_frame
  * Frames of one application are processed strictly in submit order (the recurrent
  * state of frame t feeds frame t+1). HS_E_QUEUE_FULL (frame NOT enqueued) when
- * queue_depth frames are in flight or unpolled. */
+ * queue_depth frames are in flight or unpolled.  If a HIP call fails after part of the frame
+ * has been handed to the GPU (HS_E_DEVICE), the recurrent state may already have been advanced
+ * by a frame that is never delivered: the application is unusable from then on, every later
+ * submit returns HS_E_DEVICE, and it must be destroyed.  The same holds for every member of a
+ * group when hs_submit_group fails that way. */
 hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
                           uint64_t frame_id);
 /* Deliver the oldest finished, not yet delivered frame (submit order). Non-blocking:
@@ -368,7 +374,8 @@ hs_status hs_device_copy(hs_ctx* ctx, void* d_dst, const void* d_src, size_t byt
  * A stream whose previous frame still waits for its batch gets HS_E_QUEUE_FULL, and so does the
  * stream that would complete a batch while the application's queue is full (its frame is not
  * taken, the others keep waiting).  While a mux exists the application is driven only through
- * it.  The calls are thread-safe among themselves.  `batch` must equal the application's. */
+ * it.  The calls are thread-safe among themselves.  hs_create_mux: HS_E_INVAL unless `batch`
+ * equals the application's batch, HS_E_STATE for a member of a group. */
 hs_status hs_create_mux(hs_app* app, int batch, hs_mux** out);
 hs_status hs_destroy_mux(hs_mux* mux);
 hs_status hs_mux_submit(hs_mux* mux, int stream, const uint8_t* d_frame, uint8_t* d_overlay_out,

@@ -88,6 +88,17 @@ static bool mux_take(hs_mux* m, int stream, hs_result* out) {
 extern "C" hs_status hs_create_mux(hs_app* app, int batch, hs_mux** out) {
   using hs::set_error;
   if (!app || !out || batch < 1 || batch > 16) { set_error("hs_create_mux: bad argument"); return HS_E_INVAL; }
+  // the batch buffers below are handed to hs_submit_batch / hs_poll_batch, which move exactly
+  // the application's batch of entries
+  if (batch != hs_internal_app_batch(app)) {
+    set_error("hs_create_mux: batch %d given, the application batches %d streams", batch,
+              hs_internal_app_batch(app));
+    return HS_E_INVAL;
+  }
+  if (hs_internal_app_grouped(app)) {
+    set_error("hs_create_mux: the application is a member of a group");
+    return HS_E_STATE;
+  }
   try {
     hs_mux* m = new hs_mux();
     m->app = app;

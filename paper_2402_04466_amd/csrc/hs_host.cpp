@@ -22,6 +22,8 @@ void set_error(const char* fmt, ...) {
   va_end(ap);
 }
 
+int xcd_count(int device_cus) { return std::max(1, device_cus / 32); }
+
 hs_status admission_check(const uint32_t* claimed, const uint32_t* req_a, const uint32_t* req_b,
                           int n_words, int device_cus) {
   if (!req_a || !req_b || n_words < 1 || n_words > HS_MAX_CU_WORDS || device_cus < 1 ||
@@ -51,6 +53,23 @@ hs_status admission_check(const uint32_t* claimed, const uint32_t* req_a, const 
   if (!any_a || !any_b) {
     set_error("admission denied: empty CU mask");
     return HS_E_OVERSUBSCRIBED;
+  }
+  // The device deals workgroups to all of its XCDs (32 CUs each) and CU i sits on XCD
+  // i mod n_xcd: a mask that leaves an XCD without a CU cannot be bound to a queue.
+  const int n_xcd = xcd_count(device_cus);
+  for (int which = 0; which < 2; ++which) {
+    const uint32_t* m = which ? req_b : req_a;
+    for (int x = 0; x < n_xcd; ++x) {
+      bool any = false;
+      for (int cu = x; cu < 32 * n_words && cu < device_cus; cu += n_xcd)
+        any = any || ((m[cu / 32] >> (cu % 32)) & 1u);
+      if (!any) {
+        set_error("admission: %s mask has no CU on XCD %d (CU i is on XCD i mod %d); "
+                  "use whole groups of %d consecutive CUs", which ? "overlay" : "inference", x,
+                  n_xcd, n_xcd);
+        return HS_E_INVAL;
+      }
+    }
   }
   return HS_OK;
 }

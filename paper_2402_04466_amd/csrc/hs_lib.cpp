@@ -885,7 +885,9 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
         rp.d_magic = (uint32_t)((num + D - 1) / D);
         rp.d_shift = (uint32_t)(l - 1);
       }
-      r.bytes = B * (3.0 * d->frame_w * d->frame_h + 8.0 * d->net_w * d->net_h +
+      // algorithmic bytes: the frame read once, three fp16 channels written per pixel (the
+      // fourth, zero channel of the padded layout is this implementation's, not the method's)
+      r.bytes = B * (3.0 * d->frame_w * d->frame_h + 6.0 * d->net_w * d->net_h +
                      (d->net_fp32_input ? 12.0 * d->net_w * d->net_h : 0.0));
       s.pre.push_back(r);
     }
@@ -1145,6 +1147,13 @@ static hs_status guarded(const char* fn, F&& body) {
     return HS_E_DEVICE;
   }
 }
+
+extern "C" {
+
+}  // extern "C"
+
+int hs_internal_app_batch(const hs_app* app) { return app->batch; }
+int hs_internal_app_grouped(const hs_app* app) { return app->group != nullptr; }
 
 extern "C" {
 
@@ -1428,23 +1437,6 @@ hs_status hs_set_partition(hs_app* app, const uint32_t* cu_mask_infer,
       for (int w = 0; w < HS_MAX_CU_WORDS; ++w) others[w] |= o->claim[w];
   hs_status st = admission_check(others, cu_mask_infer, cu_mask_overlay, n_words, ctx->n_cus);
   if (st != HS_OK) return st;
-  // The device deals workgroups to all of its XCDs, and CU i sits on XCD i mod n_xcd: a mask
-  // that leaves an XCD without a CU cannot be bound to a queue (the runtime refuses it).
-  const int n_xcd = std::max(1, ctx->n_cus / 32);
-  for (int which = 0; which < 2; ++which) {
-    const uint32_t* m = which ? cu_mask_overlay : cu_mask_infer;
-    for (int x = 0; x < n_xcd; ++x) {
-      bool any = false;
-      for (int cu = x; cu < 32 * n_words && cu < ctx->n_cus; cu += n_xcd)
-        any = any || ((m[cu / 32] >> (cu % 32)) & 1u);
-      if (!any) {
-        set_error("hs_set_partition: %s mask has no CU on XCD %d (CU i is on XCD i mod %d); "
-                  "use whole groups of %d consecutive CUs", which ? "overlay" : "inference", x,
-                  n_xcd, n_xcd);
-        return HS_E_INVAL;
-      }
-    }
-  }
   st = make_streams(app, cu_mask_infer, cu_mask_overlay, n_words);
   if (st != HS_OK) return st;
   std::memset(app->claim, 0, sizeof(app->claim));
@@ -1469,6 +1461,21 @@ static void finish_submit(hs_app* app, Slot* s) {
 // Enqueues stages 1-3 of one batch and, with own_overlay, stage 4 as well.  Without it the
 // caller draws the overlay (a group), records s->ev_overlay and calls finish_submit; *slot_out
 // and *stream_out then name the slot taken and the stream whose tail is the ev_post record.
+static hs_status enqueue_stages(hs_app* app, Slot* s, bool idle, const uint8_t* const* d_frames,
+                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
+                                uint64_t t_submit, bool own_overlay, Slot** slot_out,
+                                hipStream_t* stream_out, hipEvent_t frames_ready);
+
+// A submit that fails after part of a frame has been handed to the GPU leaves the recurrent
+// state advanced by a frame that is never delivered: the application is unusable from then on.
+// Every later submit returns HS_E_DEVICE with this message.
+static void poison(hs_app* app, const char* what) {
+  std::lock_guard<std::mutex> lk(app->mu);
+  if (app->completer_error.empty())
+    app->completer_error = std::string("a submit failed after work had been enqueued (") + what +
+                           "); destroy the application";
+}
+
 static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
                                uint64_t t_submit, bool own_overlay, Slot** slot_out,
@@ -1498,7 +1505,18 @@ static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
     s = &app->slots[app->n_submitted % app->depth];
     idle = app->n_completed == app->n_submitted;
   }
+  const hs_status st = enqueue_stages(app, s, idle, d_frames, d_overlay_outs, frame_id, t_submit,
+                                      own_overlay, slot_out, stream_out, frames_ready);
+  if (st != HS_OK) poison(app, hs_last_error());
+  return st;
+}
+
+static hs_status enqueue_stages(hs_app* app, Slot* s, bool idle, const uint8_t* const* d_frames,
+                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
+                                uint64_t t_submit, bool own_overlay, Slot** slot_out,
+                                hipStream_t* stream_out, hipEvent_t frames_ready) {
   HS_HIP(hipSetDevice(app->ctx->device));
+  const int B = app->batch;
   const size_t n_map = (size_t)app->map_w * app->map_h;
   const size_t netin_img = (size_t)app->netin_h * app->netin_w * 4;
   for (int j = 0; j < B; ++j) {
@@ -1802,18 +1820,31 @@ hs_status hs_submit_group(hs_group* group, const uint8_t* d_frame, uint8_t* d_ov
     slot[i] = w->slot; tail[i] = w->tail;
     if (st0 == HS_OK && w->status != HS_OK) { st0 = w->status; err0 = w->error; }
   }
-  if (st0 != HS_OK) { set_error("%s", err0.c_str()); return st0; }
+  // From here on a failure leaves some members a frame ahead of the others (their cells have
+  // been updated by a frame that will never be delivered): the whole group is poisoned.
+  auto fail_all = [&](hs_status st) {
+    const std::string why = hs_last_error();
+    for (hs_app* a : group->members) poison(a, why.c_str());
+    set_error("%s", why.c_str());
+    return st;
+  };
+  if (st0 != HS_OK) { set_error("%s", err0.c_str()); return fail_all(st0); }
   for (size_t i = 0; i < n; ++i) op.layer[i] = slot[i]->overlay[0].overlay.layer[0];
   op.src[0] = d_frame;
   op.dst[0] = d_overlay_out;
   // one launch draws every member's layer, on member 0's overlay stream, after all stage 3s
   hs_app* a0 = group->members[0];
   hipStream_t ov_stream = a0->s_overlay ? a0->s_overlay : tail[0];
-  for (size_t i = 0; i < n; ++i)
-    if (tail[i] != ov_stream) HS_HIP(hipStreamWaitEvent(ov_stream, slot[i]->ev_post, 0));
-  hs_status st = run_ops(a0, group->overlay, ov_stream);
-  if (st != HS_OK) return st;
-  for (size_t i = 0; i < n; ++i) HS_HIP(hipEventRecord(slot[i]->ev_overlay, ov_stream));
+  auto overlay_all = [&]() -> hs_status {
+    for (size_t i = 0; i < n; ++i)
+      if (tail[i] != ov_stream) HS_HIP(hipStreamWaitEvent(ov_stream, slot[i]->ev_post, 0));
+    const hs_status st = run_ops(a0, group->overlay, ov_stream);
+    if (st != HS_OK) return st;
+    for (size_t i = 0; i < n; ++i) HS_HIP(hipEventRecord(slot[i]->ev_overlay, ov_stream));
+    return HS_OK;
+  };
+  const hs_status st = overlay_all();
+  if (st != HS_OK) return fail_all(st);
   for (size_t i = 0; i < n; ++i) finish_submit(group->members[i], slot[i]);
   return HS_OK;
 }

@@ -77,15 +77,17 @@ def _m(cus):
 
 
 def test_admission_disjoint_partitions_are_admitted_until_full():
-    """Six equal partitions of 42 CUs (6 x 42 = 252 <= 256) fit; a seventh does not."""
+    """Six equal partitions of 40 CUs (five groups of 8 consecutive CUs: 32 for inference, 8 for
+    the overlay; 6 x 40 = 240 <= 256) fit; a request that touches a claimed CU does not; the two
+    groups left over do."""
     claimed = np.zeros(8, np.uint32)
     for i in range(6):
-        infer, over = _m(range(42 * i, 42 * i + 36)), _m(range(42 * i + 36, 42 * i + 42))
+        infer, over = _m(range(40 * i, 40 * i + 32)), _m(range(40 * i + 32, 40 * i + 40))
         assert hs.hs_admission_check(claimed, infer, over, 256) == hs.HS_OK
         claimed |= infer | over
-    assert hs.hs_admission_check(claimed, _m(range(250, 256)), _m(range(250, 256)), 256) \
+    assert hs.hs_admission_check(claimed, _m(range(232, 248)), _m(range(232, 248)), 256) \
         == hs.HS_E_OVERSUBSCRIBED
-    assert hs.hs_admission_check(claimed, _m(range(252, 256)), _m(range(252, 256)), 256) == hs.HS_OK
+    assert hs.hs_admission_check(claimed, _m(range(240, 256)), _m(range(240, 248)), 256) == hs.HS_OK
 
 
 def test_admission_five_quarters_oversubscribe():
@@ -102,15 +104,39 @@ def test_admission_five_quarters_oversubscribe():
 
 
 def test_admission_rejects_empty_out_of_range_and_bad_args():
+    # a device of 24 CUs has a single XCD: only the emptiness / range / claim rules act
     z = np.zeros(8, np.uint32)
-    assert hs.hs_admission_check(None, z, _m([1]), 256) == hs.HS_E_OVERSUBSCRIBED
-    assert hs.hs_admission_check(None, _m([1]), z, 256) == hs.HS_E_OVERSUBSCRIBED
-    assert hs.hs_admission_check(None, _m([200]), _m([3]), 128) == hs.HS_E_OVERSUBSCRIBED
-    assert hs.hs_admission_check(None, _m([127]), _m([3]), 128) == hs.HS_OK
+    assert hs.hs_admission_check(None, z, _m([1]), 24) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([1]), z, 24) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([24]), _m([3]), 24) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([200]), _m([3]), 24) == hs.HS_E_OVERSUBSCRIBED
+    assert hs.hs_admission_check(None, _m([23]), _m([3]), 24) == hs.HS_OK
     assert hs.hs_admission_check(None, _m([3]), _m([3]), 0) == hs.HS_E_INVAL
     assert "CU" in hs.hs_last_error() or "argument" in hs.hs_last_error()
     # inference and overlay masks of ONE application may overlap each other
     assert hs.hs_admission_check(z, _m(range(0, 32)), _m(range(16, 48)), 256) == hs.HS_OK
+
+
+def test_admission_needs_a_cu_on_every_xcd():
+    """CU i sits on XCD i mod 8 of a 256-CU device (i mod 4 with 128 CUs): a mask that leaves an
+    XCD without a CU is refused with HS_E_INVAL, whichever of the two masks it is; the other
+    rules are judged first."""
+    full = _m(range(0, 8))
+    for hole in range(8):
+        cus = [c for c in range(16, 48) if c % 8 != hole]          # 28 CUs, none on XCD `hole`
+        assert hs.hs_admission_check(None, _m(cus), full, 256) == hs.HS_E_INVAL
+        assert f"XCD {hole}" in hs.hs_last_error() and "inference" in hs.hs_last_error()
+        assert hs.hs_admission_check(None, full, _m(cus), 256) == hs.HS_E_INVAL
+        assert "overlay" in hs.hs_last_error()
+        assert hs.hs_admission_check(None, _m(cus + [hole + 48]), full, 256) == hs.HS_OK
+    # one CU per XCD is the smallest admissible mask; they need not be consecutive
+    assert hs.hs_admission_check(None, _m([0, 9, 18, 27, 36, 45, 54, 63]), full, 256) == hs.HS_OK
+    assert hs.hs_admission_check(None, _m(range(0, 7)), full, 256) == hs.HS_E_INVAL
+    # 128 CUs: four XCDs
+    assert hs.hs_admission_check(None, _m([4, 5, 6, 7]), _m([0, 1, 2, 3]), 128) == hs.HS_OK
+    assert hs.hs_admission_check(None, _m([4, 5, 6]), _m([0, 1, 2, 3]), 128) == hs.HS_E_INVAL
+    # a claimed CU is reported as over-subscription even when the mask is also XCD-incomplete
+    assert hs.hs_admission_check(_m([3]), _m([3]), full, 256) == hs.HS_E_OVERSUBSCRIBED
 
 
 # ---- metrics ---------------------------------------------------------------------------------
