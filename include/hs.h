@@ -245,6 +245,25 @@ hs_status hs_admission_check(const uint32_t* claimed_by_others, const uint32_t* 
  * group when hs_submit_group fails that way. */
 hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overlay_out,
                           uint64_t frame_id);
+/* hs_submit_frame for callers that cannot allocate device memory or let the library touch an
+ * allocator while they run: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same results bit for bit, same status codes; the call
+ * allocates nothing, neither on the device nor (on its success path) on the host.  The one
+ * scratch buffer of the hot path, the fp32 partial sums of the convolutions that are split
+ * along K, is taken from a fixed 8 MiB device array inside the library (one copy per GPU, held
+ * until the process ends) instead of the application's workspace; kernels are always launched
+ * one by one (never as a HIP graph).  The 1920x1080 -> 854x480 network needs 6.6 MB of it.
+ *   HS_E_NOMEM  a frame of this application needs more scratch than the array holds
+ *               (hs_last_error() names both sizes); nothing is enqueued
+ *   HS_E_STATE  batched or grouped application, kernel timing switched on, or a frame of this
+ *               application still in flight (the call takes one frame at a time)
+ * Every call on a GPU shares that GPU's array, which holds whatever the last frame left in it
+ * (every value a frame reads it has written before, so nothing needs clearing).  Frames of
+ * DIFFERENT applications submitted through this call must not be in flight together on one GPU:
+ * they race on the array and the library does not detect it.  Frames submitted through the
+ * other calls are not affected. */
+hs_status hs_submit_frame_static_scratch(hs_app* app, const uint8_t* d_frame,
+                                         uint8_t* d_overlay_out, uint64_t frame_id);
 /* Deliver the oldest finished, not yet delivered frame (submit order). Non-blocking:
  * HS_E_NOT_READY if none has finished. Frees that frame's queue slot. */
 hs_status hs_poll_result(hs_app* app, hs_result* out);

@@ -19,6 +19,7 @@ __all__ = [
     "hs_latency_metrics", "hs_kernel_time", "lib_path", "load", "hs_init", "hs_shutdown",
     "hs_device_cus", "hs_query_workspace", "hs_create_app", "hs_destroy_app", "hs_reset_state",
     "hs_get_state", "hs_get_features", "hs_set_partition", "hs_admission_check", "hs_submit_frame",
+    "hs_submit_frame_static_scratch",
     "hs_poll_result", "hs_wait_result", "hs_submit_batch", "hs_submit_batch_after", "hs_poll_batch",
     "hs_wait_batch",
     "hs_create_group", "hs_destroy_group", "hs_submit_group", "hs_poll_group", "hs_wait_group",
@@ -136,6 +137,8 @@ def load() -> C.CDLL:
         "hs_set_partition": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
         "hs_admission_check": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
         "hs_submit_frame": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
+        "hs_submit_frame_static_scratch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_uint64]),
         "hs_poll_result": (C.c_int, [C.c_void_p, P(hs_result)]),
         "hs_wait_result": (C.c_int, [C.c_void_p, P(hs_result), C.c_uint64]),
         "hs_create_group": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, P(C.c_void_p)]),
@@ -303,6 +306,13 @@ def hs_admission_check(claimed_by_others, req_infer, req_overlay, device_cus: in
 def hs_submit_frame(app: int, d_frame: int, d_overlay_out: int, frame_id: int) -> int:
     """Returns HS_OK or HS_E_QUEUE_FULL; raises on any other status."""
     return _check(load().hs_submit_frame(app, d_frame, d_overlay_out, frame_id),
+                  soft=(HS_E_QUEUE_FULL,))
+
+
+def hs_submit_frame_static_scratch(app: int, d_frame: int, d_overlay_out: int, frame_id: int) -> int:
+    """hs_submit_frame with the split-K scratch in the library's fixed device array (no
+    allocation).  Returns HS_OK or HS_E_QUEUE_FULL; raises on any other status."""
+    return _check(load().hs_submit_frame_static_scratch(app, d_frame, d_overlay_out, frame_id),
                   soft=(HS_E_QUEUE_FULL,))
 
 

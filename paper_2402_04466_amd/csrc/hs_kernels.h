@@ -171,6 +171,13 @@ struct OverlayParams {
 };
 KernelDesc describe(const OverlayParams& p);
 
+// ---- scratch for callers that cannot allocate ---------------------------------------------
+// A fixed device array inside the library (one copy per GPU, held until the process ends) that
+// can stand in for the split-K scratch of an application's workspace.  Returns the array's
+// device address ON THE CURRENT DEVICE and its size; the address is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+hipError_t static_scratch_address(void** d_ptr, size_t* bytes);
+
 // ---- helpers ------------------------------------------------------------------------------
 void launch_fill_zero(void* d, size_t bytes, hipStream_t s);   // bytes multiple of 16
 void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);   // bytes multiple of 16

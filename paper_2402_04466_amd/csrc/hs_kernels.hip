@@ -3,6 +3,7 @@
 #include "hs_kernels.h"
 
 #include <algorithm>
+#include <mutex>
 
 namespace hs {
 
@@ -1723,6 +1724,34 @@ KernelDesc describe(const OverlayParams& p) {
   const unsigned groups = (unsigned)(((p.wf + 15) >> 4) * p.hf);
   const void* f = p.n_layers > 1 ? (const void*)k_overlay<true> : (const void*)k_overlay<false>;
   return KernelDesc{f, dim3((groups + 255) / 256, p.batch), dim3(256), 0};
+}
+
+// ---------------------------------------------------------------------------------------------
+// Split-K scratch for callers that cannot allocate.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: every GPU holds its own copy at its own address, looked up
+// once per device (with that device current) and used as an ordinary device pointer from then
+// on -- the kernels receive it in their parameter blocks like the workspace scratch it replaces.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch_address(void** d_ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static void* ptr_of[kMaxDevices] = {nullptr};
+  static std::mutex mu;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr_of[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    ptr_of[dev] = ptr;
+  }
+  *d_ptr = ptr_of[dev];
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------------------------

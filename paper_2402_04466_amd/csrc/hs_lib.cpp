@@ -117,6 +117,8 @@ constexpr int kMaxLanes = 2;
 struct Slot {
   std::vector<Op> pre;     // stage 1: one launch, blockIdx.y = stream of the batch
   std::vector<Op> infer;   // stage 2: the network over the whole batch
+  std::vector<Op> infer_static;   // the same with the split-K scratch in the library's fixed
+                                  // device array (empty when the scratch needed exceeds it)
   std::vector<Op> post;    // stage 3
   std::vector<Op> overlay; // stage 4: one launch, blockIdx.y = stream of the batch
   hipEvent_t ev_pre = nullptr, ev_infer = nullptr, ev_post = nullptr, ev_overlay = nullptr;
@@ -154,6 +156,8 @@ using namespace hs;
 struct hs_ctx {
   int device = 0;
   int n_cus = 0;
+  void* d_static_scratch = nullptr;   // the library's fixed scratch array on this device
+  size_t static_scratch_bytes = 0;
   std::mutex mu;
   std::vector<hs_app*> apps;
 };
@@ -195,6 +199,7 @@ struct hs_app {
   uint64_t acc_n[F_COUNT] = {0};
   void* pinned = nullptr;
   hs_group* group = nullptr;   // set while the application is a member of a multi-network group
+  size_t partial_bytes = 0;    // split-K scratch one frame needs
 };
 
 // A multi-network application: the members run stages 1-3 on the same frame side by side, one
@@ -272,6 +277,7 @@ struct Builder {
   const float* blob;
   size_t blob_off = 0;
   size_t partial_floats = 0;
+  float* d_partial = nullptr;     // split-K scratch of this lane inside the workspace
   std::vector<Op> ops;            // stage-2 ops; slot-dependent pointers are patched per slot
   int first_conv_op = -1;         // op whose conv.in is the slot's padded net input
   int logits_op = -1;             // op that writes the slot's logits
@@ -752,6 +758,7 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
   b.walk(ph, pw);
   auto bind_partial = [](Builder& bb) {
     float* d_partial = bb.carve.take<float>(bb.partial_floats);
+    bb.d_partial = d_partial;
     for (Op& op : bb.ops) {
       if (op.fam == F_CONV && op.conv.use_partial) {
         op.conv.partial = d_partial;
@@ -900,6 +907,22 @@ static hs_status build_plan(const hs_app_desc* d, hs_app* app, size_t* bytes_out
     if (lo.fam == F_CONV) lo.conv.out_f32 = s.d_logits;
     else if (lo.fam == F_SPLITK) lo.splitk.out_f32 = s.d_logits;
     else lo.lstm.logits = s.d_logits;
+    app->partial_bytes = b.partial_floats * sizeof(float);
+    if (app->partial_bytes <= app->ctx->static_scratch_bytes && app->ctx->d_static_scratch) {
+      // the same launches with every split-K pointer moved from the lane's scratch in the
+      // workspace to the same offset inside the library's fixed array
+      float* const from = lane_b[s.lane]->d_partial;
+      float* const to = (float*)app->ctx->d_static_scratch;
+      auto move = [&](auto*& ptr) {
+        if (ptr) ptr = to + (ptr - from);
+      };
+      s.infer_static = s.infer;
+      for (Op& op : s.infer_static) {
+        if (op.fam == F_CONV) { move(op.conv.partial); move(op.conv.partial2); }
+        if (op.fam == F_SPLITK) { move(op.splitk.partial); move(op.splitk.partial2); }
+        if (op.fam == F_LSTM) move(op.lstm.partial);
+      }
+    }
     {
       Op p;
       p.fam = F_POST;
@@ -1175,9 +1198,15 @@ hs_status hs_init(int device, hs_ctx** out) {
               prop.gcnArchName);
     return HS_E_DEVICE;
   }
+  // the fixed scratch array of this device (for hs_submit_frame_static_scratch)
+  void* d_scratch = nullptr;
+  size_t scratch_bytes = 0;
+  HS_HIP(static_scratch_address(&d_scratch, &scratch_bytes));
   hs_ctx* c = new hs_ctx();
   c->device = device;
   c->n_cus = prop.multiProcessorCount;
+  c->d_static_scratch = d_scratch;
+  c->static_scratch_bytes = scratch_bytes;
   *out = c;
   return HS_OK;
 }
@@ -1464,7 +1493,8 @@ static void finish_submit(hs_app* app, Slot* s) {
 static hs_status enqueue_stages(hs_app* app, Slot* s, bool idle, const uint8_t* const* d_frames,
                                 uint8_t* const* d_overlay_outs, uint64_t frame_id,
                                 uint64_t t_submit, bool own_overlay, Slot** slot_out,
-                                hipStream_t* stream_out, hipEvent_t frames_ready);
+                                hipStream_t* stream_out, hipEvent_t frames_ready,
+                                bool static_scratch);
 
 // A submit that fails after part of a frame has been handed to the GPU leaves the recurrent
 // state advanced by a frame that is never delivered: the application is unusable from then on.
@@ -1479,7 +1509,8 @@ static void poison(hs_app* app, const char* what) {
 static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
                                uint8_t* const* d_overlay_outs, uint64_t frame_id,
                                uint64_t t_submit, bool own_overlay, Slot** slot_out,
-                               hipStream_t* stream_out, hipEvent_t frames_ready = nullptr) {
+                               hipStream_t* stream_out, hipEvent_t frames_ready = nullptr,
+                               bool static_scratch = false) {
   if (!app || !d_frames || !d_overlay_outs) { set_error("hs_submit_batch: NULL argument"); return HS_E_INVAL; }
   const int B = app->batch;
   for (int j = 0; j < B; ++j) {
@@ -1504,9 +1535,15 @@ static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
     }
     s = &app->slots[app->n_submitted % app->depth];
     idle = app->n_completed == app->n_submitted;
+    if (static_scratch && !idle) {
+      // one scratch array serves every frame that uses it: no second frame beside it
+      set_error("hs_submit_frame_static_scratch: a frame of this application is still in flight");
+      return HS_E_STATE;
+    }
   }
   const hs_status st = enqueue_stages(app, s, idle, d_frames, d_overlay_outs, frame_id, t_submit,
-                                      own_overlay, slot_out, stream_out, frames_ready);
+                                      own_overlay, slot_out, stream_out, frames_ready,
+                                      static_scratch);
   if (st != HS_OK) poison(app, hs_last_error());
   return st;
 }
@@ -1514,8 +1551,10 @@ static hs_status submit_stages(hs_app* app, const uint8_t* const* d_frames,
 static hs_status enqueue_stages(hs_app* app, Slot* s, bool idle, const uint8_t* const* d_frames,
                                 uint8_t* const* d_overlay_outs, uint64_t frame_id,
                                 uint64_t t_submit, bool own_overlay, Slot** slot_out,
-                                hipStream_t* stream_out, hipEvent_t frames_ready) {
+                                hipStream_t* stream_out, hipEvent_t frames_ready,
+                                bool static_scratch) {
   HS_HIP(hipSetDevice(app->ctx->device));
+  std::vector<Op>& infer = static_scratch ? s->infer_static : s->infer;
   const int B = app->batch;
   const size_t n_map = (size_t)app->map_w * app->map_h;
   const size_t netin_img = (size_t)app->netin_h * app->netin_w * 4;
@@ -1554,7 +1593,7 @@ static hs_status enqueue_stages(hs_app* app, Slot* s, bool idle, const uint8_t* 
   app->lane_last_stream[s->lane] = lane_stream;
   // the caller's producer (another stream) may still be writing the frames
   if (frames_ready) HS_HIP(hipStreamWaitEvent(lane_stream, frames_ready, 0));
-  if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing) {
+  if (app->launch_mode == HS_LAUNCH_GRAPH && !app->timing && !static_scratch) {
     void* args[1];
     hipKernelNodeParams kp = node_params(s->pre[0], args);
     HS_HIP(hipGraphExecKernelNodeSetParams(s->graph_exec, s->resize_nodes[0], &kp));
@@ -1566,15 +1605,15 @@ static hs_status enqueue_stages(hs_app* app, Slot* s, bool idle, const uint8_t* 
     if (s->wait_idx >= 0) {
       // the recurrent cell waits for the previous frame's state update (other lane)
       Slot& before = app->slots[(size_t)((s - app->slots.data()) + app->depth - 1) % app->depth];
-      st = run_ops(app, s->infer, lane_stream, 0, (size_t)s->wait_idx);
+      st = run_ops(app, infer, lane_stream, 0, (size_t)s->wait_idx);
       if (st != HS_OK) return st;
       if (app->depth > 1) HS_HIP(hipStreamWaitEvent(lane_stream, before.ev_state, 0));
-      st = run_ops(app, s->infer, lane_stream, (size_t)s->wait_idx, (size_t)s->record_idx + 1);
+      st = run_ops(app, infer, lane_stream, (size_t)s->wait_idx, (size_t)s->record_idx + 1);
       if (st != HS_OK) return st;
       HS_HIP(hipEventRecord(s->ev_state, lane_stream));
-      st = run_ops(app, s->infer, lane_stream, (size_t)s->record_idx + 1);
+      st = run_ops(app, infer, lane_stream, (size_t)s->record_idx + 1);
     } else {
-      st = run_ops(app, s->infer, lane_stream);
+      st = run_ops(app, infer, lane_stream);
     }
     if (st != HS_OK) return st;
     HS_HIP(hipEventRecord(s->ev_infer, lane_stream));
@@ -1628,6 +1667,29 @@ hs_status hs_submit_frame(hs_app* app, const uint8_t* d_frame, uint8_t* d_overla
     return HS_E_STATE;
   }
   return hs_submit_batch(app, &d_frame, &d_overlay_out, frame_id);
+}
+
+hs_status hs_submit_frame_static_scratch(hs_app* app, const uint8_t* d_frame,
+                                         uint8_t* d_overlay_out, uint64_t frame_id) {
+  const uint64_t t_submit = now_ns();
+  if (!app) { set_error("hs_submit_frame_static_scratch: NULL argument"); return HS_E_INVAL; }
+  if (refuse_grouped(app, "hs_submit_frame_static_scratch") != HS_OK) return HS_E_STATE;
+  if (app->batch != 1) {
+    set_error("hs_submit_frame_static_scratch: the application batches %d streams", app->batch);
+    return HS_E_STATE;
+  }
+  if (app->timing) {   // per-kernel timing creates events, i.e. allocates
+    set_error("hs_submit_frame_static_scratch: kernel timing is on");
+    return HS_E_STATE;
+  }
+  if (app->slots[0].infer_static.empty()) {
+    set_error("hs_submit_frame_static_scratch: a frame of this application needs %zu bytes of "
+              "split-K scratch, the library's fixed array holds %zu", app->partial_bytes,
+              app->ctx->static_scratch_bytes);
+    return HS_E_NOMEM;
+  }
+  return submit_stages(app, &d_frame, &d_overlay_out, frame_id, t_submit, true, nullptr, nullptr,
+                       nullptr, true);
 }
 
 // Copies the oldest finished batch's results (one per stream) out and frees its slot.
