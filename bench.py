@@ -1,20 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the per-frame tool-tracking hot path on one MI355X.
 
-A step is one frame through all four stages (format conversion + resize, ResNet-18-style
-backbone + ConvLSTM + head on fp16 MFMA, postprocess, overlay) of one application stream.
-Default workload: one stream of 1920x1080 frames resized to 854x480 (the configuration
-the headline metric is quoted on).  Frames are synthetic and already resident in HBM when
-the timed region starts.
+A step is one pass of all four stages (format conversion + resize, ResNet-18-style backbone +
+ConvLSTM + head on fp16 MFMA, postprocess, overlay) over one batch of input: one 1920x1080
+frame of every stream the workload serves.  Frames are synthetic and already resident in HBM
+when the timed region starts.
 
-Prints ONE JSON line: aggregate frames/s over the timed steps, the per-frame end-to-end
-latency determinism metrics of a paced (fixed frame-rate) run, the roofline of the
-dominant kernel measured with HIP events on its own stream, and the CPU oracle timed on
-the host cores of this machine.
+Without workload flags the run covers the benchmark's configurations in one process and prints
+ONE JSON line:
+  * headline (`value`, `config`, `latency_ms`, `roofline`, `kernels`): twelve concurrent 1080p
+    streams at 30 frames per second each, batched across streams through one pass of the network
+    (the largest single-GPU configuration);
+  * `configs`: short runs of the other configurations -- one stream; five unpartitioned
+    applications at 60 frames per second; six applications unpartitioned, on six CU partitions
+    with inference and overlay on separate CU sets, on six partitions with one queue each, and
+    re-shaped into three applications of two streams on three partitions -- each with frames/s
+    and the latency determinism metrics (paper Section V-A); the six-stream arrangements carry
+    their maximum and median against the unpartitioned run's and the Mann-Whitney z of the two
+    latency samples (paper, appendix "Additional Evaluation");
+  * `cpu_baseline`: the CPU oracle timed on this machine's host cores.
+With workload flags (--streams, --batch, --partition, ...) it measures that one workload.
 """
 from __future__ import annotations
 
 import argparse
+import copy
 import json
 import os
 import sys
@@ -27,18 +37,27 @@ if ROOT not in sys.path:
 
 PEAK_FP16_TFLOPS = 2500.0   # MI355X dense fp16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+FW, FH, NW, NH = 1920, 1080, 854, 480
+
+WORKLOAD_FLAGS = ("--streams", "--batch", "--partition", "--partition-groups", "--tiny-groups",
+                  "--hog", "--tiny-apps", "--group-nets", "--per-stream-submit", "--annotate",
+                  "--fps", "--first-seed")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 100 batches of the headline workload, 240 frames "
+                         "of a workload given by flags)")
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--streams", type=int, default=1, help="concurrent application streams")
+    ap.add_argument("--streams", type=int, default=1, help="concurrent applications")
     ap.add_argument("--batch", type=int, default=1,
                     help="streams per application, batched through the network together "
                          "(--streams counts applications; 12 with --fps 30 is the saturation case)")
     ap.add_argument("--fps", type=float, default=60.0, help="pacing of the latency run")
+    ap.add_argument("--first-seed", type=int, default=None,
+                    help="scene seed of the first stream (default: 1 for a single stream, else 2)")
     ap.add_argument("--partition", choices=["none", "equal", "equal-shared"], default="none",
                     help="equal: disjoint CU-masked partitions, inference and overlay on separate "
                          "CU sets and queues; equal-shared: one CU set and one queue per "
@@ -77,10 +96,13 @@ def parse():
                          "its own thread (hs_mux); latency then counts from the stream's own "
                          "arrival and includes the wait for the rest of the batch")
     ap.add_argument("--paced-frames", type=int, default=60)
-    ap.add_argument("--repeats", type=int, default=3,
+    ap.add_argument("--repeats", type=int, default=None,
                     help="repeat the paced latency run this many times (state reset in between) "
-                         "and pool the trimmed latencies, as the paper pools its repeated runs")
-    ap.add_argument("--distinct-frames", type=int, default=8)
+                         "and pool the trimmed latencies, as the paper pools its repeated runs "
+                         "(default 3; 2 per configuration in the run over all configurations)")
+    ap.add_argument("--distinct-frames", type=int, default=None,
+                    help="distinct frames per stream, cycled (default 8; 4 and 2 in the run over "
+                         "all configurations)")
     ap.add_argument("--queue-depth", type=int, default=4)
     ap.add_argument("--launch-mode", choices=["graph", "eager"], default="eager",
                     help="stages 1-3 kernel by kernel (the library's default: lowest latency), "
@@ -89,8 +111,10 @@ def parse():
                     help="first run the library's plain copy kernel 4 times over this many MiB "
                          "(reference dispatches for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=21,
-                    help="frames of the CPU oracle sample (the first is untimed): about 12 s of CPU work")
+    ap.add_argument("--cpu-frames", type=int, default=16,
+                    help="frames of the all-core CPU oracle sample (one more, untimed, first)")
+    ap.add_argument("--cpu-frames-1thread", type=int, default=2,
+                    help="frames of the single-thread CPU oracle sample")
     return ap.parse_args()
 
 
@@ -112,35 +136,40 @@ def equal_partitions(n_cus: int, n_streams: int, overlay_groups: int = 1, spare_
     return parts
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this library has no multi-GPU path (streams would "
-              "shard one application per GPU with no communication); run with --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-    import paper_2402_04466_amd as hs
+class Env:
+    """What every measured workload shares: the library context, the weight blob and a cache
+    of generated scenes (so that arrangements of the same streams reuse their frames)."""
+
+    def __init__(self):
+        import numpy as np
+        import torch
+        import paper_2402_04466_amd as hs
+        import synth_inputs as si
+        self.np, self.torch, self.hs, self.si = np, torch, hs, si
+        self.ctx = hs.hs_init(0)
+        self.n_cus = hs.hs_device_cus(self.ctx)
+        self.blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+        self._scenes = {}
+
+    def scene(self, seed: int, n: int):
+        key = (seed, n)
+        if key not in self._scenes:
+            self._scenes[key] = list(self.si.tool_scene_frames(n, FH, FW, seed))
+        return self._scenes[key]
+
+
+def measure(args, env: Env, want_roofline: bool = True, note=lambda s: None) -> dict:
+    """One workload: throughput back to back, latency determinism at the paced rate, per-kernel
+    timing of its first application.  Creates and destroys its applications."""
+    hs, np, torch, si, ctx, n_cus = env.hs, env.np, env.torch, env.si, env.ctx, env.n_cus
     from paper_2402_04466_amd.harness import AppStream, GroupStream, run_paced
     from paper_2402_04466_amd.harness import run_back_to_back as harness_back_to_back
-    import synth_inputs as si
-
-    FW, FH, NW, NH = 1920, 1080, 854, 480
-    ctx = hs.hs_init(0)
-    n_cus = hs.hs_device_cus(ctx)
-    if args.calibrate_copy:
-        nbytes = args.calibrate_copy << 20
-        a = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        for _ in range(4):
-            hs.hs_device_copy(ctx, b.data_ptr(), a.data_ptr(), nbytes)
-        del a, b
-    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    blob = env.blob
     grouped = args.group_nets > 1
     if grouped and args.batch != 1:
         raise SystemExit("--group-nets needs --batch 1")
+    first_seed = args.first_seed if args.first_seed is not None else \
+        (1 if args.streams * args.batch == 1 else 2)
 
     def apps_of(s):
         """The library applications behind one benchmark stream."""
@@ -163,9 +192,8 @@ def main():
         streams.append(s)
         per_stream = []
         for j in range(args.batch):
-            seed = 1 if args.streams * args.batch == 1 else 2 + i * args.batch + j
-            per_stream.append([s.upload_frame(f) for f in
-                               si.tool_scene_frames(args.distinct_frames, FH, FW, seed)])
+            seed = first_seed + i * args.batch + j
+            per_stream.append([s.upload_frame(f) for f in env.scene(seed, args.distinct_frames)])
         # frames[i][k] = what is submitted as frame k of application i (one tensor per stream)
         frames.append([[per_stream[j][k] for j in range(args.batch)]
                        for k in range(args.distinct_frames)])
@@ -175,7 +203,7 @@ def main():
                       net_h=NH, blob=blob, palette=si.DEFAULT_PALETTE,
                       queue_depth=args.queue_depth, batch=1)
         hogs.append(s)
-        hog_frames.append([s.upload_frame(f) for f in si.tool_scene_frames(2, FH, FW, 100 + i)])
+        hog_frames.append([s.upload_frame(f) for f in env.scene(100 + i, 2)])
         hog_outs.append([s.new_output() for _ in range(args.queue_depth)])
     tiny, tiny_frames, tiny_outs = [], [], []
     if args.tiny_apps:
@@ -229,11 +257,13 @@ def main():
         torch.cuda.synchronize()
         return elapsed
 
-    # ---- throughput: W warm-up steps, then exactly K timed steps per stream ---------------
-    run_back_to_back(args.warmup)
+    # ---- throughput: W warm-up steps, then exactly K timed steps per application -------------
+    if args.warmup > 0:
+        run_back_to_back(args.warmup)
     elapsed = run_back_to_back(args.steps)
     total_frames = args.steps * args.streams * args.batch
     fps = total_frames / elapsed
+    note("throughput done")
 
     # ---- latency determinism at a fixed frame rate (paper Section V-A metrics) -------------
     for s in streams:
@@ -283,8 +313,7 @@ def main():
                                         outs + tiny_outs, pin_cpus=pins,
                                         n_frames=args.paced_frames, with_lateness=True,
                                         muxes=muxes + [None] * len(tiny) if muxes else None)
-        print(f"[bench] paced run {rep + 1} of {max(1, args.repeats)} done", file=sys.stderr,
-              flush=True)
+        note(f"paced run {rep + 1} of {max(1, args.repeats)} done")
         lateness_us.extend(v / 1e3 for per in late for v in per)
         dropped.extend(drop)
         tiny_results, results = res_all[len(streams):], res_all[:len(streams)]
@@ -341,52 +370,59 @@ def main():
     worst_ms = {k: round(v, 4) for k, v in worst_ms.items()}
     worst_ms["repeat"], worst_ms["frame"] = w_rep, w_k
 
-    # ---- roofline of the dominant kernel: HIP events around every launch -------------------
+    # ---- roofline of the dominant kernel: HIP events attached to every launch ----------------
     s0 = streams[0]
     app0 = apps_of(s0)[0]     # a group: its first network (and the shared overlay launch)
-    # the paced run leaves the GPU idle most of the time and its clocks low: a short back-to-back
-    # burst brings them back up before the per-launch timing (untimed, results discarded)
-    harness_back_to_back(streams[:1], frames[:1], outs[:1], 60)
-    hs.hs_set_kernel_timing(app0, True)
-    n_prof = 40
-    for k in range(n_prof):
-        assert s0.submit_batch(frames[0][k % len(frames[0])], outs[0][k % len(outs[0])],
-                               k) == hs.HS_OK
-        s0.wait_batch()
-    kt = hs.hs_get_kernel_times(app0)
-    hs.hs_set_kernel_timing(app0, False)
-    dom = max(kt, key=lambda e: e["total_ms"])
-    if dom["flops"] > 0:
-        ach = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_FP16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(ach / PEAK_FP16_TFLOPS, 4), "traffic": None}
-    else:
-        ach = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
-    # HBM bytes per launch from committed rocprofv3 counter runs, valid only for the kernel
-    # source they were taken with
-    try:
-        from paper_2402_04466_amd.pmc_traffic import kernel_source_hash
-        tag = "config2_1stream" if args.streams * args.batch == 1 else f"batch{args.batch}"
-        with open(os.path.join(ROOT, "profiles", f"conv_traffic_{tag}.json")) as fh:
-            tr = json.load(fh)
-        if tr["kernel_source_sha256"] == kernel_source_hash() and dom["name"] == "conv_mfma":
-            roof["traffic"] = round(tr["conv_hbm_bytes_per_launch"]["total"])
-    except (OSError, KeyError, ValueError):
-        pass
-    roof["kernel"] = dom["name"]
-    roof["avg_launch_us"] = round(dom["total_ms"] * 1e3 / dom["launches"], 2)
-    roof["launches_per_frame"] = dom["launches"] // n_prof
-    kernels = {}
-    for e in kt:
-        d = {"us_per_frame": round(e["total_ms"] * 1e3 / n_prof, 2),
-             "launches_per_frame": e["launches"] // n_prof}
-        if e["flops"] > 0:
-            d["TFLOP/s"] = round(e["flops"] / (e["total_ms"] * 1e-3) / 1e12, 2)
-        if e["bytes"] > 0:
-            d["GB/s"] = round(e["bytes"] / (e["total_ms"] * 1e-3) / 1e9, 1)
-        kernels[e["name"]] = d
+    roof, kernels, kt = None, {}, []
+    if want_roofline:
+        # the paced run leaves the GPU idle most of the time and its clocks low: a short
+        # back-to-back burst brings them back up before the per-launch timing (untimed)
+        harness_back_to_back(streams[:1], frames[:1], outs[:1], 60)
+        hs.hs_set_kernel_timing(app0, True)
+        n_prof = 40
+        for k in range(n_prof):
+            assert s0.submit_batch(frames[0][k % len(frames[0])], outs[0][k % len(outs[0])],
+                                   k) == hs.HS_OK
+            s0.wait_batch()
+        kt = hs.hs_get_kernel_times(app0)
+        hs.hs_set_kernel_timing(app0, False)
+        dom = max(kt, key=lambda e: e["total_ms"])
+        if dom["flops"] > 0:
+            ach = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
+            roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_FP16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / PEAK_FP16_TFLOPS, 4), "traffic": None}
+        else:
+            ach = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
+            roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+        # HBM bytes per launch: not measured in this run.  They come from committed rocprofv3
+        # counter runs and are given only while the kernel sources still hash to what those
+        # runs recorded.
+        roof["traffic_source"] = None
+        try:
+            from paper_2402_04466_amd.pmc_traffic import kernel_source_hash
+            tag = "config2_1stream" if args.streams * args.batch == 1 else f"batch{args.batch}"
+            rel = os.path.join("profiles", f"conv_traffic_{tag}.json")
+            with open(os.path.join(ROOT, rel)) as fh:
+                tr = json.load(fh)
+            if tr["kernel_source_sha256"] == kernel_source_hash() and dom["name"] == "conv_mfma":
+                roof["traffic"] = round(tr["conv_hbm_bytes_per_launch"]["total"])
+                roof["traffic_source"] = rel + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an " \
+                                               "earlier run of this kernel source, not this run)"
+        except (OSError, KeyError, ValueError):
+            pass
+        roof["kernel"] = dom["name"]
+        roof["avg_launch_us"] = round(dom["total_ms"] * 1e3 / dom["launches"], 2)
+        roof["launches_per_step"] = dom["launches"] // n_prof
+        roof["frames_per_launch"] = args.batch
+        for e in kt:
+            d = {"us_per_step": round(e["total_ms"] * 1e3 / n_prof, 2),
+                 "launches_per_step": e["launches"] // n_prof}
+            if e["flops"] > 0:
+                d["TFLOP/s"] = round(e["flops"] / (e["total_ms"] * 1e-3) / 1e12, 2)
+            if e["bytes"] > 0:
+                d["GB/s"] = round(e["bytes"] / (e["total_ms"] * 1e-3) / 1e9, 1)
+            kernels[e["name"]] = d
 
     # what the first application's share of the device can pull and compute: a plain copy of the
     # overlay's shape under the same CU mask, and the fp16 MFMA peak of its CUs
@@ -414,48 +450,29 @@ def main():
             part["conv_peak_of_its_cus_TFLOP/s"] = round(peak, 1)
             part["conv_frac_of_its_cus"] = round(ach / peak, 4)
         del src, dst
+    hog_rate = round(sum(hog_count) / t_hog, 1) if hogs else None
     for s in streams + tiny + hogs:
         s.close()
-    hs.hs_shutdown(ctx)
 
-    # ---- the CPU oracle on the host cores, bounded sample --------------------------------
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        app = oracle.OracleApp("resnet18_convlstm", blob, NW, NH, True, si.DEFAULT_PALETTE)
-        fr = list(si.tool_scene_frames(args.cpu_frames, FH, FW, 1))
-        app.process(fr[0])                       # first call pays one-time page-in costs
-        t0 = time.perf_counter()
-        for f in fr[1:]:
-            app.process(f)
-        dt = time.perf_counter() - t0
-        cpu = {"value": round((len(fr) - 1) / dt, 4), "unit": "frames/s", "cores": int(cores),
-               "kind": "oracle",
-               "sample": f"{len(fr) - 1} frames of the same 1080p workload, one stream, all "
-                         "four stages, NumPy float64 (BLAS threads = cores)"}
-
-    line = {
-        "metric": "aggregate frames/s + p50/max per-frame latency at N concurrent streams, 1 GPU",
-        "value": round(fps, 2), "unit": "frames/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(1e3 * elapsed / args.steps, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
-        "data": "synthetic",
-        "config": {"workload": f"{args.streams * args.batch} stream(s) x 1920x1080 RGB uint8 -> 854x480 fp16, "
+    n_streams = args.streams * args.batch
+    return {
+        "value": round(fps, 2), "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * elapsed / args.steps, 4),
+        "config": {"workload": f"{n_streams} stream(s) x 1920x1080 RGB uint8 -> 854x480 fp16, "
                                "ResNet-18-style + ConvLSTM(256) + 8-ch head, sigmoid/threshold/"
                                "argmax, alpha-blend overlay on the 1080p frame"
+                               + (f"; {args.batch} streams batched through one pass of the network "
+                                  "per application" if args.batch > 1 else "")
                                + (f"; {args.group_nets} such networks per stream, one overlay "
                                   "launch for their layers" if grouped else ""),
-                   "streams": args.streams, "batch": args.batch, "group_nets": args.group_nets,
-                   "per_stream_submit": bool(muxes),
-                   "partition": args.partition,
-                   "partition_groups": args.partition_groups,
+                   "streams": n_streams, "applications": args.streams, "batch": args.batch,
+                   "group_nets": args.group_nets, "paced_fps": args.fps,
+                   "first_seed": first_seed, "per_stream_submit": bool(muxes),
+                   "partition": args.partition, "partition_groups": args.partition_groups,
                    "queue_depth": args.queue_depth, "launch_mode": args.launch_mode,
-                   "hog_apps": args.hog, "tiny_apps": args.tiny_apps, "tiny_groups": args.tiny_groups, "annotate": bool(args.annotate), "device_cus": n_cus},
+                   "hog_apps": args.hog, "tiny_apps": args.tiny_apps,
+                   "tiny_groups": args.tiny_groups, "annotate": bool(args.annotate),
+                   "device_cus": n_cus},
         "latency_ms": {"paced_fps": args.fps, "frames": int(m["n"]), "repeats": max(1, args.repeats),
                        "p50": round(m["p50"], 4), "p99": round(m["p99"], 4),
                        "p999": round(float(np.percentile(lat_ms, 99.9)), 4),
@@ -469,12 +486,181 @@ def main():
                        "per_stream_p50": per_stream_p50,
                        "mann_whitney": mwu, "pinned_cpus": bool(args.pin_cpus),
                        "tiny_apps": tiny_m,
-                       "hog_frames_per_s": round(sum(hog_count) / t_hog, 1) if hogs else None},
+                       "hog_frames_per_s": hog_rate},
         "roofline": roof,
         "partition_share": part,
         "kernels": kernels,
+        "_lat_ms": lat_ms,
+    }
+
+
+def cpu_baseline(args, env: Env) -> dict:
+    """The CPU oracle as it stands on this machine's host cores: all four stages of one 1080p
+    stream, with every core the BLAS library takes, and on a single thread."""
+    import oracle
+    si = env.si
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threadpool_limits = None
+        cores = os.cpu_count() or 1
+    app = oracle.OracleApp("resnet18_convlstm", env.blob, NW, NH, True, si.DEFAULT_PALETTE)
+    fr = list(si.tool_scene_frames(args.cpu_frames + 1, FH, FW, 1))
+    app.process(fr[0])                       # first call pays one-time page-in costs
+    t0 = time.perf_counter()
+    for f in fr[1:]:
+        app.process(f)
+    dt = time.perf_counter() - t0
+    cpu = {"value": round((len(fr) - 1) / dt, 4), "unit": "frames/s", "cores": int(cores),
+           "kind": "oracle",
+           "sample": f"{len(fr) - 1} frames of one 1080p stream of the same workload, all four "
+                     "stages, NumPy float64; `cores` = BLAS threads (the integer stages run on "
+                     "one)"}
+    if threadpool_limits is not None and args.cpu_frames_1thread > 0:
+        with threadpool_limits(limits=1):
+            n1 = min(args.cpu_frames_1thread, len(fr) - 1)
+            t0 = time.perf_counter()
+            for f in fr[1:1 + n1]:
+                app.process(f)
+            dt1 = time.perf_counter() - t0
+        cpu["single_thread"] = {"value": round(n1 / dt1, 4), "unit": "frames/s", "cores": 1,
+                                "sample": f"{n1} frames of the same stream, BLAS limited to one "
+                                          "thread"}
+        cpu["one_stream_per_core_estimate"] = {
+            "value": round(n1 / dt1 * (os.cpu_count() or 1), 3), "unit": "frames/s",
+            "cores": os.cpu_count() or 1,
+            "sample": "single-thread rate x host cores (streams are independent); not run"}
+    return cpu
+
+
+def summary(name: str, res: dict) -> dict:
+    """The short form of a measured workload for the `configs` array."""
+    lat = res["latency_ms"]
+    out = {"name": name, "workload": res["config"]["workload"],
+           "applications": res["config"]["applications"], "batch": res["config"]["batch"],
+           "partition": res["config"]["partition"],
+           "partition_groups": res["config"]["partition_groups"],
+           "first_seed": res["config"]["first_seed"],
+           "frames_per_s": res["value"], "steps": res["steps"], "ms_per_step": res["ms_per_step"],
+           "latency_ms": {k: lat[k] for k in ("paced_fps", "frames", "repeats", "p50", "p99", "max",
+                                              "mean", "std", "tail", "flatness", "dropped",
+                                              "above_2x_p50")}}
+    if res["partition_share"]:
+        out["partition_share"] = res["partition_share"]
+    if res["kernels"]:
+        out["kernels"] = res["kernels"]
+        out["roofline"] = res["roofline"]
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this library has no multi-GPU path (streams would "
+              "shard one application per GPU with no communication); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    custom = any(a.split("=")[0] in WORKLOAD_FLAGS for a in sys.argv[1:])
+    env = Env()
+    hs, torch = env.hs, env.torch
+
+    def note(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    if args.calibrate_copy:
+        nbytes = args.calibrate_copy << 20
+        a = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            hs.hs_device_copy(env.ctx, b.data_ptr(), a.data_ptr(), nbytes)
+        del a, b
+
+    configs = None
+    if custom:
+        if args.steps is None:
+            args.steps = 240
+        if args.repeats is None:
+            args.repeats = 3
+        if args.distinct_frames is None:
+            args.distinct_frames = 8
+        head = measure(args, env, note=note)
+    else:
+        def variant(**kw):
+            v = copy.copy(args)
+            v.repeats = args.repeats if args.repeats is not None else 2
+            v.distinct_frames = args.distinct_frames if args.distinct_frames is not None else 2
+            for k, val in kw.items():
+                setattr(v, k, val)
+            return v
+
+        # headline: configuration 5, twelve streams batched, 30 frames per second each
+        h = variant(streams=1, batch=12, fps=30.0, first_seed=13,
+                    steps=args.steps if args.steps is not None else 100,
+                    distinct_frames=args.distinct_frames if args.distinct_frames is not None else 4)
+        note("configuration 5: 12 streams batched, 30 fps")
+        head = measure(h, env, note=note)
+        torch.cuda.empty_cache()
+        # the other configurations, short: 120 frames per application back to back, then the
+        # paced run.  Arrangements of configuration 4 share seeds 7-12.
+        plan = [
+            ("config 2: 1 stream, 60 fps", dict(streams=1, batch=1, first_seed=1, steps=240)),
+            ("config 3: 5 applications, 60 fps each, unpartitioned",
+             dict(streams=5, batch=1, first_seed=2, steps=120)),
+            ("config 4: 6 applications, 60 fps each, unpartitioned (the reference run)",
+             dict(streams=6, batch=1, first_seed=7, steps=120)),
+            ("config 4 as stated: 6 applications on 6 equal CU partitions, inference (32 CUs) and "
+             "overlay (8 CUs) on separate CU sets and queues",
+             dict(streams=6, batch=1, first_seed=7, steps=120, partition="equal")),
+            ("config 4, one queue per partition: 6 applications on 6 equal CU partitions of 40 CUs",
+             dict(streams=6, batch=1, first_seed=7, steps=120, partition="equal-shared")),
+            ("config 4 re-shaped: 3 applications x 2 streams batched, on 3 CU partitions of 80 CUs "
+             "(at most four hardware queues in use)",
+             dict(streams=3, batch=2, first_seed=7, steps=120, partition="equal-shared")),
+        ]
+        configs, ref = [], None
+        for name, kw in plan:
+            note(name)
+            res = measure(variant(**kw), env, want_roofline=kw.get("streams") == 1, note=note)
+            torch.cuda.empty_cache()
+            entry = summary(name, res)
+            if name.startswith("config 4"):
+                if ref is None:
+                    ref = res
+                else:
+                    z = hs.hs_mann_whitney_u(res["_lat_ms"], ref["_lat_ms"])
+                    rl, l = ref["latency_ms"], res["latency_ms"]
+                    entry["vs_unpartitioned"] = {
+                        "max_ratio": round(l["max"] / rl["max"], 3),
+                        "p50_ratio": round(l["p50"] / rl["p50"], 3),
+                        "std_ratio": round(l["std"] / max(rl["std"], 1e-9), 3),
+                        "flatness_ratio": round(l["flatness"] / max(rl["flatness"], 1e-9), 3),
+                        "max_below_unpartitioned": bool(l["max"] < rl["max"]),
+                        "mann_whitney_z": round(z["z"], 2), "significant": bool(z["significant"])}
+            configs.append(entry)
+    hs.hs_shutdown(env.ctx)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        note("CPU oracle")
+        cpu = cpu_baseline(args, env)
+
+    line = {
+        "metric": "aggregate frames/s + p50/max per-frame latency at N concurrent streams, 1 GPU",
+        "value": head["value"], "unit": "frames/s", "n_gpus": 1, "steps": head["steps"],
+        "warmup": head["warmup"], "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": head["config"],
+        "latency_ms": head["latency_ms"],
+        "roofline": head["roofline"],
+        "partition_share": head["partition_share"],
+        "kernels": head["kernels"],
         "cpu_baseline": cpu,
     }
+    if configs is not None:
+        line["configs"] = configs
     print(json.dumps(line))
 
 

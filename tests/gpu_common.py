@@ -9,9 +9,17 @@ import synth_inputs as si
 
 TOL_NET = 2e-2        # fp16 GPU vs fp32 oracle, max |diff| / max |ref| per output tensor
 TOL_CELL = 2e-3       # one ConvLSTM step / head on identical fp16 inputs: fp32-accumulate vs fp64
+TOL_EMU = 1.2e-2      # logits: fp16 GPU vs the oracle's fp16-storage emulation (both round every
+                      # stored tensor to half precision, at decorrelated places: the distance
+                      # is that of two independent roundings, not zero)
 TOL_STATE_RMS = 2e-2  # end-to-end recurrent state: rms(diff) / rms(ref)
-TOL_STATE_MAX = 0.15  # end-to-end recurrent state: max |diff| / max |ref| (gates near zero
-                      # amplify the fp16 storage noise of the 20 layers before them)
+# End-to-end recurrent state, max |diff| / max |ref|, per network input size: gates near zero
+# amplify the fp16 storage noise of the 20 layers before them.  Each bound is at most 1.5 times
+# the distance between the oracle's own fp16-storage and fp32 modes over the first four frames
+# of the same stream, which a CPU test measures (tests/test_oracle_convnet.py: 6.8e-2 and
+# 8.5e-2).  It is the maximum over 10^5 values of a heavy-tailed error, so two implementations
+# that round at different places differ in it by tens of per cent.
+TOL_STATE_MAX = {"288x160": 0.10, "854x480": 0.125}
 
 
 def rms_rel(a, ref):
@@ -27,8 +35,11 @@ def rel_err(a, ref):
 
 
 def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, threshold, alpha,
-                palette, fp32_input, mean=0.5, std=0.25, tag="", glyphs=None, marker=(12, 1, 2)):
-    """g: GPU outputs of one frame; o32 / o16: oracle outputs (fp32 storage / fp16 emulation)."""
+                palette, fp32_input, mean=0.5, std=0.25, tag="", glyphs=None, marker=(12, 1, 2),
+                tol_net=TOL_NET):
+    """g: GPU outputs of one frame; o32 / o16: oracle outputs (fp32 storage / fp16 emulation).
+    tol_net: max-norm bound on the logits against the fp32 oracle (the nominal 2e-2 unless the
+    caller has a reason, stated where it passes another)."""
     # ---- stage 1: bit-exact -------------------------------------------------------------
     lut16 = oracle.normalize_lut(mean, std, fp16=True)
     want = lut16[o32["resized"]]                                   # (H, W, 3) float32 of fp16
@@ -41,10 +52,15 @@ def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, thre
         assert np.array_equal(g["net_input_f32"], want32), f"{tag}: stage-1 fp32 tensor differs"
     # ---- stage 2: tolerance --------------------------------------------------------------
     e32 = rel_err(g["logits"], o32["logits"])
-    assert e32 <= TOL_NET, f"{tag}: logits vs fp32 oracle {e32:.3e}"
+    assert e32 <= tol_net, f"{tag}: logits vs fp32 oracle {e32:.3e} (bound {tol_net:.3e})"
+    r32 = rms_rel(g["logits"], o32["logits"])
+    assert r32 <= TOL_NET, f"{tag}: logits vs fp32 oracle, rms {r32:.3e}"
+    print(f"[{tag}] logits vs fp32 oracle: max-norm {e32:.2e} (bound {tol_net:.2e}), rms {r32:.2e}",
+          flush=True)
     if o16 is not None:
         e16 = rel_err(g["logits"], o16["logits"])
-        assert e16 <= TOL_NET, f"{tag}: logits vs fp16-emulating oracle {e16:.3e}"
+        print(f"[{tag}] logits vs fp16-storage emulation: max-norm {e16:.2e}", flush=True)
+        assert e16 <= TOL_EMU, f"{tag}: logits vs fp16-emulating oracle {e16:.3e}"
     # ---- stage 3, stage-isolated: the oracle's postprocess on the GPU's own logits ---------
     p = oracle.postprocess(g["logits"], threshold)
     assert np.array_equal(g["mask"], p["mask"]), f"{tag}: mask differs"
@@ -54,7 +70,7 @@ def check_frame(g: dict, frame: np.ndarray, o32: dict, o16: dict | None, *, thre
     assert np.abs(g["peak"] - p["peak"]).max() <= 1e-6, f"{tag}: peak differs"
     # end to end: mask / argmax may differ from the fp32 oracle only inside the tolerance band
     theta = float(oracle.logit_threshold(threshold))
-    band = TOL_NET * np.abs(o32["logits"]).max()
+    band = tol_net * np.abs(o32["logits"]).max()
     bad = (g["mask"] != o32["mask"]) & (np.abs(o32["logits"] - theta) > band)
     assert not bad.any(), f"{tag}: {int(bad.sum())} mask cells differ outside the band"
     ref = o32["logits"].reshape(8, -1)

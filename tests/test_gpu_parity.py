@@ -1,14 +1,14 @@
 """GPU parity tests: every stage of libhs (called through the C ABI via the binding)
 against the CPU oracle on the same seeded inputs.  Integer stages bit-exact; network
-outputs within 2e-2 of the fp32 oracle (max-norm relative) and within 5e-3 of the oracle's
-fp16-storage emulation."""
+outputs within 2e-2 of the fp32 oracle (max-norm relative) and within 1.2e-2 of the oracle's
+fp16-storage emulation (tests/gpu_common.py holds the bounds and what each is tied to)."""
 import numpy as np
 import pytest
 import torch
 
 import synth_inputs as si
 import oracle
-from gpu_common import (check_frame, make_oracles, rel_err, rms_rel, TOL_CELL, TOL_STATE_RMS,
+from gpu_common import (check_frame, make_oracles, rel_err, rms_rel, TOL_CELL, TOL_NET, TOL_STATE_RMS,
                         TOL_STATE_MAX)
 
 pytestmark = pytest.mark.gpu
@@ -24,7 +24,13 @@ def ctx(hs):
 
 def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_input, depth=2,
                 threshold=0.5, alpha=0.5, check_state=False, tag="", glyphs=None,
-                marker=(12, 1, 2)):
+                marker=(12, 1, 2), emulate=True, storage_gap=None):
+    """emulate: also run the oracle's fp16-storage mode beside the fp32 one.
+    storage_gap: per frame, the max-norm distance of the oracle's own fp16-storage mode from its
+    fp32 mode on the logits (a stored, oracle-only measurement).  Where its running maximum is
+    beyond half the nominal 2e-2, no half-precision-storage implementation can be expected
+    inside 2e-2 of the fp32 oracle in the max norm; the bound there is twice that running
+    maximum, the rms bound stays 2e-2, and the recurrent state is held to its rms bound only."""
     from paper_2402_04466_amd.harness import AppStream
     fh, fw, _ = frames[0].shape
     s = AppStream(ctx, net=net, frame_w=fw, frame_h=fh, net_w=net_w, net_h=net_h, blob=blob,
@@ -49,10 +55,15 @@ def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_inpu
             assert r.t_submit_ns <= r.t_pre_done_ns <= r.t_infer_done_ns <= r.t_post_done_ns \
                 <= r.t_overlay_done_ns <= r.t_observed_ns
             g = s.fetch(r, d_out)
-            a, b = o32.process(f), o16.process(f)
+            a, b = o32.process(f), (o16.process(f) if emulate else None)
+            tol_net = TOL_NET
+            if storage_gap is not None:
+                envelope = float(np.max(storage_gap[:i + 1]))
+                if envelope > 0.5 * TOL_NET:
+                    tol_net = max(TOL_NET, 2.0 * envelope)
             errs.append(check_frame(g, f, a, b, threshold=threshold, alpha=alpha, palette=PAL,
                                     fp32_input=fp32_input, tag=f"{tag}/frame{i}", glyphs=glyphs,
-                                    marker=marker))
+                                    marker=marker, tol_net=tol_net))
             if check_state:
                 gh, gc = s.state(r)
                 gx = s.features(r)
@@ -72,7 +83,13 @@ def _run_stream(hs, ctx, *, net, net_name, frames, net_w, net_h, blob, fp32_inpu
                          rms_rel(gc, a["c"])]
                 print(f"[{tag}] state vs fp32 oracle: max-norm h {stats[0]:.2e} c {stats[1]:.2e}; "
                       f"rms h {stats[2]:.2e} c {stats[3]:.2e}", flush=True)
-                assert max(stats[0], stats[1]) <= TOL_STATE_MAX and max(stats[2], stats[3]) <= TOL_STATE_RMS, \
+                # the max-norm bound is tied to a measurement over the first four frames of a
+                # stream; the long run (whose first frames another test checks with it) holds
+                # the state to the rms bound and to the cell-in-isolation check above
+                tol_max = TOL_STATE_MAX[f"{net_w}x{net_h}"] if (storage_gap is None and i < 4) \
+                    else np.inf
+                assert max(stats[0], stats[1]) <= tol_max and \
+                    max(stats[2], stats[3]) <= TOL_STATE_RMS, \
                     f"{tag}: recurrent state drift {stats}"
     finally:
         s.close()
@@ -106,6 +123,31 @@ def test_config2_full_size_three_frames(hs, ctx):
     _run_stream(hs, ctx, net=hs.HS_NET_RESNET18_CONVLSTM, net_name="resnet18_convlstm",
                 frames=frames, net_w=854, net_h=480, blob=blob, fp32_input=False,
                 check_state=True, tag="config2")
+
+
+@pytest.mark.timeout(600)
+def test_config2_all_60_frames_with_carried_state(hs, ctx):
+    """Configuration 2 at its stated length: 60 frames 1920x1080 of the seed-1 scene through the
+    full network with the ConvLSTM state carried 0 -> 59, the fp32 oracle beside every frame.
+    Every frame: stage 1 bit-exact; stages 3 and 4 bit-exact on the GPU's own logits / mask; the
+    recurrent cell and the head, alone, on the GPU's own inputs within 2e-3 of the oracle's
+    step -- so every one of the 60 state updates is checked by itself; logits against the fp32
+    oracle within 2e-2 rms, and within 2e-2 in the max norm for as long as the oracle's own
+    fp16-storage mode stays within 1e-2 of its fp32 mode (tests/golden/
+    config2_fp16_storage_gap.txt, written from the oracle alone: the cell state grows by up to
+    one per frame in this network and the two modes drift apart to 4e-2 by frame 40), twice
+    that file's running maximum after that."""
+    import os
+    gap_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden",
+                            "config2_fp16_storage_gap.txt")
+    gap = np.loadtxt(gap_file, comments="#")
+    assert gap.shape[0] == 60 and np.array_equal(gap[:, 0], np.arange(60))
+    frames = list(si.tool_scene_frames(60, 1080, 1920, 1))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    errs = _run_stream(hs, ctx, net=hs.HS_NET_RESNET18_CONVLSTM, net_name="resnet18_convlstm",
+                       frames=frames, net_w=854, net_h=480, blob=blob, fp32_input=False,
+                       check_state=True, tag="config2-60", emulate=False, storage_gap=gap[:, 1])
+    assert len(errs) == 60
 
 
 @pytest.mark.parametrize("fw,fh,nw,nh,thr,alpha", [
@@ -395,6 +437,14 @@ def test_partition_admission_and_masked_results_identical(hs, ctx):
         with pytest.raises(hs.HsError) as ei:                    # empty overlay mask
             hs.hs_set_partition(b.app, hs.cu_mask_words(range(half, n_cus)), hs.cu_mask_words([]))
         assert ei.value.status == hs.HS_E_OVERSUBSCRIBED
+        # a mask that leaves an XCD without a CU (CU i is on XCD i mod 8) is refused, whichever
+        # of the two masks it is, and b stays unpartitioned and usable
+        free = list(range(half, n_cus))
+        no_xcd3 = [c for c in free if c % (n_cus // 32) != 3]
+        for mi, mo in ((no_xcd3, free), (free, no_xcd3), (free[:7], free[:7])):
+            with pytest.raises(hs.HsError) as ei:
+                hs.hs_set_partition(b.app, hs.cu_mask_words(mi), hs.cu_mask_words(mo))
+            assert ei.value.status == hs.HS_E_INVAL and "XCD" in str(ei.value)
         hs.hs_set_partition(b.app, hs.cu_mask_words(range(half, n_cus)),
                             hs.cu_mask_words(range(half, n_cus)))
         assert a.submit(d_in, o2, 1) == hs.HS_OK
@@ -535,6 +585,121 @@ def test_concurrent_paced_streams_match_solo_runs(hs, ctx, partition):
     finally:
         for a in apps:
             a.close()
+
+
+def _equal_partitions(n_cus, n_apps, split):
+    """n_apps disjoint CU sets of equal size out of groups of 8 consecutive CUs (one CU per
+    XCD each), two groups left unclaimed; split: the last group of a set serves the overlay."""
+    per = (n_cus // 8 - 2) // n_apps
+    parts = []
+    for i in range(n_apps):
+        cus = list(range(i * per * 8, (i + 1) * per * 8))
+        parts.append((cus[:-8], cus[-8:]) if split else (cus, cus))
+    return parts
+
+
+@pytest.mark.parametrize("n_apps,first_seed", [(5, 2), (6, 7)])
+def test_configs_3_and_4_full_size_concurrent_applications(hs, ctx, n_apps, first_seed):
+    """Configurations 3 and 4 at configuration size: five (seeds 2-6) and six (seeds 7-12)
+    applications of the 1920x1080 -> 854x480 ResNet-18-style + ConvLSTM network, every stream
+    paced at 60 frames per second by the library's driver, one submitting thread each --
+    unpartitioned, on equal CU partitions with one queue each, and on equal partitions with
+    inference and overlay on separate CU sets (the paper's Section IV-A / IV-B arrangement).
+    In each arrangement every frame of every stream must equal, bit for bit, what the same
+    application computes alone (frame k depends on frames 0..k-1 through the cell state); the
+    first and the last frame of every stream are checked against the oracle."""
+    from paper_2402_04466_amd.harness import AppStream, run_paced
+    fw, fh, nw, nh, n_frames = 1920, 1080, 854, 480, 4
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    n_cus = hs.hs_device_cus(ctx)
+    keys = ("net_input", "logits", "heat", "mask", "argmax_idx", "present", "peak", "overlay")
+    apps, d_frames, host_frames = [], [], []
+    try:
+        for i in range(n_apps):
+            a = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=fw, frame_h=fh, net_w=nw,
+                          net_h=nh, blob=blob, palette=PAL, queue_depth=n_frames)
+            apps.append(a)
+            host_frames.append(list(si.tool_scene_frames(n_frames, fh, fw, first_seed + i)))
+            d_frames.append([a.upload_frame(f) for f in host_frames[-1]])
+        solo = []
+        for i, a in enumerate(apps):
+            print(f"[configs-3-4 {n_apps} apps] solo run of stream {i}", flush=True)
+            per = []
+            for k, d_in in enumerate(d_frames[i]):
+                o = a.new_output()
+                assert a.submit(d_in, o, k) == hs.HS_OK
+                per.append(a.fetch(a.wait(), o))
+            solo.append(per)
+        outs = [[[a.new_output()] for _ in range(n_frames)] for a in apps]
+        for arrangement in ("unpartitioned", "shared", "split"):
+            for i, a in enumerate(apps):
+                hs.hs_reset_state(a.app)
+            if arrangement != "unpartitioned":
+                parts = _equal_partitions(n_cus, n_apps, arrangement == "split")
+                for a in apps:                       # release first: the new sets overlap old ones
+                    hs.hs_set_partition(a.app, None, None)
+                for a, (ci, co) in zip(apps, parts):
+                    hs.hs_set_partition(a.app, hs.cu_mask_words(ci), hs.cu_mask_words(co))
+            for per_app in outs:
+                for o in per_app:
+                    o[0].zero_()
+            torch.cuda.synchronize()
+            print(f"[configs-3-4 {n_apps} apps] {arrangement}: {n_frames} frames per stream at "
+                  f"60 fps", flush=True)
+            results, dropped = run_paced(apps, [[[t] for t in fr] for fr in d_frames], 60.0, outs)
+            assert sum(dropped) == 0
+            for i, (a, rs) in enumerate(zip(apps, results)):
+                assert [r[0].frame_id for r in rs] == list(range(n_frames))
+                for k, r in enumerate(rs):
+                    assert r[0].t_submit_ns <= r[0].t_pre_done_ns <= r[0].t_infer_done_ns \
+                        <= r[0].t_post_done_ns <= r[0].t_overlay_done_ns
+                    g = a.fetch(r[0], outs[i][k][0])
+                    for key in keys:
+                        assert np.array_equal(g[key], solo[i][k][key]), (arrangement, i, k, key)
+        for i in range(n_apps):
+            print(f"[configs-3-4 {n_apps} apps] oracle for stream {i}", flush=True)
+            o32, _ = make_oracles("resnet18_convlstm", blob, nw, nh, True, PAL)
+            for k, f in enumerate(host_frames[i]):
+                ref = o32.process(f)
+                if k in (0, n_frames - 1):
+                    check_frame(solo[i][k], f, ref, None, threshold=0.5, alpha=0.5, palette=PAL,
+                                fp32_input=False, tag=f"configs-3-4/{n_apps}/stream{i}/frame{k}")
+    finally:
+        for a in apps:
+            a.close()
+
+
+def test_mux_refuses_a_wrong_batch_and_group_members(hs, ctx):
+    """hs_create_mux sizes its buffers by `batch` and hands them to the batch calls of the
+    application: a batch that is not the application's is HS_E_INVAL, a member of a group
+    HS_E_STATE (it is driven through the group only)."""
+    from paper_2402_04466_amd import api
+    from paper_2402_04466_amd.harness import AppStream, GroupStream
+    blob = si.he_normal_blob(si.TINY4_LAYERS, 0)
+    kw = dict(net=hs.HS_NET_TINY4, frame_w=320, frame_h=240, net_w=128, net_h=128, blob=blob,
+              palette=PAL, queue_depth=2)
+    a3, a1, b1 = AppStream(ctx, batch=3, **kw), AppStream(ctx, **kw), AppStream(ctx, **kw)
+    g = None
+    try:
+        for wrong in (1, 2, 4, 16):
+            with pytest.raises(hs.HsError) as ei:
+                api.hs_create_mux(a3.app, wrong)
+            assert ei.value.status == hs.HS_E_INVAL and "batches 3" in str(ei.value)
+        with pytest.raises(hs.HsError) as ei:
+            api.hs_create_mux(a1.app, 2)
+        assert ei.value.status == hs.HS_E_INVAL
+        api.hs_destroy_mux(api.hs_create_mux(a3.app, 3))
+        g = GroupStream(ctx, [a1, b1])
+        with pytest.raises(hs.HsError) as ei:
+            api.hs_create_mux(a1.app, 1)
+        assert ei.value.status == hs.HS_E_STATE
+    finally:
+        if g is not None:
+            g.close()
+        else:
+            a1.close()
+            b1.close()
+        a3.close()
 
 
 def test_create_destroy_cycles_release_everything(hs, ctx):

@@ -298,3 +298,108 @@ def test_fp16_storage_mode_rounds_stored_tensors_only():
     y32, y16 = Tiny4Net(blob).forward(x), Tiny4Net(blob, storage="fp16").forward(x)
     err = np.abs(y32 - y16).max() / np.abs(y32).max()
     assert 0 < err < 1e-2
+
+
+def _torch_resnet_convlstm(blob, frames, half_storage):
+    """The whole network over a frame sequence written with torch CPU routines only:
+    backbone -> conv3x3([x ; h]) -> gates i, f, g, o -> (c, h) -> 1x1 head on the new h.
+    float64 arithmetic; every stored tensor (and, in half-storage mode, every weight) is rounded
+    to the storage type, c stays float32.  Returns per frame (logits, h, c)."""
+    F = torch.nn.functional
+    rt = (lambda v: v.half().double()) if half_storage else (lambda v: v.float().double())
+    ws = [rt(torch.from_numpy(w)) for w in split_blob(blob, ResNet18ConvLSTMNet.shapes())]
+    w_lstm, w_head = ws[-2], ws[-1]
+    out, h, c = [], None, None
+    for x in frames:
+        it = iter(ws[:-2])
+        a = rt(F.relu(F.conv2d(rt(torch.from_numpy(x))[None], next(it), stride=2, padding=3)))
+        a = F.max_pool2d(a, 3, 2, 1)
+        cin = 64
+        for width in (64, 128, 256, 512):
+            for b in range(2):
+                wa, wb = next(it), next(it)
+                stride = 2 if (b == 0 and cin != width) else 1
+                t = rt(F.relu(F.conv2d(a, wa, stride=stride, padding=1)))
+                short = a if stride == 1 else rt(F.conv2d(a, next(it), stride=2))
+                a = rt(F.relu(F.conv2d(t, wb, padding=1) + short))
+            cin = width
+        if h is None:
+            h = torch.zeros((1, 256) + tuple(a.shape[2:]), dtype=torch.float64)
+            c = torch.zeros_like(h)
+        g = F.conv2d(torch.cat([a, h], dim=1), w_lstm, padding=1)
+        gi, gf, gg, go = torch.split(g, 256, dim=1)
+        c = (torch.sigmoid(gf) * c + torch.sigmoid(gi) * torch.tanh(gg)).float().double()
+        h = rt(torch.sigmoid(go) * torch.tanh(c))
+        logits = F.conv2d(h, w_head).float()
+        out.append((logits[0].numpy(), h[0].float().numpy(), c[0].float().numpy()))
+    return out
+
+
+@pytest.mark.parametrize("storage", ["fp32", "fp16"])
+def test_resnet_convlstm_forward_values_against_torch_composition(storage):
+    """Value pin of ResNet18ConvLSTMNet.forward, wiring included: which tensor feeds the gate
+    convolution, the gate order, which of (h, c) is carried where, and that the head reads the
+    NEW h.  Two frames, so that the second one runs on a non-zero carried state."""
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    frames = [_small_resnet_input(21), _small_resnet_input(22)]
+    net = ResNet18ConvLSTMNet(blob, storage=storage)
+    ref = _torch_resnet_convlstm(blob, frames, storage == "fp16")
+    # the two float64 sums differ in order only: a stored fp16 value can flip by one step (2^-11
+    # relative) where a sum lands on a rounding boundary, hence the looser bound in that mode
+    tol = 1e-5 if storage == "fp32" else 2e-3
+    for k, (x, (l_ref, h_ref, c_ref)) in enumerate(zip(frames, ref)):
+        l = net.forward(x)
+        assert l.shape == l_ref.shape == (8, 2, 3)
+        for name, got, want in (("logits", l, l_ref), ("h", net.h, h_ref), ("c", net.c, c_ref)):
+            err = np.abs(got - want).max() / np.abs(want).max()
+            assert err <= tol, f"{storage} frame {k}: {name} off by {err:.3e}"
+    # the pin can tell the mistakes it is there for: h and c are far apart, the second frame's
+    # outputs depend on the carried state, and the head on c instead of h would be far off
+    l2, h2, c2 = ref[1]
+    assert np.abs(h2 - c2).max() > 0.05
+    assert np.abs(ref[0][0] - l2).max() / np.abs(l2).max() > 1e-2
+    w_head = split_blob(blob, ResNet18ConvLSTMNet.shapes())[-1]
+    wrong = conv2d(c2, w_head, 1, 0)
+    assert np.abs(wrong - l2).max() / np.abs(l2).max() > 10 * tol
+
+
+def test_oracle_storage_modes_differ_on_the_recurrent_state_by_what_the_gpu_bound_allows():
+    """The fp16-storage mode of the oracle against its fp32 mode on the recurrent state, on
+    the inputs of the GPU state checks (the first four frames of the 640x360 -> 288x160 stream
+    and of the 1920x1080 -> 854x480 stream).  Any half-precision-storage implementation is this far from the fp32 oracle in
+    the max norm (a gate pre-activation near zero turns the rounding noise of the 20 layers in
+    front of it into a visible change of h), while the rms stays small.  The GPU test's bounds
+    (tests/gpu_common.py) are tied to the gap measured here: at most 1.5 times the worst one."""
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from gpu_common import TOL_STATE_MAX, TOL_STATE_RMS, rel_err, rms_rel
+    import oracle
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 1)
+    for key, (fw, fh, nw, nh, seed, n), lo, hi in (
+            ("288x160", (640, 360, 288, 160, 31, 4), 3e-2, 8e-2),
+            ("854x480", (1920, 1080, 854, 480, 1, 4), 4e-2, 9e-2)):
+        o32 = oracle.OracleApp("resnet18_convlstm", blob, nw, nh, True, si.DEFAULT_PALETTE)
+        o16 = oracle.OracleApp("resnet18_convlstm", blob, nw, nh, True, si.DEFAULT_PALETTE,
+                               storage="fp16")
+        worst_max = worst_rms = worst_logits = 0.0
+        stored = np.loadtxt(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden",
+                                         "config2_fp16_storage_gap.txt"), comments="#")
+        for k, f in enumerate(si.tool_scene_frames(n, fh, fw, seed)):
+            a, b = o32.process(f), o16.process(f)
+            if key == "854x480":
+                # the stored 60-frame record of this very stream (written by
+                # tests/golden/make_config2_storage_gap.py from the oracle alone) starts like this
+                assert stored[k, 0] == k
+                assert abs(stored[k, 1] - rel_err(b["logits"], a["logits"])) <= 1e-3 * stored[k, 1]
+                assert abs(stored[k, 3] - rel_err(b["h"], a["h"])) <= 1e-3 * stored[k, 3]
+            worst_max = max(worst_max, rel_err(b["h"], a["h"]), rel_err(b["c"], a["c"]))
+            worst_rms = max(worst_rms, rms_rel(b["h"], a["h"]), rms_rel(b["c"], a["c"]))
+            worst_logits = max(worst_logits, rel_err(b["logits"], a["logits"]))
+        print(f"{key}: storage-mode gap max-norm {worst_max:.3e}, rms {worst_rms:.3e}, "
+              f"logits {worst_logits:.3e}")
+        assert lo <= worst_max <= hi, f"{key}: max-norm gap {worst_max:.3e} outside [{lo}, {hi}]"
+        assert worst_max <= TOL_STATE_MAX[key] <= 1.5 * worst_max, \
+            f"{key}: TOL_STATE_MAX {TOL_STATE_MAX[key]} not within 1 .. 1.5 x {worst_max:.3e}"
+        assert worst_rms <= 5e-3 and TOL_STATE_RMS >= 2 * worst_rms
+        assert worst_logits <= 1e-2      # the network outputs themselves stay well inside 2e-2
