@@ -49,6 +49,9 @@ KernelDesc describe(const ResizeParams& p);
 struct ConvParams {
   const f16* in;
   const f16* wt;        // packed [cout_pad][ktot], ktot = nchunks*KC, zero rows above cout
+  const f16* wt_frag;   // variant 6: the same weights in MFMA fragment order,
+                        // [cout_pad / 32][Cin chunk][tap][K-step of 16][lane][8 halves], lane r + 32 h
+                        // holding k = 16 * step + 8 * h .. + 7 of channel 32 * group + r
   int hin, win, cin_pitch;
   int hout, wout, m;    // m = batch*hout*wout output pixels (images stacked along m)
   int batch, img_m;     // images per launch, pixels per image (hout*wout)
@@ -66,6 +69,9 @@ struct ConvParams {
                         // 5: a whole 64 -> 64 -> 64 channel block (two 3x3/1 convolutions, ReLU
                         //    between, shortcut from the input, ReLU) in one launch
                         //    (k_block64_fused): wt = first, wt2 = second convolution, res = in
+                        // 6: 3x3/1 layers with >= 2 Cin chunks on grids of >= 1.5 workgroups per CU:
+                        //    8 x 16 tile as variant 2, weights read as MFMA fragments straight
+                        //    from wt_frag into registers, no weight tile in LDS (k_conv3x3_dira)
   int tiles_x;          // variant 1..5: spatial tiles per output row
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;

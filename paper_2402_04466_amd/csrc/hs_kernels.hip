@@ -1102,12 +1102,210 @@ __global__ __launch_bounds__(256, 2) void k_block64_fused(ConvParams p) {
   }
 }
 
+// =============================================================================================
+// 3x3 stride-1 pad-1 layers with several Cin chunks on grids of at least 1.5 workgroups per CU
+// (stages 2-4 and the ConvLSTM gates from a few frames per launch on).  Same 8 x 16 spatial
+// tile, wavefront layout and accumulation order as k_conv3x3_halo<2, ...> -- bit-identical
+// results -- but the weights never touch LDS: they are packed on the host in MFMA fragment
+// order (one 1 KB block of 64 lanes x 16 bytes per 32 channels, tap and K-step of 16) and every
+// wavefront loads its "A" fragments straight into registers, three taps ahead.  On those grids
+// the layers are paced by LDS throughput (a tap step of the LDS-staged kernel moves 48 KB of
+// fragment reads and 10 KB of writes per workgroup; writes run at under half the rate of
+// reads): without the weight tile the LDS carries the pixel fragments only (32 KB of reads per
+// tap step), the per-tap barrier disappears (one barrier per Cin chunk, for the patch), and
+// the weight bytes come through the vector memory path, which has room (16 KB per tap step
+// and workgroup; the two wavefronts that share a channel half fetch the same lines).
+// The input patch is double buffered: chunk c+1 streams into the other buffer during the
+// taps of chunk c, at most four vectors per thread in flight.
+// p.wt_frag: [cout_pad / 32][Cin chunk][tap][K-step][lane][8 halves]; a workgroup's K range is
+// one contiguous run per channel half, walked by a pointer that advances 4 KB per tap.
+// =============================================================================================
+__global__ __launch_bounds__(256, 3) void k_conv3x3_dira(ConvParams p) {
+  constexpr int KC = 64, TH = 8, TW = 16, IPH = TH + 2, IPW = TW + 2, NPIX = IPH * IPW;
+  constexpr int PITCH = KC + 8;
+  constexpr int RP = (IPW * PITCH * 2 + ((128 - (IPW * PITCH * 2) % 256 + 256) % 256)) / 2;
+  static_assert((RP * 2) % 256 == 128, "plane row pitch must be 128 mod 256 bytes");
+  constexpr int PV = NPIX * 8;               // 16-byte vectors in a patch
+  constexpr int PL = (PV + 255) / 256;       // patch vectors per thread
+  static_assert(PL == 6, "the patch pipeline below is written out for six vectors per thread");
+  __shared__ __align__(16) f16 s_patch[2][IPH * RP];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if (tile >= p.tiles_m * p.tiles_n * p.nsplit) return;
+  const int within = tile % (p.tiles_m * p.tiles_n);              // tile order: see k_conv3x3_halo
+  const int blk = p.tiles_m * p.n_block, in_blk = within % blk;
+  const int tm = in_blk / p.n_block;
+  const int tile_n = (within / blk) * p.n_block + in_blk % p.n_block;
+  const int split = tile / (p.tiles_m * p.tiles_n);
+  const int tiles_img = p.tiles_m / p.batch;
+  const int n0 = tile_n * 64;
+  const int cc_begin = split * p.chunks_per_split;
+  const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
+  const int img = tm / tiles_img, ts = tm - img * tiles_img, ty = ts / p.tiles_x;
+  const int y0 = ty * TH, x0 = (ts - ty * p.tiles_x) * TW;
+  const int wm = wave & 1, wn = wave >> 1;
+
+  // ---- patch loader: LDS slot and source offset (in halves from p.in, -1: padding) per vector
+  int l_plds[PL], l_poff[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) {
+    const int v = tid + 256 * i;
+    const int pix = min(v >> 3, NPIX - 1), py = pix / IPW, px = pix - py * IPW;
+    l_plds[i] = v >= PV ? -1 : py * RP + px * PITCH + (v & 7) * 8;
+    const int iy = y0 + py - 1, ix = x0 + px - 1;
+    const bool inb = v < PV && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+    l_poff[i] = inb ? ((img * p.hin + iy) * p.win + ix) * p.cin_pitch + (tid & 7) * 8 : -1;
+  }
+#define HS_LOAD_P(I_, CC_) \
+  st_p[(I_) & 3] = *reinterpret_cast<const u32x4*>(p.in + (l_poff[I_] >= 0 ? l_poff[I_] + (CC_) * KC : 0));
+#define HS_HAND_P(I_, PB_)                                                                     \
+  if (l_plds[I_] >= 0) {                                                                       \
+    const u32x4 zero_ = {0u, 0u, 0u, 0u};                                                      \
+    *reinterpret_cast<u32x4*>(&s_patch[PB_][l_plds[I_]]) = l_poff[I_] >= 0 ? st_p[(I_) & 3] : zero_; \
+  }
+  u32x4 st_p[4];
+
+  // ---- weight fragments: this wavefront's 32 channels, one 1 KB block per (chunk, tap, K-step)
+  const u32x4* wf = reinterpret_cast<const u32x4*>(p.wt_frag) +
+                    ((size_t)(n0 / 32 + wn) * p.chunks_per_tap + cc_begin) * (9 * 4 * 64) + lane;
+  const u32x4* const wf_last = wf + (size_t)((cc_end - cc_begin) * 9 - 1) * (4 * 64);
+  u32x4 fa[3][4];
+#define HS_LOAD_A(S_)                                                                          \
+  {                                                                                            \
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) fa[S_][ks] = wf[ks * 64];                 \
+    wf = wf + 4 * 64 <= wf_last ? wf + 4 * 64 : wf_last;   /* the last steps re-read the last tap */ \
+  }
+
+  const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  floatx16 acc[2] = {zero16, zero16};
+  const int fp_off = (4 * wm + (r >> 3)) * RP + (r & 7) * PITCH + h * 8;
+
+  // A chunk is 36 K-steps of 16 (tap-major, four per tap); Q_ and LAST_ are literals.  Weight
+  // stage (Q_ / 4) % 3 holds the tap's fragments and is refilled, behind their last use, with
+  // those of the step three taps ahead.  Pixel fragments are read from LDS BD K-steps before
+  // the MFMAs that use them (a ring of BD + 1 register sets), so that an LDS round trip hides
+  // behind 2 * BD MFMAs of this wavefront; only the first BD steps of a chunk, behind its
+  // barrier, wait for theirs.  Vector i of the next chunk's patch is fetched at tap i and
+  // handed to the other buffer at tap i + 3.
+  constexpr int BD = 3;
+  half8 bf[BD + 1][2];
+#define HS_READ_B(Q_)                                                                          \
+  {                                                                                            \
+    const f16* fp_ = &s_patch[pb][fp_off + ((Q_) / 12) * RP + (((Q_) / 4) % 3) * PITCH + ((Q_) % 4) * 16]; \
+    _Pragma("unroll") for (int g = 0; g < 2; ++g)                                              \
+      bf[(Q_) % (BD + 1)][g] = *reinterpret_cast<const half8*>(fp_ + g * 8 * PITCH);           \
+  }
+#define HS_KSTEP(Q_, LAST_)                                                                    \
+  {                                                                                            \
+    if ((Q_) + BD < 36) HS_READ_B((Q_) + BD)                                                   \
+    if ((Q_) % 4 == 0) {                                                                       \
+      if (!(LAST_) && (Q_) / 4 >= 3) HS_HAND_P((Q_) / 4 - 3, pb ^ 1)                           \
+      if (!(LAST_) && (Q_) / 4 < PL) HS_LOAD_P((Q_) / 4, cc + 1)                               \
+    }                                                                                          \
+    const half8 a_ = __builtin_bit_cast(half8, fa[((Q_) / 4) % 3][(Q_) % 4]);                  \
+    _Pragma("unroll") for (int g = 0; g < 2; ++g)                                              \
+      acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_, bf[(Q_) % (BD + 1)][g], acc[g], 0, 0, 0); \
+    if ((Q_) % 4 == 3) HS_LOAD_A(((Q_) / 4) % 3)                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
+#define HS_TAP(T_, LAST_)                                                                      \
+  HS_KSTEP(4 * (T_), LAST_) HS_KSTEP(4 * (T_) + 1, LAST_) HS_KSTEP(4 * (T_) + 2, LAST_)        \
+  HS_KSTEP(4 * (T_) + 3, LAST_)
+#define HS_CHUNK(LAST_)                                                                        \
+  HS_READ_B(0) HS_READ_B(1) HS_READ_B(2)                                                       \
+  HS_TAP(0, LAST_) HS_TAP(1, LAST_) HS_TAP(2, LAST_) HS_TAP(3, LAST_) HS_TAP(4, LAST_)         \
+  HS_TAP(5, LAST_) HS_TAP(6, LAST_) HS_TAP(7, LAST_) HS_TAP(8, LAST_)
+  static_assert(BD == 3, "HS_CHUNK primes three K-steps");
+
+  // ---- prologue: first patch into buffer 0, first three taps of weights into the stages
+  int cc = cc_begin, pb = 0;
+  {
+    u32x4 first[PL];
+#pragma unroll
+    for (int i = 0; i < PL; ++i)
+      first[i] = *reinterpret_cast<const u32x4*>(p.in + (l_poff[i] >= 0 ? l_poff[i] + cc * KC : 0));
+    HS_LOAD_A(0) HS_LOAD_A(1) HS_LOAD_A(2)
+#pragma unroll
+    for (int i = 0; i < PL; ++i)
+      if (l_plds[i] >= 0) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(&s_patch[0][l_plds[i]]) = l_poff[i] >= 0 ? first[i] : zero;
+      }
+  }
+  __syncthreads();
+
+  const int oy = y0 + 4 * wm + (r >> 3);
+  const int n_base = n0 + wn * 32 + h * 4;
+  for (; cc + 1 < cc_end; ++cc) {
+    HS_CHUNK(false)
+    __syncthreads();      // the next patch is complete, and every wavefront is done with this one
+    pb ^= 1;
+  }
+  // residual of the block's second convolution: fetched while the last chunk is computed
+  const bool res_here = p.res != nullptr && !p.use_partial;
+  half4 res_pre[2][4];
+  if (res_here) {
+    const int oy_c = min(oy, p.hout - 1);
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int ox_c = min(x0 + 8 * g + (r & 7), p.wout - 1);
+      const f16* rp = p.res + (size_t)(img * p.img_m + oy_c * p.wout + ox_c) * p.res_pitch;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        res_pre[g][i] = *reinterpret_cast<const half4*>(rp + min(n_base + 8 * i, p.cout - 4));
+    }
+  }
+  HS_CHUNK(true)
+
+  // ---- epilogue: accumulator quad i of group g = channels n_base + 8*i .. +3 of pixel (oy, ox_g)
+  const bool wide_out = !p.use_partial && p.out_f32 == nullptr && (p.cout & 63) == 0;
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const int ox = x0 + 8 * g + (r & 7);
+    const bool valid = oy < p.hout && ox < p.wout;
+    const int m = img * p.img_m + oy * p.wout + ox;
+    if (wide_out) {                       // every lane takes part in the exchange
+      store_octets(p, valid, m, n0 + wn * 32, h, acc[g], res_pre[g], res_here);
+    } else if (valid) {
+      if (p.use_partial) {
+        float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<float4*>(dst + 8 * i) =
+              make_float4(acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int n = n_base + 8 * i;
+          if (n < p.cout) {
+            float v[4] = {acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]};
+            if (res_here) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) v[j] += (float)res_pre[g][i][j];
+            }
+            store_quad<false>(p, m, n, v);
+          }
+        }
+      }
+    }
+  }
+#undef HS_CHUNK
+#undef HS_TAP
+#undef HS_KSTEP
+#undef HS_READ_B
+#undef HS_LOAD_A
+#undef HS_HAND_P
+#undef HS_LOAD_P
+}
+
 constexpr int OCC3 = 2, OCC4 = 2;   // waves per SIMD the tile-walking instantiations are built for
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
   const dim3 grid(8u * (unsigned)p.tiles_per_xcd);
   const bool walk = p.tiles_per_wg > 1;
   if (p.variant == 5) return KernelDesc{(const void*)k_block64_fused, grid, dim3(256), 0};
+  if (p.variant == 6) return KernelDesc{(const void*)k_conv3x3_dira, grid, dim3(256), 0};
   if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 3 && walk && p.chunks_per_tap == 1 && !p.use_partial && p.nsplit == 1 &&

@@ -246,6 +246,24 @@ static void pack_generic(const float* w, int cout, int cin, int k, int cout_pad,
               (f16)w[(((size_t)n * cin + c) * k + ky) * k + kx];
 }
 
+// The same layer in MFMA fragment order for the kernel that reads its weight operand straight
+// from memory (3x3, cin % 64 == 0): dst[(((g*chunks + cc)*9 + tap)*4 + ks)*64 + lane][j] =
+// w[32*g + r][64*cc + 16*ks + 8*h + j][tap], lane = r + 32*h; channels above cout are zero.
+static void pack_frag(const float* w, int cout, int cin, int cout_pad, f16* dst) {
+  const int chunks = cin / 64;
+  std::memset(dst, 0, (size_t)cout_pad * 9 * cin * sizeof(f16));
+  for (int n = 0; n < cout; ++n) {
+    const int g = n / 32, r = n % 32;
+    for (int c = 0; c < cin; ++c) {
+      const int cc = c / 64, ks = (c % 64) / 16, h = (c % 16) / 8, j = c % 8;
+      for (int tap = 0; tap < 9; ++tap) {
+        const size_t block = (((size_t)g * chunks + cc) * 9 + tap) * 4 + ks;
+        dst[(block * 64 + (size_t)(r + 32 * h)) * 8 + j] = (f16)w[((size_t)n * cin + c) * 9 + tap];
+      }
+    }
+  }
+}
+
 // First layer on the padded 4-channel image: one chunk per kernel row, covering chunk_px
 // adjacent pixels of 4 channels; packed[n][ky][px][ch] = w[n][ch][ky][px] (px < k, ch < 3).
 static void pack_rowtap(const float* w, int cout, int k, int chunk_px, int cout_pad, f16* dst) {
@@ -324,6 +342,9 @@ struct Builder {
       const int ty = (c.hout + 7) / 8;
       const int wide = c.batch * ty * ((c.wout + 15) / 16) * (c.cout_pad / 64);
       c.variant = wide > 512 ? 3 : wide >= 192 ? 2 : 1;
+      // from 1.5 workgroups per CU on, layers with several Cin chunks are paced by LDS
+      // throughput: the variant that keeps the weights out of LDS takes them
+      if (wide >= 384 && c.chunks_per_tap >= 2) c.variant = 6;
       const int tw = c.variant == 1 ? 8 : 16;
       c.tiles_x = (c.wout + tw - 1) / tw;
       c.tiles_m = c.batch * ty * c.tiles_x;
@@ -359,7 +380,7 @@ struct Builder {
     // block size, count what the eight L2s fetch (each its own spatial groups' input slices and
     // its own channel tiles' weight slices, once) and keep the cheapest.
     c.n_block = 1;
-    if (c.variant >= 1 && c.variant <= 4 && c.tiles_n > 1) {
+    if (((c.variant >= 1 && c.variant <= 4) || c.variant == 6) && c.tiles_n > 1) {
       const double in_unit = 2.0 * c.batch * c.hin * c.win * (c.chunks_per_tap * 64.0) /
                              ((double)groups_m * c.nsplit);
       const double w_unit = 2.0 * c.cout_pad * c.ktot / ((double)c.tiles_n * c.nsplit);
@@ -394,11 +415,12 @@ struct Builder {
   // stride-2 layer (out2 == NULL: none).
   int add_conv(ConvParams c, size_t w_off, const Tensor* res, const Tensor* out, bool relu,
                bool want_f32, bool keep_partial, double flops, size_t w2_off = 0,
-               const Tensor* out2 = nullptr) {
+               const Tensor* out2 = nullptr, size_t wf_off = (size_t)-1) {
     Op op;
     op.fam = F_CONV;
     op.flops = flops;
     c.wt = d_w ? d_w + w_off : nullptr;
+    c.wt_frag = (d_w && wf_off != (size_t)-1) ? d_w + wf_off : nullptr;
     choose_split(c);
     const bool partial = c.nsplit > 1 || keep_partial;
     c.use_partial = partial ? 1 : 0;
@@ -470,9 +492,19 @@ struct Builder {
     const bool fuse = proj_out && k == 3 && stride == 2 && pad == 1 && g.kc == 64 &&
                       (double)g.batch * g.hin * g.win * g.cin_pitch < 2147483648.0;
     if (proj_fused) *proj_fused = fuse;
-    if (!fuse)
+    if (!fuse) {
+      // the kernel variant is a function of the shapes alone: layers that will read their
+      // weights as MFMA fragments get a second, fragment-ordered copy
+      size_t wf_off = (size_t)-1;
+      ConvParams probe = g;
+      choose_split(probe);
+      if (probe.variant == 6) {
+        wf_off = reserve_w((size_t)g.cout_pad * g.ktot);
+        if (pack) pack_frag(blob + blob_at, cout, cin, g.cout_pad, host_w.data() + wf_off);
+      }
       return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
-                      2.0 * g.m * (double)cout * cin * k * k);
+                      2.0 * g.m * (double)cout * cin * k * k, 0, nullptr, wf_off);
+    }
     const size_t w2_off = reserve_w((size_t)g.cout_pad * cin);
     if (pack) pack_generic(blob + proj_at, cout, cin, 1, g.cout_pad, host_w.data() + w2_off);
     proj_out->h = g.hout; proj_out->w = g.wout; proj_out->c = cout;
