@@ -72,6 +72,9 @@ struct ConvParams {
                         // 6: 3x3/1 layers with >= 2 Cin chunks on grids of >= 1.5 workgroups per CU:
                         //    8 x 16 tile as variant 2, weights read as MFMA fragments straight
                         //    from wt_frag into registers, no weight tile in LDS (k_conv3x3_dira)
+                        // 7: 3x3/2 layers (+ fused 1x1/2 projection) on such grids, weights from
+                        //    wt_frag / wt2_frag, fp16 outputs with cout % 64 == 0 or split-K
+                        //    partials, no residual (k_conv3x3s2_dira)
   int tiles_x;          // variant 1..5: spatial tiles per output row
   int ntaps, kw, chunks_per_tap, nchunks, ktot;
   int stride, pad;
@@ -83,6 +86,8 @@ struct ConvParams {
   int tiles_per_xcd;    // ceil(workgroups / 8)
   int n_block;          // variant 1..4: channel tiles per block of the tile order (divides tiles_n;
                         // 1: spatial tile fastest, tiles_n: channel tile fastest)
+  int frag_ok;          // host planning hint: the layer may use the fragment-weight kernels
+                        // (fp16 output of whole 64-channel tiles or split-K partials, no residual)
   int use_partial;      // 1: store fp32 partial sums for a reduction kernel, no epilogue here
   float* partial;       // [nsplit][m][cout_pad] fp32
   // fused epilogue (use_partial == 0)
@@ -94,6 +99,8 @@ struct ConvParams {
   float* out_f32;       // if set: planar fp32 out_f32[n*m_total + m] instead of `out`
   // variant 4 only: fused 1x1 stride-2 projection of the same input (no residual, no ReLU)
   const f16* wt2;       // packed [cout_pad][cin], or NULL
+  const f16* wt2_frag;  // variant 7: the projection in MFMA fragment order,
+                        // [cout_pad / 32][Cin chunk][K-step of 16][lane][8 halves], or NULL
   f16* out2; int out2_pitch;
   float* partial2;      // [nsplit][m][cout_pad] fp32 when use_partial
 };

@@ -1299,6 +1299,263 @@ __global__ __launch_bounds__(256, 3) void k_conv3x3_dira(ConvParams p) {
 #undef HS_LOAD_P
 }
 
+// =============================================================================================
+// 3x3 stride-2 pad-1 layers (with the block's 1x1 stride-2 projection riding along) on grids of
+// at least 1.5 workgroups per CU: the stride-2 counterpart of k_conv3x3_dira.  Output tile 8 x 8
+// pixels x 128 channels; wavefront w = all 64 pixels (two groups of four rows), channels
+// 32*w .. +31: a weight fragment is fetched by one wavefront only and serves two MFMAs, and
+// the patch -- the heavy operand of a stride-2 tile -- serves 128 channels.
+// A stride-2 tile needs four input pixels per output pixel (17 x 17 of them), and with the
+// weight tile in LDS and a barrier per tap a wavefront got four MFMAs per barrier: those layers
+// ran the matrix pipe at 16-23 %.  Here
+//   - the weights come as MFMA fragments straight from memory (p.wt_frag, and p.wt2_frag for the
+//     projection), three taps ahead: no weight tile, no per-tap barrier;
+//   - the patch is cut into half chunks of 32 input channels (one "item" = one half chunk of
+//     one tile: nine taps + the projection, two K-steps of 16 each), stored as four parity
+//     planes of 9 x 9 pixels (pixel (py, px) in plane (py & 1, px & 1) at (py / 2, px / 2), so that
+//     the lanes of a tap read neighbouring plane pixels) with 64 bytes per pixel and no padding:
+//     the four 16-byte vectors of a pixel are permuted by its plane row and column
+//     (v ^ ((col >> 2) & 1 | (row & 1) << 1)), which makes every fragment read conflict free.
+//     Two buffers of 20 KB: the next item's patch streams in during the taps of the current
+//     one (four vectors per thread in flight), one barrier per item, two workgroups per CU
+//     (four accumulators per wavefront with the projection's);
+//   - a workgroup walks tiles_per_wg consecutive spatial tiles in one pipeline (the next tile's
+//     first patch and weights are fetched during the last taps of the current tile), so the
+//     short K loops of the 64-channel layer do not pay a cold start per tile.
+// Per output the K order is chunk, half chunk, tap, K-step: within a chunk the two halves are
+// summed one after the other, not interleaved tap by tap as in k_conv3x3_halo<1, 1, 3, 2, ...>;
+// results agree with that kernel to fp32 rounding, not bit for bit.
+// =============================================================================================
+__global__ __launch_bounds__(256, 2) void k_conv3x3s2_dira(ConvParams p) {
+  constexpr int TH = 8, TW = 8, IPW = 2 * TW + 1, NPIX = IPW * IPW;   // 17 x 17 input pixels
+  constexpr int PLW = TW + 1, PLANE = PLW * PLW;                      // 9 x 9 pixels per parity plane
+  constexpr int PV = NPIX * 4, PL = (PV + 255) / 256;                 // 16-byte vectors, per thread
+  static_assert(PL == 5, "the patch pipeline below is written out for five vectors per thread");
+  __shared__ __align__(16) f16 s_patch[2][4 * PLANE * 32];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  const int groups_m = (p.tiles_m + p.tiles_per_wg - 1) / p.tiles_per_wg;
+  if (tile >= groups_m * p.tiles_n * p.nsplit) return;
+  const int within = tile % (groups_m * p.tiles_n);               // tile order: see k_conv3x3_halo
+  const int blk = groups_m * p.n_block, in_blk = within % blk;
+  const int tm_begin = (in_blk / p.n_block) * p.tiles_per_wg;
+  const int tm_end = min(p.tiles_m, tm_begin + p.tiles_per_wg);
+  const int tile_n = (within / blk) * p.n_block + in_blk % p.n_block;
+  const int split = tile / (groups_m * p.tiles_n);
+  const int tiles_img = p.tiles_m / p.batch;
+  const int n0 = tile_n * 128;
+  const int cc_begin = split * p.chunks_per_split;
+  const int cc_end = min(p.chunks_per_tap, cc_begin + p.chunks_per_split);
+  const int n_halves = 2 * (cc_end - cc_begin);                   // items per tile
+  const int n_items = (tm_end - tm_begin) * n_halves;
+  const bool has_proj = p.wt2_frag != nullptr;
+
+  // ---- patch loader: the LDS slot of every vector is fixed, its source depends on the tile
+  int l_plds[PL], l_pyx[PL], l_poff[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) {
+    const int vec = tid + 256 * i, pix = min(vec >> 2, NPIX - 1), v = vec & 3;
+    const int py = pix / IPW, px = pix - py * IPW, prow = py >> 1, pcol = px >> 1;
+    const int sw = ((pcol >> 2) & 1) | ((prow & 1) << 1);
+    l_pyx[i] = py | (px << 8);
+    l_plds[i] = vec >= PV ? -1
+                          : ((((py & 1) * 2 + (px & 1)) * PLANE + prow * PLW + pcol) * 4 + (v ^ sw)) * 8;
+  }
+  // source offsets (halves from p.in, channel 8 * (tid & 3) of the pixel; -1: padding) of tile TM_
+#define HS_TILE_SETUP(TM_, IMG_, Y0_, X0_)                                                     \
+  {                                                                                            \
+    IMG_ = (TM_) / tiles_img;                                                                  \
+    const int ts_ = (TM_) - IMG_ * tiles_img, ty_ = ts_ / p.tiles_x;                           \
+    Y0_ = ty_ * TH;                                                                            \
+    X0_ = (ts_ - ty_ * p.tiles_x) * TW;                                                        \
+    _Pragma("unroll") for (int i = 0; i < PL; ++i) {                                           \
+      const int iy_ = 2 * Y0_ + (l_pyx[i] & 0xff) - 1, ix_ = 2 * X0_ + (l_pyx[i] >> 8) - 1;    \
+      const bool inb_ = l_plds[i] >= 0 && iy_ >= 0 && iy_ < p.hin && ix_ >= 0 && ix_ < p.win;  \
+      l_poff[i] = inb_ ? ((IMG_ * p.hin + iy_) * p.win + ix_) * p.cin_pitch + (tid & 3) * 8 : -1; \
+    }                                                                                          \
+  }
+  u32x4 st_p[4];
+#define HS_LOAD_P(I_) \
+  st_p[(I_) & 3] = *reinterpret_cast<const u32x4*>(p.in + (l_poff[I_] >= 0 ? l_poff[I_] + ch_n : 0));
+#define HS_HAND_P(I_, PB_)                                                                     \
+  if (l_plds[I_] >= 0) {                                                                       \
+    const u32x4 zero_ = {0u, 0u, 0u, 0u};                                                      \
+    *reinterpret_cast<u32x4*>(&s_patch[PB_][l_plds[I_]]) = l_poff[I_] >= 0 ? st_p[(I_) & 3] : zero_; \
+  }
+
+  // ---- pixel fragments: lane (r, h) reads output pixels (4*g + r/8, r%8), g = 0, 1; tap (ky, kx)
+  // reads plane (ky & 1, kx & 1) at (+ky/2, +kx/2); K-step j of the item is vector 2*j + h of the
+  // pixel.  Group 1 lies four plane rows below group 0 (same row parity, same permutation).
+  constexpr int GOFF = 4 * PLW * 32;
+  const int oy_l = r >> 3, ox_l = r & 7;
+  int fb[2][2][2];    // [ky / 2][kx / 2][j]: halves offset inside a plane
+#pragma unroll
+  for (int dy = 0; dy < 2; ++dy)
+#pragma unroll
+    for (int dx = 0; dx < 2; ++dx) {
+      const int prow = oy_l + dy, pcol = ox_l + dx;
+      const int sw = ((pcol >> 2) & 1) | ((prow & 1) << 1);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[dy][dx][j] = ((prow * PLW + pcol) * 4 + ((2 * j + h) ^ sw)) * 8;
+    }
+
+  // ---- weight fragments of this wavefront's 32 channels: blocks of 64 lanes x 16 bytes,
+  // [chunk][tap][K-step of 16] for the 3x3 taps, [chunk][K-step] for the projection
+  const u32x4* const wf0 = reinterpret_cast<const u32x4*>(p.wt_frag) +
+                           (size_t)(n0 / 32 + wave) * p.chunks_per_tap * (9 * 4 * 64) + lane;
+  const u32x4* const wp0 = has_proj ? reinterpret_cast<const u32x4*>(p.wt2_frag) +
+                                          (size_t)(n0 / 32 + wave) * p.chunks_per_tap * (4 * 64) + lane
+                                    : wf0;
+  // half chunk HF_ (0 .. n_halves - 1) of the K range: chunk cc_begin + HF_ / 2, K-steps 2 * (HF_ & 1) ..
+#define HS_WBASE(HF_) (wf0 + ((size_t)(cc_begin + ((HF_) >> 1)) * 36 + 2 * ((HF_) & 1)) * 64)
+#define HS_PBASE(HF_) (wp0 + ((size_t)(cc_begin + ((HF_) >> 1)) * 4 + 2 * ((HF_) & 1)) * 64)
+  u32x4 fa[3][2], fp2[2];
+#define HS_LOAD_A(S_, BASE_, T_)                                                               \
+  {                                                                                            \
+    fa[S_][0] = (BASE_)[(T_) * 4 * 64];                                                        \
+    fa[S_][1] = (BASE_)[(T_) * 4 * 64 + 64];                                                   \
+  }
+
+  const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  floatx16 acc[2] = {zero16, zero16}, acc2[2] = {zero16, zero16};
+
+  // K-step Q_ (literal) of the current item: Q_ / 2 = tap (9: the projection, on the centre
+  // tap's pixels), Q_ & 1 = which 16 of the item's 32 channels.  Pixel fragments are read BD
+  // steps ahead (ring of BD + 1); weight stage tap % 3 is refilled behind its last use with
+  // the tap three ahead, from the next item's block once that runs past this item's ninth tap.
+  constexpr int BD = 3;
+  half8 bf[BD + 1][2];
+#define HS_TAPQ(Q_) ((Q_) / 2 == 9 ? 4 : (Q_) / 2)     /* the projection reads the centre tap */
+#define HS_READ_B(Q_)                                                                          \
+  {                                                                                            \
+    const f16* fp_ = &s_patch[pb][((((HS_TAPQ(Q_) / 3) & 1) * 2 + ((HS_TAPQ(Q_) % 3) & 1)) * PLANE) * 32 + \
+                                  fb[(HS_TAPQ(Q_) / 3) >> 1][(HS_TAPQ(Q_) % 3) >> 1][(Q_) & 1]]; \
+    bf[(Q_) % (BD + 1)][0] = *reinterpret_cast<const half8*>(fp_);                             \
+    bf[(Q_) % (BD + 1)][1] = *reinterpret_cast<const half8*>(fp_ + GOFF);                      \
+  }
+#define HS_KSTEP(Q_)                                                                           \
+  {                                                                                            \
+    if ((Q_) + BD < 20) { if ((Q_) + BD < 18 || has_proj) HS_READ_B((Q_) + BD) }               \
+    if (((Q_) & 1) == 0 && more) {                                                             \
+      if ((Q_) / 2 >= 3 && (Q_) / 2 - 3 < PL) HS_HAND_P((Q_) / 2 - 3, pb ^ 1)                  \
+      if ((Q_) / 2 < PL) HS_LOAD_P((Q_) / 2)                                                   \
+    }                                                                                          \
+    if ((Q_) < 18) {                                                                           \
+      const half8 a_ = __builtin_bit_cast(half8, fa[((Q_) / 2) % 3][(Q_) & 1]);                \
+      _Pragma("unroll") for (int g = 0; g < 2; ++g)                                            \
+        acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_, bf[(Q_) % (BD + 1)][g], acc[g], 0, 0, 0); \
+      if ((Q_) & 1) {                                                                          \
+        if ((Q_) / 2 + 3 < 9) HS_LOAD_A(((Q_) / 2) % 3, w_cur, (Q_) / 2 + 3)                   \
+        else HS_LOAD_A(((Q_) / 2) % 3, w_nxt, (Q_) / 2 + 3 - 9)                                \
+      }                                                                                        \
+    } else if (has_proj) {                                                                     \
+      const half8 a_ = __builtin_bit_cast(half8, fp2[(Q_) & 1]);                               \
+      _Pragma("unroll") for (int g = 0; g < 2; ++g)                                            \
+        acc2[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_, bf[(Q_) % (BD + 1)][g], acc2[g], 0, 0, 0); \
+    }                                                                                          \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
+
+  // ---- prologue: first item's patch into buffer 0, its first three taps of weights
+  int img, y0, x0;
+  HS_TILE_SETUP(tm_begin, img, y0, x0)
+  int pb = 0;
+  {
+    u32x4 first[PL];
+    const int ch0 = cc_begin * 64;
+#pragma unroll
+    for (int i = 0; i < PL; ++i)
+      first[i] = *reinterpret_cast<const u32x4*>(p.in + (l_poff[i] >= 0 ? l_poff[i] + ch0 : 0));
+    const u32x4* w0 = HS_WBASE(0);
+    HS_LOAD_A(0, w0, 0) HS_LOAD_A(1, w0, 1) HS_LOAD_A(2, w0, 2)
+#pragma unroll
+    for (int i = 0; i < PL; ++i)
+      if (l_plds[i] >= 0) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(&s_patch[0][l_plds[i]]) = l_poff[i] >= 0 ? first[i] : zero;
+      }
+  }
+  __syncthreads();
+
+  const int n_base = n0 + wave * 32 + h * 4;
+  int tm = tm_begin, hf = 0;
+  for (int item = 0; item < n_items; ++item) {
+    // the item after this one: next half chunk of the tile, or the first of the next tile
+    const bool more = item + 1 < n_items;
+    const bool cross = hf + 1 == n_halves;
+    const int hf_n = more ? (cross ? 0 : hf + 1) : hf;
+    const int s_img = img, s_y0 = y0, s_x0 = x0;      // this item's tile (for the store below)
+    if (more && cross) HS_TILE_SETUP(tm + 1, img, y0, x0)   // l_poff now describes the next tile
+    const int ch_n = (cc_begin + (hf_n >> 1)) * 64 + (hf_n & 1) * 32;
+    const u32x4* const w_cur = HS_WBASE(hf);
+    const u32x4* const w_nxt = HS_WBASE(hf_n);
+    if (has_proj) {
+      const u32x4* pbase = HS_PBASE(hf);
+      fp2[0] = pbase[0];
+      fp2[1] = pbase[64];
+    }
+    HS_READ_B(0) HS_READ_B(1) HS_READ_B(2)
+    HS_KSTEP(0) HS_KSTEP(1) HS_KSTEP(2) HS_KSTEP(3) HS_KSTEP(4) HS_KSTEP(5) HS_KSTEP(6)
+    HS_KSTEP(7) HS_KSTEP(8) HS_KSTEP(9) HS_KSTEP(10) HS_KSTEP(11) HS_KSTEP(12) HS_KSTEP(13)
+    HS_KSTEP(14) HS_KSTEP(15) HS_KSTEP(16) HS_KSTEP(17) HS_KSTEP(18) HS_KSTEP(19)
+    if (cross) {
+      // ---- the tile is complete: accumulator quad i of group g = channels n_base + 8*i .. +3 of
+      // pixel (4*g + r/8, r%8) of the tile
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int oy = s_y0 + 4 * g + oy_l, ox = s_x0 + ox_l;
+        const bool valid = oy < p.hout && ox < p.wout;
+        const int m = s_img * p.img_m + oy * p.wout + ox;
+        if (p.use_partial) {
+          if (valid) {
+            float* dst = p.partial + ((size_t)split * p.m + m) * p.cout_pad + n_base;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              *reinterpret_cast<float4*>(dst + 8 * i) = make_float4(
+                  acc[g][4 * i], acc[g][4 * i + 1], acc[g][4 * i + 2], acc[g][4 * i + 3]);
+            if (has_proj) {
+              float* dst2 = p.partial2 + ((size_t)split * p.m + m) * p.cout_pad + n_base;
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<float4*>(dst2 + 8 * i) = make_float4(
+                    acc2[g][4 * i], acc2[g][4 * i + 1], acc2[g][4 * i + 2], acc2[g][4 * i + 3]);
+            }
+          }
+        } else {
+          // fp16 outputs with whole 128-channel tiles (the host selects this kernel only then)
+          const half4 none[4] = {};
+          store_octets(p, valid, m, n0 + wave * 32, h, acc[g], none, false);
+          if (has_proj && valid) {                 // projection: no residual, no ReLU
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              half4 o;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) o[j] = (f16)acc2[g][4 * i + j];
+              *reinterpret_cast<half4*>(p.out2 + (size_t)m * p.out2_pitch + n_base + 8 * i) = o;
+            }
+          }
+        }
+      }
+      acc[0] = acc[1] = zero16;
+      acc2[0] = acc2[1] = zero16;
+      ++tm;
+    }
+    hf = hf_n;
+    __syncthreads();      // the next patch is complete, and every wavefront is done with this one
+    pb ^= 1;
+  }
+#undef HS_KSTEP
+#undef HS_READ_B
+#undef HS_TAPQ
+#undef HS_LOAD_A
+#undef HS_PBASE
+#undef HS_WBASE
+#undef HS_HAND_P
+#undef HS_LOAD_P
+#undef HS_TILE_SETUP
+}
+
 constexpr int OCC3 = 2, OCC4 = 2;   // waves per SIMD the tile-walking instantiations are built for
 KernelDesc describe(const ConvParams& p) {
   // 1-D grid, padded to a multiple of 8 so that every XCD owns tiles_per_xcd consecutive tiles
@@ -1306,6 +1563,7 @@ KernelDesc describe(const ConvParams& p) {
   const bool walk = p.tiles_per_wg > 1;
   if (p.variant == 5) return KernelDesc{(const void*)k_block64_fused, grid, dim3(256), 0};
   if (p.variant == 6) return KernelDesc{(const void*)k_conv3x3_dira, grid, dim3(256), 0};
+  if (p.variant == 7) return KernelDesc{(const void*)k_conv3x3s2_dira, grid, dim3(256), 0};
   if (p.variant == 1) return KernelDesc{(const void*)k_conv3x3_halo<1, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 2) return KernelDesc{(const void*)k_conv3x3_halo<2, 2, 9, 1, false, 1>, grid, dim3(256), 0};
   if (p.variant == 3 && walk && p.chunks_per_tap == 1 && !p.use_partial && p.nsplit == 1 &&

@@ -249,16 +249,18 @@ static void pack_generic(const float* w, int cout, int cin, int k, int cout_pad,
 // The same layer in MFMA fragment order for the kernel that reads its weight operand straight
 // from memory (3x3, cin % 64 == 0): dst[(((g*chunks + cc)*9 + tap)*4 + ks)*64 + lane][j] =
 // w[32*g + r][64*cc + 16*ks + 8*h + j][tap], lane = r + 32*h; channels above cout are zero.
-static void pack_frag(const float* w, int cout, int cin, int cout_pad, f16* dst) {
+// ntaps = 9 (3x3) or 1 (the 1x1 projection fused into a stride-2 layer).
+static void pack_frag(const float* w, int cout, int cin, int ntaps, int cout_pad, f16* dst) {
   const int chunks = cin / 64;
-  std::memset(dst, 0, (size_t)cout_pad * 9 * cin * sizeof(f16));
+  std::memset(dst, 0, (size_t)cout_pad * ntaps * cin * sizeof(f16));
   for (int n = 0; n < cout; ++n) {
     const int g = n / 32, r = n % 32;
     for (int c = 0; c < cin; ++c) {
       const int cc = c / 64, ks = (c % 64) / 16, h = (c % 16) / 8, j = c % 8;
-      for (int tap = 0; tap < 9; ++tap) {
-        const size_t block = (((size_t)g * chunks + cc) * 9 + tap) * 4 + ks;
-        dst[(block * 64 + (size_t)(r + 32 * h)) * 8 + j] = (f16)w[((size_t)n * cin + c) * 9 + tap];
+      for (int tap = 0; tap < ntaps; ++tap) {
+        const size_t block = (((size_t)g * chunks + cc) * ntaps + tap) * 4 + ks;
+        dst[(block * 64 + (size_t)(r + 32 * h)) * 8 + j] =
+            (f16)w[((size_t)n * cin + c) * ntaps + tap];
       }
     }
   }
@@ -331,6 +333,12 @@ struct Builder {
       c.tiles_m = c.batch * ((c.hout + 7) / 8) * c.tiles_x;
       c.tiles_n = c.cout_pad / 64;
       const int tiles = c.tiles_m * c.tiles_n;
+      // from 1.5 workgroups per CU on: weights as fragments from memory, half-chunk patches
+      // (channel tiles of 128 there: the patch, the heavy operand at stride 2, serves them all)
+      if (tiles >= 768 && c.frag_ok && c.cout % 128 == 0) {
+        c.variant = 7;
+        c.tiles_n = c.cout_pad / 128;
+      }
       const int units = c.chunks_per_tap;
       int ns = 1;
       if (tiles < 192) ns = std::max(1, std::min((256 + tiles - 1) / tiles, units));
@@ -374,13 +382,17 @@ struct Builder {
       const int wgs = c.tiles_m * c.tiles_n * c.nsplit;
       if (wgs > 1536) c.tiles_per_wg = (wgs + 511) / 512;
     }
+    if (c.variant == 7) {   // two workgroups per CU are resident: at most two rounds
+      const int wgs = c.tiles_m * c.tiles_n * c.nsplit;
+      if (wgs > 1024) c.tiles_per_wg = (wgs + 1023) / 1024;
+    }
     const int groups_m = (c.tiles_m + c.tiles_per_wg - 1) / c.tiles_per_wg;
     c.tiles_per_xcd = (groups_m * c.tiles_n * c.nsplit + 7) / 8;
     // Tile order: every XCD (own L2) takes a run of tiles_per_xcd consecutive tiles.  For every
     // block size, count what the eight L2s fetch (each its own spatial groups' input slices and
     // its own channel tiles' weight slices, once) and keep the cheapest.
     c.n_block = 1;
-    if (((c.variant >= 1 && c.variant <= 4) || c.variant == 6) && c.tiles_n > 1) {
+    if (((c.variant >= 1 && c.variant <= 4) || c.variant == 6 || c.variant == 7) && c.tiles_n > 1) {
       const double in_unit = 2.0 * c.batch * c.hin * c.win * (c.chunks_per_tap * 64.0) /
                              ((double)groups_m * c.nsplit);
       const double w_unit = 2.0 * c.cout_pad * c.ktot / ((double)c.tiles_n * c.nsplit);
@@ -415,7 +427,8 @@ struct Builder {
   // stride-2 layer (out2 == NULL: none).
   int add_conv(ConvParams c, size_t w_off, const Tensor* res, const Tensor* out, bool relu,
                bool want_f32, bool keep_partial, double flops, size_t w2_off = 0,
-               const Tensor* out2 = nullptr, size_t wf_off = (size_t)-1) {
+               const Tensor* out2 = nullptr, size_t wf_off = (size_t)-1,
+               size_t wf2_off = (size_t)-1) {
     Op op;
     op.fam = F_CONV;
     op.flops = flops;
@@ -428,9 +441,11 @@ struct Builder {
     c.out = nullptr; c.out_pitch = 0; c.res = nullptr; c.res_pitch = 0; c.relu = 0;
     c.out_f32 = nullptr;
     c.wt2 = nullptr; c.out2 = nullptr; c.out2_pitch = 0; c.partial2 = nullptr;
-    const bool fused = out2 != nullptr && c.variant == 4;
+    const bool fused = out2 != nullptr && (c.variant == 4 || c.variant == 7);
+    c.wt2_frag = nullptr;
     if (fused) {
       c.wt2 = d_w ? d_w + w2_off : nullptr;
+      c.wt2_frag = (d_w && wf2_off != (size_t)-1) ? d_w + wf2_off : nullptr;
       if (!partial) { c.out2 = out2->p; c.out2_pitch = out2->pitch; }
     }
     if (partial) {
@@ -486,6 +501,7 @@ struct Builder {
     g.ntaps = k * k; g.kw = k; g.chunks_per_tap = cin / g.kc;
     g.nchunks = g.ntaps * g.chunks_per_tap; g.ktot = g.nchunks * g.kc;
     g.stride = stride; g.pad = pad;
+    g.frag_ok = (res == nullptr && !want_f32) ? 1 : 0;
     const size_t w_off = reserve_w((size_t)g.cout_pad * g.ktot);
     if (pack) pack_generic(blob + blob_at, cout, cin, k, g.cout_pad, host_w.data() + w_off);
     out->h = g.hout; out->w = g.wout; out->c = cout;
@@ -498,9 +514,9 @@ struct Builder {
       size_t wf_off = (size_t)-1;
       ConvParams probe = g;
       choose_split(probe);
-      if (probe.variant == 6) {
+      if (probe.variant == 6 || probe.variant == 7) {
         wf_off = reserve_w((size_t)g.cout_pad * g.ktot);
-        if (pack) pack_frag(blob + blob_at, cout, cin, g.cout_pad, host_w.data() + wf_off);
+        if (pack) pack_frag(blob + blob_at, cout, cin, 9, g.cout_pad, host_w.data() + wf_off);
       }
       return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
                       2.0 * g.m * (double)cout * cin * k * k, 0, nullptr, wf_off);
@@ -508,8 +524,19 @@ struct Builder {
     const size_t w2_off = reserve_w((size_t)g.cout_pad * cin);
     if (pack) pack_generic(blob + proj_at, cout, cin, 1, g.cout_pad, host_w.data() + w2_off);
     proj_out->h = g.hout; proj_out->w = g.wout; proj_out->c = cout;
+    size_t wf_off = (size_t)-1, wf2_off = (size_t)-1;
+    ConvParams probe = g;
+    choose_split(probe);
+    if (probe.variant == 7) {   // fragment-ordered copies of the 3x3 weights and of the projection
+      wf_off = reserve_w((size_t)g.cout_pad * g.ktot);
+      wf2_off = reserve_w((size_t)g.cout_pad * cin);
+      if (pack) {
+        pack_frag(blob + blob_at, cout, cin, 9, g.cout_pad, host_w.data() + wf_off);
+        pack_frag(blob + proj_at, cout, cin, 1, g.cout_pad, host_w.data() + wf2_off);
+      }
+    }
     return add_conv(g, w_off, res, out, relu, want_f32, keep_partial,
-                    2.0 * g.m * (double)cout * cin * (k * k + 1), w2_off, proj_out);
+                    2.0 * g.m * (double)cout * cin * (k * k + 1), w2_off, proj_out, wf_off, wf2_off);
   }
 
   // A 64 -> 64 -> 64 channel BasicBlock without projection as ONE launch (k_block64_fused):

@@ -262,6 +262,43 @@ def test_batched_streams_match_per_stream_oracles(hs, ctx, net, net_name, layers
         s.close()
 
 
+def test_batch16_ragged_maps_on_the_large_grid_kernels(hs, ctx):
+    """Sixteen streams of 640x360 frames batched through a 416x240 network input: feature maps of
+    60x104, 30x52, 15x26 and 8x13 pixels, none a multiple of the 8 x 16 spatial tile, on grids
+    large enough (512 workgroups in stage 2) for the kernels that only run from a few frames
+    per launch on -- the tile-walking ones and the one that reads its weights as MFMA fragments
+    straight from memory.  Streams 0, 9 and 15 against their own oracle streams over two
+    frames, every stage; all sixteen finite and distinct."""
+    from paper_2402_04466_amd.harness import AppStream
+    B, T, sampled = 16, 2, (0, 9, 15)
+    fw, fh, nw, nh = 640, 360, 416, 240
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 6)
+    frames = {j: list(si.tool_scene_frames(T, fh, fw, 40 + j)) for j in range(B)}
+    s = AppStream(ctx, net=hs.HS_NET_RESNET18_CONVLSTM, frame_w=fw, frame_h=fh, net_w=nw, net_h=nh,
+                  blob=blob, palette=PAL, queue_depth=2, batch=B)
+    oracles = {j: make_oracles("resnet18_convlstm", blob, nw, nh, True, PAL) for j in sampled}
+    try:
+        for t in range(T):
+            print(f"[batch16-ragged] frame {t}", flush=True)
+            d_in = [s.upload_frame(frames[j][t]) for j in range(B)]
+            d_out = [s.new_output() for _ in range(B)]
+            assert s.submit_batch(d_in, d_out, t) == hs.HS_OK
+            rs = s.wait_batch()
+            logits = [s.fetch(rs[j])["logits"] for j in range(B)]
+            assert all(np.isfinite(l).all() for l in logits)
+            for j in range(1, B):
+                assert not np.array_equal(logits[j], logits[0])
+            for j in sampled:
+                g = s.fetch(rs[j], d_out[j])
+                a, b = oracles[j][0].process(frames[j][t]), oracles[j][1].process(frames[j][t])
+                check_frame(g, frames[j][t], a, b, threshold=0.5, alpha=0.5, palette=PAL,
+                            fp32_input=False, tag=f"batch16-ragged/stream{j}/frame{t}")
+                gh, gc = s.state(rs[j], stream=j)
+                assert rms_rel(gh, a["h"]) <= TOL_STATE_RMS and rms_rel(gc, a["c"]) <= TOL_STATE_RMS
+    finally:
+        s.close()
+
+
 def test_config5_full_size_batch12_sampled_streams(hs, ctx):
     """The saturation configuration as bench.py runs it: 12 streams of 1920x1080 frames batched
     through one pass of the big network (854x480 input, HIP-graph launch, the large-grid kernel
