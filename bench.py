@@ -14,7 +14,8 @@ ONE JSON line:
   * `configs`: short runs of the other configurations -- one stream; five unpartitioned
     applications at 60 frames per second; six applications unpartitioned, on six CU partitions
     with inference and overlay on separate CU sets, on six partitions with one queue each, and
-    re-shaped into three applications of two streams on three partitions -- each with frames/s
+    re-shaped into three applications of two streams on three partitions and two applications
+    of three streams on two partitions -- each with frames/s
     and the latency determinism metrics (paper Section V-A); the six-stream arrangements carry
     their maximum and median against the unpartitioned run's and the Mann-Whitney z of the two
     latency samples (paper, appendix "Additional Evaluation");
@@ -110,6 +111,9 @@ def parse():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="first run the library's plain copy kernel 4 times over this many MiB "
                          "(reference dispatches for scaling rocprofv3 byte counters)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="default run without the configs array: the headline measurement alone, "
+                         "unchanged (the command the kernel-trace profile of the headline uses)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=16,
                     help="frames of the all-core CPU oracle sample (one more, untimed, first)")
@@ -618,9 +622,11 @@ def main():
             ("config 4 re-shaped: 3 applications x 2 streams batched, on 3 CU partitions of 80 CUs "
              "(at most four hardware queues in use)",
              dict(streams=3, batch=2, first_seed=7, steps=120, partition="equal-shared")),
+            ("config 4 re-shaped: 2 applications x 3 streams batched, on 2 CU partitions of 120 CUs",
+             dict(streams=2, batch=3, first_seed=7, steps=120, partition="equal-shared")),
         ]
-        configs, ref = [], None
-        for name, kw in plan:
+        configs, ref = ([], None) if not args.headline_only else (None, None)
+        for name, kw in (plan if not args.headline_only else []):
             note(name)
             res = measure(variant(**kw), env, want_roofline=kw.get("streams") == 1, note=note)
             torch.cuda.empty_cache()
