@@ -210,10 +210,11 @@ __device__ __forceinline__ void store_quad(const ConvParams& p, int m, int n, fl
 // (v_permlane32_swap: lanes 32..63 of the first operand <-> lanes 0..31 of the second), so that
 // each holds 8 consecutive channels per pair and stores 16 bytes at a time instead of 8.
 // For fp16 outputs whose channel count is a multiple of 32.  Every lane of the wavefront must
-// call it (the swap needs both lanes of a pair); `valid` gates the store.
-__device__ __forceinline__ void store_octets(const ConvParams& p, bool valid, int m, int cbase,
-                                             int h, const floatx16& acc, const half4 (&res)[4],
-                                             bool has_res) {
+// call it (the swap needs both lanes of a pair); `valid` gates the store.  out / pitch / relu:
+// the destination tensor (the layer's output, or the projection's).
+__device__ __forceinline__ void store_octets_to(f16* out, int pitch, bool relu, bool valid, int m,
+                                                int cbase, int h, const floatx16& acc,
+                                                const half4 (&res)[4], bool has_res) {
   uint32_t q[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -222,7 +223,7 @@ __device__ __forceinline__ void store_octets(const ConvParams& p, bool valid, in
 #pragma unroll
       for (int j = 0; j < 4; ++j) v[j] += (float)res[i][j];
     }
-    if (p.relu) {
+    if (relu) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.0f);
     }
@@ -242,13 +243,18 @@ __device__ __forceinline__ void store_octets(const ConvParams& p, bool valid, in
       q[2 * pr + 1][w] = sw[1];
     }
   if (valid) {
-    f16* dst = p.out + (size_t)m * p.out_pitch + cbase + h * 8;
+    f16* dst = out + (size_t)m * pitch + cbase + h * 8;
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
       const u32x4 o = {q[2 * pr][0], q[2 * pr][1], q[2 * pr + 1][0], q[2 * pr + 1][1]};
       *reinterpret_cast<u32x4*>(dst + 16 * pr) = o;
     }
   }
+}
+__device__ __forceinline__ void store_octets(const ConvParams& p, bool valid, int m, int cbase,
+                                             int h, const floatx16& acc, const half4 (&res)[4],
+                                             bool has_res) {
+  store_octets_to(p.out, p.out_pitch, p.relu != 0, valid, m, cbase, h, acc, res, has_res);
 }
 
 template <int KC, int DEPTH>
@@ -1526,15 +1532,9 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3s2_dira(ConvParams p) {
           // fp16 outputs with whole 128-channel tiles (the host selects this kernel only then)
           const half4 none[4] = {};
           store_octets(p, valid, m, n0 + wave * 32, h, acc[g], none, false);
-          if (has_proj && valid) {                 // projection: no residual, no ReLU
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              half4 o;
-#pragma unroll
-              for (int j = 0; j < 4; ++j) o[j] = (f16)acc2[g][4 * i + j];
-              *reinterpret_cast<half4*>(p.out2 + (size_t)m * p.out2_pitch + n_base + 8 * i) = o;
-            }
-          }
+          if (has_proj)                            // projection: no residual, no ReLU
+            store_octets_to(p.out2, p.out2_pitch, false, valid, m, n0 + wave * 32, h, acc2[g], none,
+                            false);
         }
       }
       acc[0] = acc[1] = zero16;
