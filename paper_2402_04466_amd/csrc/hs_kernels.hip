@@ -1697,10 +1697,9 @@ KernelDesc describe(const LstmEpilogueParams& p) {
 // contiguous bytes starting at input pixel 2*cx of row 2*cy + ky: MFMA pixel operands are read
 // straight from the patch, no im2col copy.
 // Wavefront (wm, wn): convolution rows 8*wm .. 8*wm+8 (row 8 is computed by both halves, it
-// feeds pooled rows 3 and 4), channels 32*wn .. +31: nine accumulators.  Pooling: ReLU, zero outside the convolution output (every pooling
-// window holds a real pixel and ReLU outputs are >= 0, so zero stands for "absent"), maximum
-// over three accumulators (rows), then over lanes r, r+1, r+2 (columns, two DPP wavefront
-// shifts); even lanes store.
+// feeds pooled rows 3 and 4), channels 32*wn .. +31: nine accumulators.  Pooling: maximum over
+// three accumulators (rows), then over lanes r, r+1, r+2 (columns, two DPP wavefront shifts),
+// ReLU last; even lanes store.
 // Rounding to fp16 after the maximum equals the maximum of the rounded values.
 // =============================================================================================
 // value of lane + 1 (DPP whole-wavefront shift; lane 63 keeps its own)
@@ -1789,38 +1788,38 @@ __global__ __launch_bounds__(256, 2) void k_stem_pool(StemPoolParams p) {
     }
   }
 
-  // ---- ReLU, zero outside the convolution output, pool
+  // ---- pool, ReLU.  max and ReLU commute, so ReLU comes last; a pooling window always holds
+  // its centre row (convolution row 2 * py exists whenever pooled row py does), rows outside the
+  // convolution output are skipped (the same for the whole wavefront), columns outside it count
+  // as 0, which cannot change ReLU(max).  Then the lane pair (r, r + 32) exchanges quads and
+  // stores 16 bytes per lane (store_octets_to); every lane takes part in the exchange.
   const int cx = cx0 + r;
   const bool col_ok = cx >= 0 && cx < p.wc;
-#pragma unroll
-  for (int j = 0; j < 9; ++j) {
-    const int cy = cy0 + 8 * wm + j;
-    const bool ok = col_ok && cy >= 0 && cy < p.hc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[j][i] = ok ? fmaxf(acc[j][i], 0.0f) : 0.0f;
-  }
   const int q = q0 + (r >> 1);
   const bool writer = (r & 1) == 0 && r <= 28 && q < p.wp;
 #pragma unroll
   for (int pl = 0; pl < 4; ++pl) {
     const int py = p0 + 4 * wm + pl;
-    float v[16];
+    const int cy_top = cy0 + 8 * wm + 2 * pl;             // rows cy_top, cy_top + 1 (centre), cy_top + 2
+    const bool top_ok = cy_top >= 0, bot_ok = cy_top + 2 < p.hc;
+    floatx16 v = acc[2 * pl + 1];
+    if (top_ok) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = fmaxf(v[i], acc[2 * pl][i]);
+    }
+    if (bot_ok) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = fmaxf(v[i], acc[2 * pl + 2][i]);
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float m = fmaxf(fmaxf(acc[2 * pl][i], acc[2 * pl + 1][i]), acc[2 * pl + 2][i]);
-      const float m2 = fmaxf(m, lane_plus_1(m));     // columns r, r+1
-      v[i] = fmaxf(m2, lane_plus_1(m2));             // columns r .. r+2
+      const float m = col_ok ? v[i] : 0.0f;
+      const float m2 = fmaxf(m, lane_plus_1(m));       // columns r, r+1
+      v[i] = fmaxf(fmaxf(m2, lane_plus_1(m2)), 0.0f);  // columns r .. r+2, ReLU
     }
-    if (writer && py < p.hp) {
-      f16* dst = p.out + (((size_t)img * p.hp + py) * p.wp + q) * 64 + 32 * wn + 4 * h;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        half4 o;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) o[c] = (f16)v[4 * i + c];
-        *reinterpret_cast<half4*>(dst + 8 * i) = o;
-      }
-    }
+    const half4 none[4] = {};
+    store_octets_to(p.out, 64, false, writer && py < p.hp, (img * p.hp + py) * p.wp + q, 32 * wn, h, v,
+                    none, false);
   }
 }
 
