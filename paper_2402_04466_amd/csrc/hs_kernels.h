@@ -128,8 +128,8 @@ KernelDesc describe(const LstmEpilogueParams& p);
 
 // Stem of the ResNet-style backbone: 7x7 stride-2 pad-3 convolution 3 -> 64, ReLU, 3x3 stride-2
 // pad-1 max-pool, fused.  in: padded 4-channel fp16 images (pad 3 on the top and left, zeros),
-// hin x win pixels each with win even; wt: [64][224] halves, k = (ky*8 + px)*4 + ch, zero where
-// px == 7 or ch == 3; out: pooled pixel-major [batch][hp][wp][64].
+// hin x win pixels each with win even; wt: the [64][224] matrix, k = (ky*8 + px)*4 + ch, zero where
+// px == 7 or ch == 3, in MFMA fragment order: [channel half][ky][K-step of 16][lane][8 halves]; out: pooled pixel-major [batch][hp][wp][64].
 struct StemPoolParams {
   const f16* in; const f16* wt; f16* out;
   int hin, win;          // padded image

@@ -1691,8 +1691,8 @@ KernelDesc describe(const LstmEpilogueParams& p) {
 //
 // A workgroup produces 8 x 15 pooled pixels, i.e. the 17 x 31 convolution outputs under them
 // (one row/column of overlap with the neighbouring tiles), as 17 row fragments of 32 pixels.
-// The whole input patch (39 rows x 70 padded 4-channel pixels) and the whole weight matrix
-// (64 x 224 halves, k = (ky*8 + px)*4 + ch) sit in LDS.  Because the image is stored with 4
+// The whole input patch (39 rows x 70 padded 4-channel pixels) sits in LDS; the weight matrix
+// (64 x 224 halves, k = (ky*8 + px)*4 + ch) is held as MFMA fragments in registers.  Because the image is stored with 4
 // channels per pixel, the 32 K-values of kernel row ky for convolution pixel cx are the 64
 // contiguous bytes starting at input pixel 2*cx of row 2*cy + ky: MFMA pixel operands are read
 // straight from the patch, no im2col copy.
@@ -1710,11 +1710,8 @@ __device__ __forceinline__ float lane_plus_1(float x) {
 
 __global__ __launch_bounds__(256, 2) void k_stem_pool(StemPoolParams p) {
   constexpr int PROWS = 39, PVEC = 35, PROW_H = PVEC * 8;      // patch rows, vectors, halves per row
-  constexpr int WPITCH = 224 + 8;                              // halves per weight row in LDS
   constexpr int NPV = PROWS * PVEC, NPL = (NPV + 255) / 256;   // patch vectors, per thread
-  constexpr int NWL = 64 * 28 / 256;                           // weight vectors per thread
   __shared__ __align__(16) f16 s_patch[PROWS * PROW_H];
-  __shared__ __align__(16) f16 s_w[64 * WPITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
   const int tile = (int)(blockIdx.x & 7u) * p.tiles_per_xcd + (int)(blockIdx.x >> 3);
@@ -1726,7 +1723,7 @@ __global__ __launch_bounds__(256, 2) void k_stem_pool(StemPoolParams p) {
   const int iy0 = 2 * cy0, ix0 = 2 * cx0;           // first pixel of the padded image (may be < 0)
 
   // ---- fill LDS: unconditional loads from clamped addresses, zeros where out of the image
-  u32x4 st_p[NPL], st_w[NWL];
+  u32x4 st_p[NPL];
   bool inb[NPL];
 #pragma unroll
   for (int i = 0; i < NPL; ++i) {
@@ -1737,10 +1734,16 @@ __global__ __launch_bounds__(256, 2) void k_stem_pool(StemPoolParams p) {
     const f16* src = inb[i] ? p.in + (((size_t)img * p.hin + y) * p.win + x) * 4 : p.in;
     st_p[i] = *reinterpret_cast<const u32x4*>(src);
   }
+  // The wavefront's 14 weight fragments come straight from memory (fragment order, one
+  // contiguous 1 KB block per wavefront load) and stay in registers.
+  const int wm = wave & 1, wn = wave >> 1;
+  half8 a[7][2];
+  {
+    const half8* wfr = reinterpret_cast<const half8*>(p.wt) + (size_t)wn * 14 * 64 + lane;
 #pragma unroll
-  for (int i = 0; i < NWL; ++i) {
-    const int v = tid + 256 * i;
-    st_w[i] = *reinterpret_cast<const u32x4*>(p.wt + (size_t)v * 8);   // rows are 28 vectors, dense
+    for (int ky = 0; ky < 7; ++ky)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) a[ky][s] = wfr[(ky * 2 + s) * 64];
   }
 #pragma unroll
   for (int i = 0; i < NPL; ++i) {
@@ -1748,30 +1751,18 @@ __global__ __launch_bounds__(256, 2) void k_stem_pool(StemPoolParams p) {
     const u32x4 zero = {0u, 0u, 0u, 0u};
     if (v < NPV) *reinterpret_cast<u32x4*>(&s_patch[v * 8]) = inb[i] ? st_p[i] : zero;
   }
-#pragma unroll
-  for (int i = 0; i < NWL; ++i) {
-    const int v = tid + 256 * i, row = v / 28, kv = v - row * 28;
-    *reinterpret_cast<u32x4*>(&s_w[row * WPITCH + kv * 8]) = st_w[i];
-  }
   __syncthreads();
 
   // ---- 14 K-steps of 16 (two per kernel row), nine row fragments each
-  const int wm = wave & 1, wn = wave >> 1;
   floatx16 acc[9];
 #pragma unroll
   for (int j = 0; j < 9; ++j)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[j][i] = 0.0f;
-  const f16* fw = &s_w[(32 * wn + r) * WPITCH + h * 8];
   const f16* fp = &s_patch[(16 * wm) * PROW_H + r * 8 + h * 8];   // patch row 2*(8*wm + j) + ky
-  // The wavefront's 14 weight fragments stay in registers.  Patch row rho serves every
-  // (convolution row j, kernel row ky) with 2*j + ky == rho, so each patch fragment is read
-  // once: 46 LDS reads feed the 126 MFMAs.  Per accumulator the K order stays ky = 0..6.
-  half8 a[7][2];
-#pragma unroll
-  for (int ky = 0; ky < 7; ++ky)
-#pragma unroll
-    for (int s = 0; s < 2; ++s) a[ky][s] = *reinterpret_cast<const half8*>(fw + ky * 32 + s * 16);
+  // Patch row rho serves every (convolution row j, kernel row ky) with 2*j + ky == rho, so each
+  // patch fragment is read once: 46 LDS reads feed the 126 MFMAs.  Per accumulator the K order
+  // stays ky = 0..6.
 #pragma unroll
   for (int rho = 0; rho < 23; ++rho) {
     if (rho % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // bounds how far reads are hoisted

@@ -279,6 +279,23 @@ static void pack_rowtap(const float* w, int cout, int k, int chunk_px, int cout_
               (f16)w[(((size_t)n * 3 + ch) * k + ky) * k + px];
 }
 
+// The 7x7 stem's weights in MFMA fragment order for k_stem_pool: block ((wn * 7 + ky) * 2 + s) of
+// 64 lanes x 8 halves; lane (h, r) holds channel 32 * wn + r, k = ky * 32 + s * 16 + h * 8 .. + 7 of
+// the row-tap layout (k = (ky * 8 + px) * 4 + ch, zero where px == 7 or ch == 3).
+static void pack_stem_frag(const float* w, f16* dst) {
+  std::vector<f16> rows((size_t)64 * 224);
+  pack_rowtap(w, 64, 7, 8, 64, rows.data());
+  for (int wn = 0; wn < 2; ++wn)
+    for (int ky = 0; ky < 7; ++ky)
+      for (int s = 0; s < 2; ++s)
+        for (int lane = 0; lane < 64; ++lane) {
+          const int h = lane >> 5, r = lane & 31;
+          const f16* src = rows.data() + (size_t)(32 * wn + r) * 224 + ky * 32 + s * 16 + h * 8;
+          f16* out = dst + ((size_t)((wn * 7 + ky) * 2 + s) * 64 + lane) * 8;
+          for (int e = 0; e < 8; ++e) out[e] = src[e];
+        }
+}
+
 // ---- plan builder ------------------------------------------------------------------------------
 static inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -633,9 +650,10 @@ struct Builder {
 
     size_t at = 0;
     {
-      // stem convolution and max-pool in one kernel; weights packed as row taps of 8 pixels
+      // stem convolution and max-pool in one kernel; weights packed as MFMA fragments of row
+      // taps of 8 pixels
       const size_t w_off = reserve_w((size_t)64 * 224);
-      if (pack) pack_rowtap(blob + at, 64, 7, 8, 64, host_w.data() + w_off);
+      if (pack) pack_stem_frag(blob + at, host_w.data() + w_off);
       Op op;
       op.fam = F_STEM;
       StemPoolParams& sp = op.stem;
