@@ -1640,7 +1640,7 @@ KernelDesc describe(const SplitKEpilogueParams& p) {
 // ConvLSTM epilogue + 1x1 head: one workgroup per pixel, one thread per hidden channel
 // (hid == 256).  Gates and state update in fp32 (c kept in fp32, h stored fp16); the head's
 // eight logits of the pixel are the workgroup-wide sums of w[k][j] * h[j] over the stored
-// (fp16) h: wavefront butterflies, then the four wavefront sums in order.
+// (fp16) h: a wavefront butterfly, then the four wavefront sums in order.
 // logits: planar per image, logits[(image*8 + k)*img_m + pixel in image].
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_lstm_epilogue(LstmEpilogueParams p) {
@@ -1664,14 +1664,31 @@ __global__ __launch_bounds__(256) void k_lstm_epilogue(LstmEpilogueParams p) {
   float v[8];
 #pragma unroll
   for (int k = 0; k < 8; ++k) v[k] = hv * (float)p.w_head[k * p.hid + j];
+  // Wavefront sums of the eight products by a halving butterfly: at offset 32 a lane keeps four
+  // of the eight (k / 4 == its bit 5) and hands the other four to its partner in the same
+  // exchange, at 16 two, at 8 one; offsets 4, 2, 1 finish that one.  Ten exchanges instead of
+  // 48, and every sum adds the same pairs level by level as the full butterfly would: lanes
+  // 8 * k .. 8 * k + 7 end with the sum of product k.
+  float a4[4], a2[2], a1;
+  {
+    const bool up = (lane & 32) != 0;
 #pragma unroll
-  for (int k = 0; k < 8; ++k)
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v[k] += __shfl_xor(v[k], off, 64);
-  if (lane == 0) {
-#pragma unroll
-    for (int k = 0; k < 8; ++k) s_part[wave][k] = v[k];
+    for (int i = 0; i < 4; ++i)
+      a4[i] = (up ? v[4 + i] : v[i]) + __shfl_xor(up ? v[i] : v[4 + i], 32, 64);
   }
+  {
+    const bool up = (lane & 16) != 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      a2[i] = (up ? a4[2 + i] : a4[i]) + __shfl_xor(up ? a4[i] : a4[2 + i], 16, 64);
+  }
+  {
+    const bool up = (lane & 8) != 0;
+    a1 = (up ? a2[1] : a2[0]) + __shfl_xor(up ? a2[0] : a2[1], 8, 64);
+  }
+#pragma unroll
+  for (int off = 4; off >= 1; off >>= 1) a1 += __shfl_xor(a1, off, 64);
+  if ((lane & 7) == 0) s_part[wave][lane >> 3] = a1;
   __syncthreads();
   if (j < 8) {
     const float sum = ((s_part[0][j] + s_part[1][j]) + s_part[2][j]) + s_part[3][j];
