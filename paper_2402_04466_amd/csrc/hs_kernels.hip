@@ -256,6 +256,24 @@ __device__ __forceinline__ void store_octets(const ConvParams& p, bool valid, in
                                              bool has_res) {
   store_octets_to(p.out, p.out_pitch, p.relu != 0, valid, m, cbase, h, acc, res, has_res);
 }
+// The residual of a pixel's 32 channels, fetched the way store_octets stores them: lane half h
+// loads channels cbase + 8h .. +7 and cbase + 16 + 8h .. +7 (two 16-byte loads, o[0] and o[1],
+// from pixel_base + cbase + 8 * h and 16 halves further); the same lane exchange (it is its own
+// inverse) turns them into the quads res[i] = channels cbase + 4h + 8i .. +3 that the
+// accumulators are laid out in.  Every lane of the wavefront must call it.
+__device__ __forceinline__ void res_octets_to_quads(const u32x4 (&o)[2], half4 (&res)[4]) {
+  uint32_t q[4][2] = {{o[0][0], o[0][1]}, {o[0][2], o[0][3]}, {o[1][0], o[1][1]}, {o[1][2], o[1][3]}};
+#pragma unroll
+  for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      const auto sw = __builtin_amdgcn_permlane32_swap(q[2 * pr][w], q[2 * pr + 1][w], false, false);
+      q[2 * pr][w] = sw[0];
+      q[2 * pr + 1][w] = sw[1];
+    }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) res[i] = __builtin_bit_cast(half4, make_uint2(q[i][0], q[i][1]));
+}
 
 template <int KC, int DEPTH>
 __global__ __launch_bounds__(256) void k_conv_mfma(ConvParams p) {
@@ -899,16 +917,16 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_c64_walk(ConvParams p) {
     if (tm + 1 < tm_end) HS_FETCH_PATCH(tm + 1)
     // residual of this tile: fetched now, used after the MFMAs (clamped addresses, unconditional)
     const int oy = y0 + 4 * wm + (r >> 3);
-    half4 res_pre[2][4];
+    u32x4 res_raw[2][2];      // two 16-byte pieces per pixel (res_octets_to_quads)
     if (p.res) {
       const int oy_c = min(oy, p.hout - 1);
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
         const int ox_c = min(x0 + 8 * g + (r & 7), p.wout - 1);
-        const f16* rp = p.res + (size_t)(img * p.img_m + oy_c * p.wout + ox_c) * p.res_pitch;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          res_pre[g][i] = *reinterpret_cast<const half4*>(rp + min(n_base + 8 * i, p.cout - 4));
+        const f16* rp = p.res + (size_t)(img * p.img_m + oy_c * p.wout + ox_c) * p.res_pitch +
+                        n0 + wn * 32 + h * 8;
+        res_raw[g][0] = *reinterpret_cast<const u32x4*>(rp);
+        res_raw[g][1] = *reinterpret_cast<const u32x4*>(rp + 16);
       }
     }
 
@@ -932,8 +950,10 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_c64_walk(ConvParams p) {
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int ox = x0 + 8 * g + (r & 7);
+      half4 res_q[4] = {};
+      if (p.res) res_octets_to_quads(res_raw[g], res_q);
       store_octets(p, oy < p.hout && ox < p.wout, img * p.img_m + oy * p.wout + ox, n0 + wn * 32, h,
-                   acc[g], res_pre[g], p.res != nullptr);
+                   acc[g], res_q, p.res != nullptr);
     }
   }
 #undef HS_FETCH_PATCH
@@ -1249,29 +1269,38 @@ __global__ __launch_bounds__(256, 3) void k_conv3x3_dira(ConvParams p) {
     pb ^= 1;
   }
   // residual of the block's second convolution: fetched while the last chunk is computed
+  // (with whole 64-channel tiles of fp16 output as two 16-byte pieces per pixel, see
+  // res_octets_to_quads; otherwise as the four quads the accumulators are laid out in)
   const bool res_here = p.res != nullptr && !p.use_partial;
+  const bool wide_out = !p.use_partial && p.out_f32 == nullptr && (p.cout & 63) == 0;
   half4 res_pre[2][4];
+  u32x4 res_raw[2][2];
   if (res_here) {
     const int oy_c = min(oy, p.hout - 1);
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int ox_c = min(x0 + 8 * g + (r & 7), p.wout - 1);
       const f16* rp = p.res + (size_t)(img * p.img_m + oy_c * p.wout + ox_c) * p.res_pitch;
+      if (wide_out) {
+        res_raw[g][0] = *reinterpret_cast<const u32x4*>(rp + n0 + wn * 32 + h * 8);
+        res_raw[g][1] = *reinterpret_cast<const u32x4*>(rp + n0 + wn * 32 + h * 8 + 16);
+      } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        res_pre[g][i] = *reinterpret_cast<const half4*>(rp + min(n_base + 8 * i, p.cout - 4));
+        for (int i = 0; i < 4; ++i)
+          res_pre[g][i] = *reinterpret_cast<const half4*>(rp + min(n_base + 8 * i, p.cout - 4));
+      }
     }
   }
   HS_CHUNK(true)
 
   // ---- epilogue: accumulator quad i of group g = channels n_base + 8*i .. +3 of pixel (oy, ox_g)
-  const bool wide_out = !p.use_partial && p.out_f32 == nullptr && (p.cout & 63) == 0;
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
     const int ox = x0 + 8 * g + (r & 7);
     const bool valid = oy < p.hout && ox < p.wout;
     const int m = img * p.img_m + oy * p.wout + ox;
-    if (wide_out) {                       // every lane takes part in the exchange
+    if (wide_out) {                       // every lane takes part in the exchanges
+      if (res_here) res_octets_to_quads(res_raw[g], res_pre[g]);
       store_octets(p, valid, m, n0 + wn * 32, h, acc[g], res_pre[g], res_here);
     } else if (valid) {
       if (p.use_partial) {
