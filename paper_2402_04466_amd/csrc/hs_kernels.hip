@@ -804,7 +804,7 @@ __global__ __launch_bounds__(256, OCC) void k_conv3x3_halo(ConvParams p) {
 // =============================================================================================
 // 3x3 stride-1 layers with 64 input channels (one Cin chunk) on grids several times the device:
 // the nine weight tiles of a workgroup's channel tile never change while it walks its spatial
-// tiles, so they are made resident once -- taps 0..4 in LDS, taps 5..8 as MFMA fragments in
+// tiles, so they are made resident once -- taps 0..2 in LDS, taps 3..8 as MFMA fragments in
 // registers (all nine in LDS would leave one workgroup per CU, all nine in registers none of
 // the registers).  A tile then costs one patch hand-over (two barriers) and 72 MFMAs per
 // wavefront with no weight traffic and no barrier between the taps.  Same tile, wavefront
@@ -817,7 +817,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_c64_walk(ConvParams p) {
   constexpr int RP = (IPW * PITCH * 2 + ((128 - (IPW * PITCH * 2) % 256 + 256) % 256)) / 2;
   static_assert((RP * 2) % 256 == 128, "plane row pitch must be 128 mod 256 bytes");
   constexpr int PV = NPIX * 8, PL = (PV + 255) / 256;
-  constexpr int LT = 5;                       // taps whose weights stay in LDS (the rest: registers)
+  constexpr int LT = 3;                       // taps whose weights stay in LDS (the rest: registers)
   constexpr int WT = 64 * PITCH;              // halves of one weight tile in LDS
   static_assert(IPH * RP >= 2 * WT, "the patch buffer stages two weight tiles in the prologue");
   __shared__ __align__(16) f16 s_patch[IPH * RP];
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_c64_walk(ConvParams p) {
   }
   HS_FETCH_PATCH(tm_begin)
 
-  // ---- weights: taps 0..4 into their LDS tiles; taps 5..8, two at a time, through the (still
+  // ---- weights: taps 0..2 into their LDS tiles; taps 3..8, two at a time, through the (still
   // unused) patch buffer into fragment registers
   half8 a_keep[9 - LT][4];
   {
