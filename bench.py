@@ -19,7 +19,7 @@ ONE JSON line:
     and the latency determinism metrics (paper Section V-A); the six-stream arrangements carry
     their maximum and median against the unpartitioned run's and the Mann-Whitney z of the two
     latency samples (paper, appendix "Additional Evaluation");
-  * `cpu_baseline`: the CPU oracle timed on this machine's host cores.
+  * `cpu_baseline`: the CPU oracle timed on the host's cores.
 With workload flags (--streams, --batch, --partition, ...) it measures that one workload.
 """
 from __future__ import annotations
@@ -499,7 +499,7 @@ def measure(args, env: Env, want_roofline: bool = True, note=lambda s: None) -> 
 
 
 def cpu_baseline(args, env: Env) -> dict:
-    """The CPU oracle as it stands on this machine's host cores: all four stages of one 1080p
+    """The CPU oracle as it stands on the host's cores: all four stages of one 1080p
     stream, with every core the BLAS library takes, and on a single thread."""
     import oracle
     si = env.si

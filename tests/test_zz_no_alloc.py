@@ -63,7 +63,7 @@ def test_static_scratch_submit_matches_workspace_submit_twice_in_a_row(hs):
                 try:
                     st = hs.hs_submit_frame_static_scratch(s_big.app, d_in.data_ptr(),
                                                            outs[1].data_ptr(), 8)
-                    # the first frame may already have finished on a fast box: then it is taken
+                    # the first frame may already have finished on a fast device: then it is taken
                     assert st == hs.HS_OK
                     second = True
                 except hs.HsError as e:
