@@ -116,6 +116,17 @@ def test_resnet_convlstm_reduced_size_with_state(hs, ctx):
                 check_state=True, tag="resnet-small")
 
 
+def test_resnet_convlstm_odd_map_sizes(hs, ctx):
+    """324x180 -> 162x90: every map of the network has an odd side (45 x 81 convolution outputs
+    under the pool, then 23 x 41, 12 x 21, 6 x 11 and 3 x 6 pixels), so the pooling window that
+    hangs over the bottom and right edge, the stride-2 tiles' last row and column and the
+    ragged 8 x 8 / 8 x 16 tiles are all met; two frames, every stage."""
+    frames = list(si.tool_scene_frames(2, 180, 324, 33))
+    blob = si.he_normal_blob(si.RESNET18_CONVLSTM_LAYERS, 2)
+    _run_stream(hs, ctx, net=hs.HS_NET_RESNET18_CONVLSTM, net_name="resnet18_convlstm",
+                frames=frames, net_w=162, net_h=90, blob=blob, fp32_input=False, tag="resnet-odd")
+
+
 def test_config2_full_size_three_frames(hs, ctx):
     """1920x1080 -> 854x480, full network, 3 frames of the seed-1 scene with state."""
     frames = list(si.tool_scene_frames(3, 1080, 1920, 1))
