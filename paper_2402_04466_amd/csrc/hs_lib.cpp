@@ -399,9 +399,9 @@ struct Builder {
       const int wgs = c.tiles_m * c.tiles_n * c.nsplit;
       if (wgs > 1536) c.tiles_per_wg = (wgs + 511) / 512;
     }
-    if (c.variant == 7) {   // two workgroups per CU are resident: at most two rounds
+    if (c.variant == 7) {   // two workgroups per CU are resident: beyond two rounds, walk in one
       const int wgs = c.tiles_m * c.tiles_n * c.nsplit;
-      if (wgs > 1024) c.tiles_per_wg = (wgs + 1023) / 1024;
+      if (wgs > 1024) c.tiles_per_wg = (wgs + 511) / 512;
     }
     const int groups_m = (c.tiles_m + c.tiles_per_wg - 1) / c.tiles_per_wg;
     c.tiles_per_xcd = (groups_m * c.tiles_n * c.nsplit + 7) / 8;
